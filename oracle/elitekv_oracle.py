@@ -1,0 +1,199 @@
+"""CPU oracle for the EliteKV decode hot path (RoPElite + joint low-rank decomposition).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, float64 statement of
+what the path computes.  Only the tests, the smoke check and the benchmark's
+`cpu_baseline` leg may import it; the product (the HIP library and its Python
+binding) never does, and this file imports nothing from the product.
+
+What is computed, and where the paper defines it:
+
+* Cache append (Section 3.1, the expression for what enters the KV cache at
+  step t of a RoPElite model; Section 3.2 "Joint Low-Rank Decomposition",
+  c = x A^{kv}; Section 3.2's definition of W^k_{e,h}, the d x 2r block of the
+  key projection that serves head h's elite chunks): the elite chunks of each
+  head's key are stored rotated by R(t * theta_i); the rest of the key and the
+  whole value are represented by the shared latent c_t = x_t W_dkv.
+
+* Decode attention (Section 3.1, the RoPElite score equation; Section 2.1, the
+  softmax attention equations; Section 3.2, B^{kv} = [B^k_J, B^v_J]): given
+  the four weight blocks and the index sets, the method's result IS textbook
+  softmax attention over the reconstructed keys
+      k_j = [ rotated elite dims | c_j W_uk,h ]   and values   v_j = c_j W_uv,h.
+  Absorbing W_uk into the query, online softmax, split-K and accumulating in
+  latent space are exact algebraic rearrangements of this, so the oracle writes
+  out the definition itself: reconstruct, then plain attention.  No blocking,
+  no absorption, no running maximum.
+
+Readings of points the paper leaves open (all listed again in the design notes):
+  - theta_i = base^(-2i/d_h) (RoFormer's frequencies; the paper only cites it);
+  - chunks are ADJACENT dims [2i, 2i+1] (Section 2.2, the definition of I);
+  - R(a) acts on a row pair as (u, v) -> (u cos a - v sin a, u sin a + v cos a);
+  - positions are explicit integers, no implicit origin;
+  - the softmax scale stays 1/sqrt(d_h) with the original d_h (Section 2.1);
+  - column order inside a head: elite slots in the caller's I_h order, each as
+    (lane 0, lane 1); non-elite dims in ascending original index;
+  - a batch row with seq_len 0 gives a zero output row.
+
+Pins (tests/test_oracle_pins.py): equality with ordinary RoPE attention when
+r = d_h/2 and the factors are exact; equality with the RoPElite score equation
+evaluated in its relative form from full keys for any r; the r = 0 case;
+R(0) = identity; shift invariance; norm preservation; the closed forms for one
+cached token and for q = 0; permutation invariances; triple-loop brute force;
+hand-computed rotations; the cache-size and parameter-count formulas.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+def rope_theta(head_dim: int, rope_base: float) -> np.ndarray:
+    """theta_i = base^(-2i/d_h), i = 0 .. d_h/2 - 1 (Section 2.2; RoFormer's choice)."""
+    i = np.arange(head_dim // 2, dtype=F64)
+    return np.power(F64(rope_base), -2.0 * i / F64(head_dim))
+
+
+def rotate_pairs(pairs: np.ndarray, alpha: np.ndarray) -> np.ndarray:
+    """Apply the 2-D rotation R(alpha) to row pairs (Section 2.2, eq. 1a).
+
+    pairs: [..., 2], alpha: [...] ->  (u cos a - v sin a, u sin a + v cos a).
+    """
+    u = pairs[..., 0]
+    v = pairs[..., 1]
+    ca = np.cos(alpha)
+    sa = np.sin(alpha)
+    return np.stack([u * ca - v * sa, u * sa + v * ca], axis=-1)
+
+
+def nonelite_dims(elite_idx_h: np.ndarray, head_dim: int) -> np.ndarray:
+    """Original head dims that are NOT in head h's elite chunks, ascending."""
+    elite = set()
+    for i in np.asarray(elite_idx_h).tolist():
+        elite.add(2 * i)
+        elite.add(2 * i + 1)
+    return np.array([t for t in range(head_dim) if t not in elite], dtype=np.int64)
+
+
+def elite_dims(elite_idx_h: np.ndarray) -> np.ndarray:
+    """Original head dims of head h's elite chunks in slot order: (2i, 2i+1) per slot."""
+    out = []
+    for i in np.asarray(elite_idx_h).tolist():
+        out += [2 * i, 2 * i + 1]
+    return np.array(out, dtype=np.int64)
+
+
+def cache_row_elems(n_heads: int, r: int, d_c: int) -> int:
+    """KV-cache elements per token per layer: 2 r n_h + d_c (Section 3.2, J-LRD)."""
+    return 2 * r * n_heads + d_c
+
+
+def param_count(d_model: int, n_heads: int, head_dim: int, r: int, d_c: int) -> int:
+    """Parameters of RoPElite + J-LRD: 2 r n_h d + d_c (d + 2 d_h n_h - 2 r n_h) (Section 3.2)."""
+    return 2 * r * n_heads * d_model + d_c * (d_model + 2 * head_dim * n_heads - 2 * r * n_heads)
+
+
+def append(x, pos, W_ke, W_dkv, elite_idx, head_dim: int, rope_base: float):
+    """Cache rows for T tokens.
+
+    x [T, d]; pos [T] ints; W_ke [d, n_h, 2r]; W_dkv [d, d_c]; elite_idx [n_h, r].
+    Returns (ke [T, n_h, 2r] rotated elite keys, c [T, d_c] latent), float64.
+    """
+    x = np.asarray(x, dtype=F64)
+    W_ke = np.asarray(W_ke, dtype=F64)
+    W_dkv = np.asarray(W_dkv, dtype=F64)
+    elite_idx = np.asarray(elite_idx)
+    pos = np.asarray(pos)
+    T, d = x.shape
+    n_h, r = elite_idx.shape
+    theta = rope_theta(head_dim, rope_base)
+
+    c = x @ W_dkv                                            # c_t = x_t A^{kv}
+    raw = (x @ W_ke.reshape(d, n_h * 2 * r)).reshape(T, n_h, r, 2)   # x_t W^k_{e,h}
+    ke = np.empty_like(raw)
+    for h in range(n_h):
+        for j in range(r):
+            alpha = pos.astype(F64) * theta[int(elite_idx[h, j])]    # t * theta_i
+            ke[:, h, j, :] = rotate_pairs(raw[:, h, j, :], alpha)
+    return ke.reshape(T, n_h, 2 * r), c
+
+
+def softmax_attention(q_vec, K, V, head_dim: int):
+    """Section 2.1: s = q K^T, p = softmax(s / sqrt(d_h)), o = p V.  q [D], K [S, D], V [S, Dv]."""
+    s = K @ q_vec / np.sqrt(F64(head_dim))
+    p = np.exp(s - np.max(s))
+    p = p / np.sum(p)
+    return p @ V
+
+
+def decode_attn(q, q_pos, ke, c, seq_len, W_uk, W_uv, elite_idx, head_dim: int,
+                rope_base: float, heads=None):
+    """Single-token decode attention over the compressed cache.
+
+    q [B, n_h, d_h] un-rotated, original dim order; q_pos [B]; ke[b] [>=S_b, n_h, 2r] and
+    c[b] [>=S_b, d_c] (indexable by b: an array with a leading batch axis or a list);
+    seq_len [B]; W_uk [d_c, n_h, d_h-2r]; W_uv [d_c, n_h, d_h]; elite_idx [n_h, r].
+    heads: optional list of head indices to compute (others left zero).
+    Returns o [B, n_h, d_h] float64.
+    """
+    q = np.asarray(q, dtype=F64)
+    W_uk = np.asarray(W_uk, dtype=F64)
+    W_uv = np.asarray(W_uv, dtype=F64)
+    elite_idx = np.asarray(elite_idx)
+    B, n_h, d_h = q.shape
+    assert d_h == head_dim
+    r = elite_idx.shape[1]
+    theta = rope_theta(head_dim, rope_base)
+    out = np.zeros((B, n_h, d_h), dtype=F64)
+    head_list = range(n_h) if heads is None else heads
+    for b in range(B):
+        S = int(seq_len[b])
+        if S == 0:
+            continue
+        ke_b = np.asarray(ke[b], dtype=F64)[:S]
+        c_b = np.asarray(c[b], dtype=F64)[:S]
+        for h in head_list:
+            idx_h = elite_idx[h]
+            # the query: elite chunks rotated at the query's position, the rest as is
+            q_e = q[b, h, elite_dims(idx_h)].reshape(r, 2)
+            alpha = F64(int(q_pos[b])) * theta[idx_h.astype(np.int64)] if r else np.zeros(0)
+            q_e = rotate_pairs(q_e, alpha).reshape(2 * r)
+            q_ne = q[b, h, nonelite_dims(idx_h, d_h)]
+            q_hat = np.concatenate([q_e, q_ne])
+            # reconstructed keys and values of every cached token
+            K_full = np.concatenate([ke_b[:, h, :], c_b @ W_uk[:, h, :]], axis=1)
+            V_full = c_b @ W_uv[:, h, :]
+            out[b, h] = softmax_attention(q_hat, K_full, V_full, d_h)
+    return out
+
+
+def mha_decode(q, q_pos, K_rot, V, seq_len, rope_base: float):
+    """Comparator: ordinary RoPE multi-head decode attention (Sections 2.1 and 2.2).
+
+    q [B, n_h, d_h] un-rotated; K_rot[b] [>=S_b, n_h, d_h] keys already rotated at their
+    own positions (what a RoPE model caches); V[b] [>=S_b, n_h, d_h].
+    Every chunk of q is rotated at q_pos[b]; then textbook attention.
+    """
+    q = np.asarray(q, dtype=F64)
+    B, n_h, d_h = q.shape
+    theta = rope_theta(d_h, rope_base)
+    out = np.zeros((B, n_h, d_h), dtype=F64)
+    for b in range(B):
+        S = int(seq_len[b])
+        if S == 0:
+            continue
+        K_b = np.asarray(K_rot[b], dtype=F64)[:S]
+        V_b = np.asarray(V[b], dtype=F64)[:S]
+        alpha = F64(int(q_pos[b])) * theta
+        for h in range(n_h):
+            q_rot = rotate_pairs(q[b, h].reshape(d_h // 2, 2), alpha).reshape(d_h)
+            out[b, h] = softmax_attention(q_rot, K_b[:, h, :], V_b[:, h, :], d_h)
+    return out
+
+
+def max_abs_rel(got, ref) -> float:
+    """Error metric of the parity gates: max|got - ref| / max|ref| over one tensor."""
+    got = np.asarray(got, dtype=F64)
+    ref = np.asarray(ref, dtype=F64)
+    denom = max(float(np.max(np.abs(ref))) if ref.size else 0.0, 1e-30)
+    return float(np.max(np.abs(got - ref))) / denom if ref.size else 0.0
