@@ -1,0 +1,260 @@
+"""Benchmark of the EliteKV decode hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+  elitekv_append of the batch's new tokens (down-projection + selective RoPE, written into the
+  cache planes) followed by elitekv_decode_attn over the whole cached context.
+The default workload is the 7B shape at 25 % cache, batch 1, 32K context.  Inputs are resident
+in HBM before the timed region.  The timed steps cycle over several distinct copies of the
+cache planes (>= 1 GiB in total) so that the 256 MB Infinity Cache cannot serve the reads.
+
+Prints one JSON line; see the design doc for the meaning of each field.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+METRIC = "decode attn HBM GB/s (% of peak) + tokens/s, 7B shape 25% cache, 32K ctx"
+
+
+class HipEvents:
+    """HIP events through the runtime's C API, recorded on the stream the kernels run on."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self):
+        ev = C.c_void_p()
+        rc = self.hip.hipEventCreate(C.byref(ev))
+        assert rc == 0, "hipEventCreate failed: %d" % rc
+        return ev
+
+    def record(self, ev, stream):
+        rc = self.hip.hipEventRecord(ev, C.c_void_p(stream))
+        assert rc == 0, "hipEventRecord failed: %d" % rc
+
+    def elapsed_ms(self, a, b):
+        self.hip.hipEventSynchronize(b)
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        assert rc == 0, "hipEventElapsedTime failed: %d" % rc
+        return float(ms.value)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="7b_25_b1_s32768")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-comparators", action="store_true")
+    ap.add_argument("--splits", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (nothing in it is distributed); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import elitekv_synth as synth
+    import paper_2503_01586_amd as ekv
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = synth.CONFIGS[args.workload]
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    esz = 2 if cfg.dtype == "bf16" else 4
+    B, S, n_h, d_h, r, d_c, d = cfg.batch, cfg.context, cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c, cfg.d_model
+    dims = ekv.make_dims(d, n_h, d_h, r, d_c, cfg.dtype, cfg.rope_base)
+    row_bytes = (2 * r * n_h + d_c) * esz
+    cache_bytes = B * S * row_bytes                                   # both planes, read once per call
+    n_copies = max(2, -(-(1 << 30) // cache_bytes))
+
+    rng = synth.rng_for(cfg.index)
+    idx_h = synth.draw_elite_idx(rng, n_h, d_h, r)
+    assert ekv.elitekv_validate_elite_idx(dims, idx_h) == 0
+    W_ke, W_dkv, W_uk, W_uv = synth.draw_weights(rng, d, n_h, d_h, r, d_c)
+    q_h = synth.draw_query(rng, B, n_h, d_h)
+    x_h = synth.draw_hidden(rng, B, d)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
+    W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d = map(to_dev, (W_ke, W_dkv, W_uk, W_uv, q_h, x_h))
+    idx_d = torch.from_numpy(idx_h).to(dev)
+    rows = B * S
+    planes = []
+    host_planes0 = None
+    for i in range(n_copies):
+        prng = synth.rng_for(cfg.index, stream=100 + i)
+        ke_h = prng.standard_normal((rows, n_h, 2 * r), dtype=np.float32)
+        c_h = prng.standard_normal((rows, d_c), dtype=np.float32)
+        ke_t, c_t = torch.from_numpy(ke_h).to(dt), torch.from_numpy(c_h).to(dt)
+        if i == 0:
+            host_planes0 = (ke_t, c_t)
+        planes.append((ke_t.to(dev), c_t.to(dev)))
+    pos_d = torch.full((B,), S - 1, dtype=torch.int32, device=dev)
+    slot_d = (torch.arange(B, dtype=torch.int64, device=dev) * S + (S - 1))
+    seq_d = torch.full((B,), S, dtype=torch.int32, device=dev)
+    out_d = torch.empty(B, n_h, d_h, dtype=dt, device=dev)
+    ws_d = torch.empty(max(ekv.elitekv_decode_workspace_bytes(dims, B, S, args.splits), 16), dtype=torch.uint8,
+                       device=dev)
+    aws_d = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, B), 16), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    ev = HipEvents()
+
+    def step(i, profile=None):
+        ke_p, c_p = planes[i % n_copies]
+        ekv.elitekv_append(dims, x_d, pos_d, slot_d, W_ke_d, W_dkv_d, idx_d, ke_p, c_p, ws=aws_d, stream=stream)
+        if profile is None:
+            ekv.elitekv_decode_attn(dims, q_d, pos_d, seq_d, S, S, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out_d, ws_d,
+                                    n_splits=args.splits, stream=stream)
+        else:
+            ekv.elitekv_decode_attn_profiled(dims, q_d, pos_d, seq_d, S, S, W_uk_d, W_uv_d, idx_d, ke_p, c_p,
+                                             out_d, ws_d, profile[0], profile[1], n_splits=args.splits,
+                                             stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = ev.create(), ev.create()
+    ev.record(e0, stream)
+    for i in range(args.steps):
+        step(i)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms_per_step = ev.elapsed_ms(e0, e1) / args.steps
+
+    # dominant kernel (the split attention kernel): one event pair per launch, same loop
+    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(i, profile=pairs[i])
+    torch.cuda.synchronize()
+    k_ms = sorted(ev.elapsed_ms(a, b) for a, b in pairs)
+    k_avg_ms = sum(k_ms) / len(k_ms)
+    assert bool(torch.isfinite(out_d.float()).all()), "non-finite output"
+
+    value_gbs = cache_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = cache_bytes / (k_avg_ms * 1e-3) / 1e9
+    result = {
+        "metric": METRIC, "value": round(value_gbs, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": B, "context": S, "d_model": d, "n_heads": n_h, "head_dim": d_h,
+                   "r": r, "d_c": d_c, "cache_fraction": (2 * r * n_h + d_c) / (2 * n_h * d_h),
+                   "step": "elitekv_append(T=batch) + elitekv_decode_attn", "plane_copies": n_copies,
+                   "n_splits": ekv.elitekv_decode_auto_splits(dims, B, S) if args.splits == 0 else args.splits},
+        "pct_of_hbm_peak": round(100.0 * value_gbs / HBM_PEAK_GBS, 2),
+        "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
+        "roofline": {"bound": "hbm", "kernel": "split attention kernel of elitekv_decode_attn",
+                     "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": cache_bytes, "avg_launch_ms": round(k_avg_ms, 5),
+                     "median_launch_ms": round(k_ms[len(k_ms) // 2], 5), "min_launch_ms": round(k_ms[0], 5)},
+    }
+
+    if not args.no_comparators:
+        result["comparators"] = comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream,
+                                            cache_bytes, args)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0,
+                                              cache_bytes)
+    print(json.dumps(result))
+
+
+def comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream, cache_bytes, args):
+    """Streaming-read ceiling over the same planes, and ordinary RoPE-MHA decode at the same shape."""
+    import torch
+    B, S, n_h, d_h = cfg.batch, cfg.context, cfg.n_heads, cfg.head_dim
+    out = {}
+    sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+    n = max(20, args.steps // 4)
+    for i in range(5):
+        ekv.elitekv_stream_read(planes[i % len(planes)][1], sink, stream=stream)
+    e0, e1 = ev.create(), ev.create()
+    ev.record(e0, stream)
+    nbytes = 0
+    for i in range(n):
+        ke_p, c_p = planes[i % len(planes)]
+        ekv.elitekv_stream_read(c_p, sink, stream=stream)
+        ekv.elitekv_stream_read(ke_p, sink, stream=stream)
+        nbytes += c_p.numel() * c_p.element_size() + ke_p.numel() * ke_p.element_size()
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    out["stream_read_GBs"] = round(nbytes / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9, 1)
+
+    # uncompressed cache: 2*n_h*d_h elements per token; use as many copies as fit ~2 GiB
+    esz = 2 if cfg.dtype == "bf16" else 4
+    full_bytes = B * S * 2 * n_h * d_h * esz
+    n_full = max(2, min(4, (2 << 30) // full_bytes))
+    g = torch.Generator(device=dev)
+    g.manual_seed(1586)
+    full = [(torch.randn(B * S, n_h, d_h, device=dev, dtype=torch.float32, generator=g).to(dt),
+             torch.randn(B * S, n_h, d_h, device=dev, dtype=torch.float32, generator=g).to(dt))
+            for _ in range(n_full)]
+    o = torch.empty(B, n_h, d_h, dtype=dt, device=dev)
+    ws = torch.empty(ekv.elitekv_mha_decode_workspace_bytes(dims, B, S, 0), dtype=torch.uint8, device=dev)
+    for i in range(5):
+        ekv.elitekv_mha_decode(dims, q_d, pos_d, seq_d, S, S, full[i % n_full][0], full[i % n_full][1], o, ws,
+                               stream=stream)
+    ev.record(e0, stream)
+    for i in range(n):
+        k_p, v_p = full[i % n_full]
+        ekv.elitekv_mha_decode(dims, q_d, pos_d, seq_d, S, S, k_p, v_p, o, ws, stream=stream)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms = ev.elapsed_ms(e0, e1) / n
+    out["mha_uncompressed_ms"] = round(ms, 5)
+    out["mha_uncompressed_GBs"] = round(full_bytes / (ms * 1e-3) / 1e9, 1)
+    out["mha_cache_bytes"] = full_bytes
+    return out
+
+
+def cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0, cache_bytes):
+    """The float64 oracle, as it stands, on the host's cores, over a bounded sample of the same
+    workload: the append of the batch's tokens plus decode attention for a subset of heads of
+    batch row 0, scaled linearly to all heads and rows."""
+    import numpy as np
+    import torch
+    from oracle import elitekv_oracle as orc
+    B, S, n_h, d_h = cfg.batch, cfg.context, cfg.n_heads, cfg.head_dim
+    to64 = lambda t: t.detach().to("cpu").to(torch.float64).numpy()
+    heads = list(range(0, n_h, max(1, n_h // 8)))[:8]
+    ke0 = host_planes0[0][:S].to(torch.float64).numpy()
+    c0 = host_planes0[1][:S].to(torch.float64).numpy()
+    Wuk, Wuv, q = to64(W_uk_d), to64(W_uv_d), to64(q_d)
+    t0 = time.perf_counter()
+    orc.append(to64(x_d), np.full(B, S - 1), to64(W_ke_d), to64(W_dkv_d), idx_h, d_h, cfg.rope_base)
+    t_app = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    orc.decode_attn(q[:1], [S - 1], [ke0], [c0], [S], Wuk, Wuv, idx_h, d_h, cfg.rope_base, heads=heads)
+    t_dec = time.perf_counter() - t0
+    est = t_app + t_dec * (n_h / len(heads)) * B
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    return {"value": round(cache_bytes / est / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "tokens_per_s": round(B / est, 4), "est_seconds_per_step": round(est, 3),
+            "sample": "oracle append of %d token(s) + oracle decode of %d of %d heads of batch row 0 over all %d "
+                      "cached tokens, scaled by heads and batch rows (host has %d logical cores)"
+                      % (B, len(heads), n_h, S, os.cpu_count())}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,196 @@
+/*
+ * libelitekv — decode hot path of EliteKV (RoPElite + joint low-rank KV compression)
+ * for AMD MI355X (gfx950).  Plain C ABI: pointers and sizes only.
+ *
+ * The library is stateless: it allocates nothing, keeps no handles and never synchronises.
+ * Every call only validates its arguments on the host and enqueues kernels on the HIP stream
+ * it is given; results are valid once the caller has synchronised that stream.  All buffers
+ * are owned by the caller.  Unless a parameter says "host", array pointers are DEVICE pointers.
+ *
+ * Notation follows the paper: d (hidden size), n_h (heads), d_h (head dim), r (elite 2-D chunks
+ * per head, Section 3.1), I_h (head h's elite chunk indices, each in [0, d_h/2)), d_c (rank of the
+ * joint latent, Section 3.2 "Joint Low-Rank Decomposition"), W_ke (W^k_{e,h}, Section 3.2),
+ * W_dkv = A^{kv}, W_uk = B^k_J, W_uv = B^v_J.
+ *
+ * Conventions fixed here where the paper is silent:
+ *   - theta_i = rope_base^(-2i/d_h); a chunk is the ADJACENT dim pair (2i, 2i+1) (Section 2.2);
+ *   - R(a) maps a row pair (u, v) to (u cos a - v sin a, u sin a + v cos a);
+ *   - column order inside a head: elite slots in the caller's I_h order, each slot as its two
+ *     lanes; non-elite dims in ascending original index;
+ *   - softmax scale is 1/sqrt(d_h) (Section 2.1).
+ *
+ * Return value of every int function: 0 on success, a negative elitekv_status otherwise.
+ * Validation happens before any launch; on error nothing has been enqueued.
+ */
+#ifndef ELITEKV_H
+#define ELITEKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum elitekv_status {
+  ELITEKV_OK = 0,
+  ELITEKV_EINVAL = -1,        /* bad dims: odd head_dim, r < 0 or r > d_h/2, d_c <= 0, negative counts, bad dtype */
+  ELITEKV_EINDEX = -2,        /* elite index out of range or repeated inside a head (host check only) */
+  ELITEKV_ENULL = -3,         /* a required pointer is NULL */
+  ELITEKV_EALIGN = -4,        /* a pointer or stride misses the 16-byte alignment the kernels need */
+  ELITEKV_EWORKSPACE = -5,    /* workspace smaller than the matching *_workspace_bytes() */
+  ELITEKV_EUNSUPPORTED = -6,  /* shape outside what the kernels cover (see each call) */
+  ELITEKV_EHIP = -7           /* the HIP runtime reported a launch error */
+};
+
+enum elitekv_dtype {
+  ELITEKV_FP32 = 0,           /* fp32 storage, fp32 arithmetic */
+  ELITEKV_BF16 = 1            /* bf16 storage (weights, activations, cache), fp32 accumulation */
+};
+
+/* Problem dimensions.  MHA only (one key/value head per query head). */
+typedef struct elitekv_dims {
+  int32_t d_model;    /* d, hidden size of x */
+  int32_t n_heads;    /* n_h */
+  int32_t head_dim;   /* d_h, even */
+  int32_t r;          /* elite chunks per head, 0 <= r <= d_h/2 */
+  int32_t d_c;        /* latent rank, > 0 */
+  int32_t dtype;      /* elitekv_dtype of x, q, weights, cache planes and out */
+  double rope_base;   /* > 0, e.g. 10000 */
+} elitekv_dims;
+
+/* Human-readable name of a status code.  Never NULL. */
+const char* elitekv_strerror(int status);
+
+/* Per-token cache row sizes in elements: *ke_elems = 2*r*n_h, *c_elems = d_c.
+ * (Section 3.2, J-LRD: the cache holds 2*r*n_h + d_c elements per token per layer.) */
+int elitekv_cache_row_elems(const elitekv_dims* dims, int64_t* ke_elems, int64_t* c_elems);
+
+/* Total parameters of the four weight blocks this ABI takes:
+ * 2*r*n_h*d + d_c*(d + 2*d_h*n_h - 2*r*n_h)  (Section 3.2, storage cost of RoPElite with J-LRD). */
+int elitekv_param_count(const elitekv_dims* dims, int64_t* n_params);
+
+/* Host-only check of the index sets I_h (Section 3.1): idx_host is a HOST array [n_h, r];
+ * every entry must lie in [0, d_h/2) and be distinct within its head.  EINDEX otherwise. */
+int elitekv_validate_elite_idx(const elitekv_dims* dims, const int32_t* idx_host);
+
+/* Workspace (device bytes) elitekv_append needs for T tokens.  0 on bad dims. */
+size_t elitekv_append_workspace_bytes(const elitekv_dims* dims, int64_t T);
+
+/*
+ * Cache append (Section 3.1, what a RoPElite model adds to its cache at step t; Section 3.2,
+ * c_t = x_t A^{kv} and W^k_{e,h}).  For every token t < T:
+ *     c_plane[slot[t], :]            = x_t W_dkv
+ *     ke_plane[slot[t], h, 2j:2j+2]  = (x_t W_ke[:, h, 2j:2j+2]) R(pos[t] * theta_{I_h[j]})
+ * The rotation angle is formed in double precision.  Old cache rows are never read.
+ *
+ *   x          [T, d_model]                 dims->dtype, row-major
+ *   pos        [T] int32                    position of each token
+ *   slot       [T] int64                    destination row in both planes; a slot outside
+ *                                           [0, plane_rows) makes that token a no-op
+ *   W_ke       [d_model, n_h, 2r]           dims->dtype
+ *   W_dkv      [d_model, d_c]               dims->dtype
+ *   elite_idx  [n_h, r] int32               DEVICE copy of I_h (validate on the host beforehand)
+ *   ke_plane   [plane_rows, n_h, 2r]        written, dims->dtype (may be NULL when r == 0)
+ *   c_plane    [plane_rows, d_c]            written, dims->dtype
+ *   ws         workspace of at least elitekv_append_workspace_bytes(dims, T) (may be NULL if 0)
+ *   hip_stream a hipStream_t (NULL = the default stream)
+ *
+ * T == 0 is a successful no-op.  Errors: EINVAL, ENULL, EALIGN (pointers must be 16-byte aligned),
+ * EWORKSPACE, EHIP.
+ */
+int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, const int64_t* slot,
+                   int64_t T, const void* W_ke, const void* W_dkv, const int32_t* elite_idx,
+                   void* ke_plane, void* c_plane, int64_t plane_rows, void* ws, size_t ws_bytes,
+                   void* hip_stream);
+
+/* Number of sequence splits elitekv_decode_attn uses when n_splits == 0 ("auto") for this shape.
+ * Returns <= 0 on bad dims. */
+int32_t elitekv_decode_auto_splits(const elitekv_dims* dims, int64_t B, int64_t max_seq_len);
+
+/* Workspace (device bytes) elitekv_decode_attn needs.  n_splits == 0 means "auto". 0 on bad dims. */
+size_t elitekv_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
+                                      int32_t n_splits);
+
+/*
+ * Single-token decode attention over the compressed cache (Section 3.1, the RoPElite score
+ * equation; Section 2.1, softmax attention; Section 3.2, B^{kv} = [B^k_J, B^v_J]; Section 5,
+ * absorption of B^k and B^v into the neighbouring products).  For batch row b and head h, over
+ * the cached rows j in [b*batch_stride_rows, b*batch_stride_rows + seq_len[b]):
+ *     s_j = ( rot(q[b,h,I_h], q_pos[b]) . ke_plane[j,h,:]  +  q[b,h,non-elite] . (c_plane[j,:] W_uk[:,h,:]) ) / sqrt(d_h)
+ *     p   = softmax_j(s),      out[b,h,:] = sum_j p_j (c_plane[j,:] W_uv[:,h,:])
+ * computed as: W_uk absorbed into the query, one online softmax over both score terms, values
+ * accumulated in latent space, split over the sequence with an exact log-sum-exp merge, then
+ * W_uv applied once.  The cached elite keys are used as stored (no re-rotation).
+ *
+ *   q          [B, n_h, d_h]        un-rotated query, original dim order, dims->dtype
+ *   q_pos      [B] int32            position of each query token
+ *   seq_len    [B] int32            cached rows each batch row attends to; values above
+ *                                   max_seq_len, or reaching past plane_rows, are clamped
+ *                                   on the device; seq_len[b] == 0 gives a zero output row
+ *   max_seq_len                     HOST upper bound on seq_len[] (plans the split)
+ *   batch_stride_rows               plane rows between consecutive batch rows' first row
+ *   W_uk       [d_c, n_h, d_h-2r]   dims->dtype
+ *   W_uv       [d_c, n_h, d_h]      dims->dtype
+ *   elite_idx  [n_h, r] int32       DEVICE copy of I_h
+ *   ke_plane   [plane_rows, n_h, 2r], c_plane [plane_rows, d_c]   read only, dims->dtype
+ *   out        [B, n_h, d_h]        written, dims->dtype
+ *   ws         at least elitekv_decode_workspace_bytes(dims, B, max_seq_len, n_splits)
+ *   n_splits   sequence splits per batch row; 0 = auto.  The result does not depend on it
+ *              beyond rounding.
+ *
+ * B == 0 is a successful no-op.  Errors: EINVAL, ENULL, EALIGN, EWORKSPACE, EUNSUPPORTED
+ * (d_c > 4096, or n_splits > 1024), EHIP.
+ */
+int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                        const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                        int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                        const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                        int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                        void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Measurement-only companions (not part of the method).
+ * ------------------------------------------------------------------------------------------- */
+
+/*
+ * elitekv_decode_attn with two HIP events (hipEvent_t, created by the caller with timing enabled)
+ * recorded on hip_stream immediately before and after the split attention kernel, the kernel that
+ * streams the cache planes.  Used by the benchmark to time that kernel alone inside the whole call.
+ * Same arguments, results and errors as elitekv_decode_attn; ENULL if an event is NULL.
+ */
+int elitekv_decode_attn_profiled(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                                 const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                                 int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                                 const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                                 int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
+                                 int32_t n_splits, void* hip_stream, void* ev_before, void* ev_after);
+
+/* Workspace bytes of elitekv_mha_decode.  n_splits == 0 means "auto". */
+size_t elitekv_mha_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
+                                          int32_t n_splits);
+
+/*
+ * Comparator: ordinary RoPE multi-head decode attention over an UNCOMPRESSED cache at the same
+ * (B, S, n_h, d_h) (Section 2.2: a RoPE model caches every chunk of k rotated, plus v).
+ *   q [B, n_h, d_h] un-rotated (all d_h/2 chunks are rotated at q_pos[b] here);
+ *   k_plane, v_plane [plane_rows, n_h, d_h], keys already rotated; out [B, n_h, d_h].
+ * Only dims->n_heads, head_dim, dtype and rope_base are used.  head_dim must be <= 256.
+ */
+int elitekv_mha_decode(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                       const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                       int64_t batch_stride_rows, const void* k_plane, const void* v_plane,
+                       int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                       void* hip_stream);
+
+/*
+ * Streaming-read probe: reads `bytes` bytes at `src` (16-byte aligned, bytes % 16 == 0) once with
+ * wide coalesced loads and folds them into sink[0..grid) so the reads cannot be elided.  Gives the
+ * achievable HBM read rate to compare the decode kernel against.  sink: >= 4096 uint32.
+ */
+int elitekv_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELITEKV_H */

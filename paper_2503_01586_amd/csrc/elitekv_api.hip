@@ -1,0 +1,272 @@
+// C-ABI entry points of libelitekv: host-side validation, split planning, workspace layout.
+// Nothing here touches the device except through the launchers, and nothing allocates.
+#include <math.h>
+#include <string.h>
+
+#include "launch.hpp"
+
+namespace ekv {
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+static int check_dims(const elitekv_dims* d) {
+  if (!d) return ELITEKV_ENULL;
+  if (d->d_model <= 0 || d->n_heads <= 0 || d->head_dim <= 0 || (d->head_dim & 1)) return ELITEKV_EINVAL;
+  if (d->r < 0 || 2 * d->r > d->head_dim || d->d_c <= 0) return ELITEKV_EINVAL;
+  if (d->dtype != ELITEKV_FP32 && d->dtype != ELITEKV_BF16) return ELITEKV_EINVAL;
+  if (!(d->rope_base > 0.0) || !isfinite(d->rope_base)) return ELITEKV_EINVAL;
+  return ELITEKV_OK;
+}
+
+static inline size_t elem_bytes(const elitekv_dims* d) { return d->dtype == ELITEKV_FP32 ? 4 : 2; }
+
+constexpr int kMaxSplits = 1024;
+constexpr int kTargetGroups = 1024;   // generic path: work-groups wanted in flight
+
+static int32_t auto_splits_generic(const elitekv_dims* d, int64_t B, int64_t max_seq) {
+  const int64_t per_split_min = 64;
+  int64_t want = (kTargetGroups + B * d->n_heads - 1) / (B * d->n_heads);
+  int64_t cap = (max_seq + per_split_min - 1) / per_split_min;
+  if (want > cap) want = cap;
+  if (want > kMaxSplits) want = kMaxSplits;
+  if (want < 1) want = 1;
+  return (int32_t)want;
+}
+
+// Decide the path and lay the workspace out.  Returns a status.
+static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_t n_splits, DecodePlan* p) {
+  int st = check_dims(d);
+  if (st) return st;
+  if (B < 0 || max_seq < 0 || n_splits < 0) return ELITEKV_EINVAL;
+  if (d->d_c > 4096 || d->head_dim > 256 || n_splits > kMaxSplits) return ELITEKV_EUNSUPPORTED;
+  memset(p, 0, sizeof(*p));
+  p->mfma = 0;
+  p->head_groups = 1;
+  const int64_t Bq = B > 0 ? B : 1;
+  p->n_splits = n_splits > 0 ? n_splits : auto_splits_generic(d, Bq, max_seq > 0 ? max_seq : 1);
+  int64_t chunk = (max_seq + p->n_splits - 1) / p->n_splits;
+  if (chunk < 1) chunk = 1;
+  p->chunk = (int32_t)chunk;
+  const size_t nh = d->n_heads, dc = d->d_c, ns = p->n_splits, Bz = (size_t)B;
+  size_t off = 0;
+  p->off_qe = off; off = align_up(off + Bz * nh * 2 * d->r * sizeof(float), 256);
+  p->off_qt = off; off = align_up(off + Bz * nh * dc * sizeof(float), 256);
+  p->off_m = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
+  p->off_l = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
+  p->off_u = off;  off = align_up(off + Bz * ns * nh * dc * sizeof(float), 256);
+  p->off_ubar = off;
+  p->off_opart = off;
+  p->off_cnt = off;
+  p->total = off;
+  return ELITEKV_OK;
+}
+
+static int plan_mha(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_t n_splits, int32_t* ns_out,
+                    int32_t* chunk_out, size_t* bytes) {
+  int st = check_dims(d);
+  if (st) return st;
+  if (B < 0 || max_seq < 0 || n_splits < 0) return ELITEKV_EINVAL;
+  if (n_splits > kMaxSplits || d->head_dim > 256) return ELITEKV_EUNSUPPORTED;
+  const int vec = d->dtype == ELITEKV_FP32 ? 4 : 8;
+  const int lpr = d->head_dim / vec;
+  if (d->head_dim % vec || lpr < 2 || lpr > 64 || (lpr & (lpr - 1))) return ELITEKV_EUNSUPPORTED;
+  const int64_t Bq = B > 0 ? B : 1;
+  int32_t ns = n_splits > 0 ? n_splits : auto_splits_generic(d, Bq, max_seq > 0 ? max_seq : 1);
+  int64_t chunk = (max_seq + ns - 1) / ns;
+  if (chunk < 1) chunk = 1;
+  *ns_out = ns;
+  *chunk_out = (int32_t)chunk;
+  *bytes = align_up((size_t)B * ns * d->n_heads * (2 + d->head_dim) * sizeof(float), 256);
+  return ELITEKV_OK;
+}
+
+}  // namespace ekv
+
+using namespace ekv;
+
+extern "C" {
+
+const char* elitekv_strerror(int status) {
+  switch (status) {
+    case ELITEKV_OK: return "ok";
+    case ELITEKV_EINVAL: return "invalid dimensions or counts";
+    case ELITEKV_EINDEX: return "elite index out of range or repeated within a head";
+    case ELITEKV_ENULL: return "required pointer is NULL";
+    case ELITEKV_EALIGN: return "pointer or stride is not 16-byte aligned";
+    case ELITEKV_EWORKSPACE: return "workspace too small";
+    case ELITEKV_EUNSUPPORTED: return "shape not covered by the kernels";
+    case ELITEKV_EHIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int elitekv_cache_row_elems(const elitekv_dims* dims, int64_t* ke_elems, int64_t* c_elems) {
+  int st = check_dims(dims);
+  if (st) return st;
+  if (!ke_elems || !c_elems) return ELITEKV_ENULL;
+  *ke_elems = 2LL * dims->r * dims->n_heads;
+  *c_elems = dims->d_c;
+  return ELITEKV_OK;
+}
+
+int elitekv_param_count(const elitekv_dims* dims, int64_t* n_params) {
+  int st = check_dims(dims);
+  if (st) return st;
+  if (!n_params) return ELITEKV_ENULL;
+  const int64_t d = dims->d_model, nh = dims->n_heads, dh = dims->head_dim, r = dims->r, dc = dims->d_c;
+  *n_params = 2 * r * nh * d + dc * (d + 2 * dh * nh - 2 * r * nh);
+  return ELITEKV_OK;
+}
+
+int elitekv_validate_elite_idx(const elitekv_dims* dims, const int32_t* idx_host) {
+  int st = check_dims(dims);
+  if (st) return st;
+  if (dims->r == 0) return ELITEKV_OK;
+  if (!idx_host) return ELITEKV_ENULL;
+  const int half = dims->head_dim / 2, r = dims->r;
+  for (int h = 0; h < dims->n_heads; ++h) {
+    for (int j = 0; j < r; ++j) {
+      const int32_t i = idx_host[h * r + j];
+      if (i < 0 || i >= half) return ELITEKV_EINDEX;
+      for (int k = 0; k < j; ++k)
+        if (idx_host[h * r + k] == i) return ELITEKV_EINDEX;
+    }
+  }
+  return ELITEKV_OK;
+}
+
+size_t elitekv_append_workspace_bytes(const elitekv_dims* dims, int64_t T) {
+  if (check_dims(dims) || T < 0) return 0;
+  return 0;
+}
+
+int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, const int64_t* slot,
+                   int64_t T, const void* W_ke, const void* W_dkv, const int32_t* elite_idx,
+                   void* ke_plane, void* c_plane, int64_t plane_rows, void* ws, size_t ws_bytes,
+                   void* hip_stream) {
+  int st = check_dims(dims);
+  if (st) return st;
+  if (T < 0 || plane_rows < 0) return ELITEKV_EINVAL;
+  if (T == 0) return ELITEKV_OK;
+  if (!x || !pos || !slot || !W_dkv || !c_plane) return ELITEKV_ENULL;
+  if (dims->r > 0 && (!W_ke || !elite_idx || !ke_plane)) return ELITEKV_ENULL;
+  if (!aligned16(x) || !aligned16(W_dkv) || !aligned16(c_plane) || !aligned16(W_ke) ||
+      !aligned16(ke_plane) || !aligned16(ws))
+    return ELITEKV_EALIGN;
+  const size_t need = elitekv_append_workspace_bytes(dims, T);
+  if (need > 0 && (!ws || ws_bytes < need)) return ws ? ELITEKV_EWORKSPACE : ELITEKV_ENULL;
+  if ((T + 7) / 8 > 2147483647LL) return ELITEKV_EUNSUPPORTED;
+
+  AppendArgs a;
+  a.dims = *dims; a.x = x; a.pos = pos; a.slot = slot; a.T = T; a.W_ke = W_ke; a.W_dkv = W_dkv;
+  a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows;
+  a.ws = (char*)ws;
+  const hipError_t e = launch_append_generic(a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+int32_t elitekv_decode_auto_splits(const elitekv_dims* dims, int64_t B, int64_t max_seq_len) {
+  DecodePlan p;
+  if (plan_decode(dims, B, max_seq_len, 0, &p)) return 0;
+  return p.n_splits;
+}
+
+size_t elitekv_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
+                                      int32_t n_splits) {
+  DecodePlan p;
+  if (plan_decode(dims, B, max_seq_len, n_splits, &p)) return 0;
+  return p.total;
+}
+
+static int decode_impl(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                       const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                       int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                       const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                       int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                       void* hip_stream, void* ev_before, void* ev_after) {
+  DecodePlan p;
+  int st = plan_decode(dims, B, max_seq_len, n_splits, &p);
+  if (st) return st;
+  if (batch_stride_rows < 0 || plane_rows < 0) return ELITEKV_EINVAL;
+  if (B == 0) return ELITEKV_OK;
+  if (B > 65535) return ELITEKV_EUNSUPPORTED;
+  if (!q || !q_pos || !seq_len || !W_uv || !c_plane || !out || !ws) return ELITEKV_ENULL;
+  if (dims->r > 0 && (!elite_idx || !ke_plane)) return ELITEKV_ENULL;
+  if (2 * dims->r < dims->head_dim && !W_uk) return ELITEKV_ENULL;
+  if (!aligned16(q) || !aligned16(W_uk) || !aligned16(W_uv) || !aligned16(ke_plane) ||
+      !aligned16(c_plane) || !aligned16(out) || !aligned16(ws))
+    return ELITEKV_EALIGN;
+  if (ws_bytes < p.total) return ELITEKV_EWORKSPACE;
+
+  DecodeArgs a;
+  a.dims = *dims; a.q = q; a.q_pos = q_pos; a.seq_len = seq_len; a.B = B; a.max_seq_len = max_seq_len;
+  a.batch_stride_rows = batch_stride_rows; a.W_uk = W_uk; a.W_uv = W_uv; a.elite_idx = elite_idx;
+  a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows; a.out = out; a.ws = (char*)ws;
+  a.ev_before = (hipEvent_t)ev_before; a.ev_after = (hipEvent_t)ev_after;
+  const hipError_t e = launch_decode_generic(a, p, (hipStream_t)hip_stream);
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                        const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                        int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                        const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                        int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                        void* hip_stream) {
+  return decode_impl(dims, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, nullptr, nullptr);
+}
+
+int elitekv_decode_attn_profiled(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                                 const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                                 int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                                 const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                                 int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
+                                 int32_t n_splits, void* hip_stream, void* ev_before, void* ev_after) {
+  if (!ev_before || !ev_after) return ELITEKV_ENULL;
+  return decode_impl(dims, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, ev_before, ev_after);
+}
+
+size_t elitekv_mha_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
+                                          int32_t n_splits) {
+  int32_t ns, chunk;
+  size_t bytes;
+  if (plan_mha(dims, B, max_seq_len, n_splits, &ns, &chunk, &bytes)) return 0;
+  return bytes;
+}
+
+int elitekv_mha_decode(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                       const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                       int64_t batch_stride_rows, const void* k_plane, const void* v_plane,
+                       int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                       void* hip_stream) {
+  int32_t ns, chunk;
+  size_t bytes;
+  int st = plan_mha(dims, B, max_seq_len, n_splits, &ns, &chunk, &bytes);
+  if (st) return st;
+  if (batch_stride_rows < 0 || plane_rows < 0) return ELITEKV_EINVAL;
+  if (B == 0) return ELITEKV_OK;
+  if (B > 65535) return ELITEKV_EUNSUPPORTED;
+  if (!q || !q_pos || !seq_len || !k_plane || !v_plane || !out || !ws) return ELITEKV_ENULL;
+  if (!aligned16(q) || !aligned16(k_plane) || !aligned16(v_plane) || !aligned16(out) || !aligned16(ws))
+    return ELITEKV_EALIGN;
+  if (ws_bytes < bytes) return ELITEKV_EWORKSPACE;
+  MhaArgs a;
+  a.dims = *dims; a.q = q; a.q_pos = q_pos; a.seq_len = seq_len; a.B = B; a.max_seq_len = max_seq_len;
+  a.batch_stride_rows = batch_stride_rows; a.k_plane = k_plane; a.v_plane = v_plane;
+  a.plane_rows = plane_rows; a.out = out; a.ws = (char*)ws; a.n_splits = ns; a.chunk = chunk;
+  const hipError_t e = launch_mha_decode(a, (hipStream_t)hip_stream);
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+int elitekv_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream) {
+  if (!src || !sink) return ELITEKV_ENULL;
+  if (!aligned16(src) || (bytes & 15u)) return ELITEKV_EALIGN;
+  if (bytes == 0) return ELITEKV_OK;
+  const hipError_t e = launch_stream_read(src, bytes, sink, (hipStream_t)hip_stream);
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Internal interface between the C-ABI entry points (host validation and planning) and the
+// kernel launchers.  Every launcher only enqueues work on `stream`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/elitekv.h"
+
+namespace ekv {
+
+// Where each intermediate of one decode call lives inside the caller's workspace.
+struct DecodePlan {
+  int32_t n_splits;     // sequence splits per batch row
+  int32_t chunk;        // cached tokens per split
+  int32_t mfma;         // 1: bf16 MFMA kernels, 0: generic VALU kernels
+  int32_t head_groups;  // MFMA path: groups of up to 32 heads
+  size_t off_qe;        // rotated, scaled elite query      fp32 [B, n_h, 2r]
+  size_t off_qt;        // absorbed, scaled latent query    fp32 [B, n_h, d_c] (generic) / bf16 (mfma)
+  size_t off_m;         // split maxima (log2 domain)       fp32 [B, n_splits, n_h_pad]
+  size_t off_l;         // split sums                       fp32 [B, n_splits, n_h_pad]
+  size_t off_u;         // split latent accumulators        fp32 [B, n_splits, ...]
+  size_t off_ubar;      // merged, normalised latent        fp32 [B, n_h, d_c]
+  size_t off_opart;     // up-projection partials           fp32
+  size_t off_cnt;       // arrival counters                 uint32
+  size_t total;
+};
+
+struct DecodeArgs {
+  elitekv_dims dims;
+  const void* q;
+  const int32_t* q_pos;
+  const int32_t* seq_len;
+  int64_t B, max_seq_len, batch_stride_rows;
+  const void* W_uk;
+  const void* W_uv;
+  const int32_t* elite_idx;
+  const void* ke_plane;
+  const void* c_plane;
+  int64_t plane_rows;
+  void* out;
+  char* ws;
+  hipEvent_t ev_before, ev_after;   // optional: recorded around the split attention kernel
+};
+
+struct AppendArgs {
+  elitekv_dims dims;
+  const void* x;
+  const int32_t* pos;
+  const int64_t* slot;
+  int64_t T;
+  const void* W_ke;
+  const void* W_dkv;
+  const int32_t* elite_idx;
+  void* ke_plane;
+  void* c_plane;
+  int64_t plane_rows;
+  char* ws;
+};
+
+struct MhaArgs {
+  elitekv_dims dims;
+  const void* q;
+  const int32_t* q_pos;
+  const int32_t* seq_len;
+  int64_t B, max_seq_len, batch_stride_rows;
+  const void* k_plane;
+  const void* v_plane;
+  int64_t plane_rows;
+  void* out;
+  char* ws;
+  int32_t n_splits, chunk;
+};
+
+hipError_t launch_append_generic(const AppendArgs& a, hipStream_t stream);
+hipError_t launch_decode_generic(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
+hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
+
+}  // namespace ekv

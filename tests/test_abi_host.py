@@ -1,0 +1,151 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and every validation path returns its error code before any launch."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import elitekv_synth as synth
+import paper_2503_01586_amd as ekv
+from oracle import elitekv_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+lib = ekv.raw()
+FAKE = 0x10000  # a non-NULL, 16-byte aligned address that is never dereferenced on these paths
+
+
+def _dims(**kw):
+    base = dict(d_model=128, n_heads=4, head_dim=32, r=2, d_c=64, dtype="fp32", rope_base=10000.0)
+    base.update(kw)
+    return ekv.make_dims(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "elitekv.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(elitekv_[a-z0-9_]+)\s*\(", hdr))
+    assert declared, "no declarations parsed"
+    for name in declared:
+        assert hasattr(lib, name), "library does not export %s" % name
+    assert declared == set(ekv.EXPORTS), (declared ^ set(ekv.EXPORTS))
+
+
+def test_strerror_names_every_code():
+    seen = set()
+    for code in range(0, -8, -1):
+        s = ekv.elitekv_strerror(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert ekv.elitekv_strerror(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_cache_row_and_param_formulas_match_oracle(name):
+    cfg = synth.CONFIGS[name]
+    d = ekv.make_dims(cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c, cfg.dtype)
+    ke, c = ekv.elitekv_cache_row_elems(d)
+    assert ke + c == orc.cache_row_elems(cfg.n_heads, cfg.r, cfg.d_c)
+    assert (ke, c) == (2 * cfg.r * cfg.n_heads, cfg.d_c)
+    assert ekv.elitekv_param_count(d) == orc.param_count(cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c)
+
+
+@pytest.mark.parametrize("bad", [dict(head_dim=31), dict(r=-1), dict(r=17), dict(d_c=0), dict(n_heads=0),
+                                 dict(d_model=0), dict(dtype=7), dict(rope_base=0.0), dict(rope_base=-3.0)])
+def test_bad_dims_are_einval(bad):
+    d = _dims(**bad)
+    ke, c = C.c_int64(), C.c_int64()
+    assert lib.elitekv_cache_row_elems(C.byref(d), C.byref(ke), C.byref(c)) == ekv.EINVAL
+    assert ekv.elitekv_decode_workspace_bytes(d, 1, 128) == 0
+    assert ekv.elitekv_append_workspace_bytes(d, 1) == 0
+    assert lib.elitekv_append(C.byref(d), FAKE, FAKE, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 16, None, 0,
+                              None) == ekv.EINVAL
+    assert lib.elitekv_decode_attn(C.byref(d), FAKE, FAKE, FAKE, 1, 16, 16, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                   16, FAKE, FAKE, 1 << 20, 0, None) == ekv.EINVAL
+
+
+def test_validate_elite_idx():
+    d = _dims()
+    good = np.array([[0, 15], [3, 4], [7, 1], [9, 2]], dtype=np.int32)
+    assert ekv.elitekv_validate_elite_idx(d, good) == ekv.OK
+    for bad in ([[0, 16]], [[-1, 2]], [[5, 5]]):
+        arr = good.copy()
+        arr[2] = bad[0]
+        assert ekv.elitekv_validate_elite_idx(d, arr) == ekv.EINDEX
+    assert lib.elitekv_validate_elite_idx(C.byref(d), None) == ekv.ENULL
+    assert lib.elitekv_validate_elite_idx(C.byref(_dims(r=0)), None) == ekv.OK
+    cfg = synth.CONFIGS["7b_25_b1_s32768"]
+    idx = synth.draw_elite_idx(synth.rng_for(2), cfg.n_heads, cfg.head_dim, cfg.r)
+    assert ekv.elitekv_validate_elite_idx(ekv.make_dims(4096, 32, 128, 8, 1536, "bf16"), idx) == ekv.OK
+
+
+def _append(d, x=FAKE, pos=FAKE, slot=FAKE, T=4, W_ke=FAKE, W_dkv=FAKE, idx=FAKE, ke=FAKE, c=FAKE,
+            rows=16, ws=None, ws_bytes=0):
+    return lib.elitekv_append(C.byref(d), x, pos, slot, T, W_ke, W_dkv, idx, ke, c, rows, ws, ws_bytes, None)
+
+
+def test_append_argument_errors():
+    d = _dims()
+    assert _append(d, T=0) == ekv.OK                      # empty call is a no-op
+    assert _append(d, T=-1) == ekv.EINVAL
+    assert _append(d, rows=-1) == ekv.EINVAL
+    for k in ("x", "pos", "slot", "W_ke", "W_dkv", "idx", "ke", "c"):
+        assert _append(d, **{k: None}) == ekv.ENULL, k
+    for k in ("x", "W_ke", "W_dkv", "ke", "c"):
+        assert _append(d, **{k: FAKE + 4}) == ekv.EALIGN, k
+    d0 = _dims(r=0)                                        # no elite part: its pointers may be NULL
+    assert _append(d0, T=0, W_ke=None, idx=None, ke=None) == ekv.OK
+
+
+def _decode(d, q=FAKE, q_pos=FAKE, seq=FAKE, B=1, max_seq=128, stride=128, W_uk=FAKE, W_uv=FAKE, idx=FAKE,
+            ke=FAKE, c=FAKE, rows=128, out=FAKE, ws=FAKE, ws_bytes=1 << 30, n_splits=0):
+    return lib.elitekv_decode_attn(C.byref(d), q, q_pos, seq, B, max_seq, stride, W_uk, W_uv, idx, ke, c,
+                                   rows, out, ws, ws_bytes, n_splits, None)
+
+
+def test_decode_argument_errors():
+    d = _dims()
+    assert _decode(d, B=0) == ekv.OK
+    assert _decode(d, B=-1) == ekv.EINVAL
+    assert _decode(d, max_seq=-1) == ekv.EINVAL
+    assert _decode(d, stride=-1) == ekv.EINVAL
+    assert _decode(d, n_splits=-1) == ekv.EINVAL
+    assert _decode(d, n_splits=4096) == ekv.EUNSUPPORTED
+    assert _decode(_dims(d_c=8192)) == ekv.EUNSUPPORTED
+    for k in ("q", "q_pos", "seq", "W_uk", "W_uv", "idx", "ke", "c", "out", "ws"):
+        assert _decode(d, **{k: None}) == ekv.ENULL, k
+    for k in ("q", "W_uk", "W_uv", "ke", "c", "out", "ws"):
+        assert _decode(d, **{k: FAKE + 8}) == ekv.EALIGN, k
+    need = ekv.elitekv_decode_workspace_bytes(d, 1, 128)
+    assert need > 0
+    assert _decode(d, ws_bytes=need - 1) == ekv.EWORKSPACE
+
+
+def test_workspace_grows_with_batch_and_splits():
+    d = ekv.make_dims(4096, 32, 128, 8, 1536, "bf16")
+    a = ekv.elitekv_decode_workspace_bytes(d, 1, 32768, 16)
+    b = ekv.elitekv_decode_workspace_bytes(d, 2, 32768, 16)
+    c = ekv.elitekv_decode_workspace_bytes(d, 1, 32768, 32)
+    assert 0 < a < b and a < c
+    ns = ekv.elitekv_decode_auto_splits(d, 1, 32768)
+    assert 1 <= ns <= 1024
+    assert ekv.elitekv_decode_workspace_bytes(d, 1, 32768, 0) == ekv.elitekv_decode_workspace_bytes(d, 1, 32768, ns)
+    assert ekv.elitekv_decode_auto_splits(d, 1, 1) == 1
+
+
+def test_mha_and_stream_argument_errors():
+    d = _dims()
+    need = ekv.elitekv_mha_decode_workspace_bytes(d, 2, 256)
+    assert need > 0
+    f = lambda **kw: lib.elitekv_mha_decode(C.byref(d), kw.get("q", FAKE), FAKE, FAKE, kw.get("B", 2), 256, 256,
+                                            kw.get("k", FAKE), FAKE, 512, FAKE, FAKE, kw.get("wsb", need), 0, None)
+    assert f(B=0) == ekv.OK
+    assert f(q=None) == ekv.ENULL
+    assert f(k=FAKE + 2) == ekv.EALIGN
+    assert f(wsb=need - 1) == ekv.EWORKSPACE
+    assert ekv.elitekv_mha_decode_workspace_bytes(_dims(head_dim=36), 1, 64) == 0   # 36/4 lanes: not a power of two
+    assert lib.elitekv_stream_read(None, 16, FAKE, None) == ekv.ENULL
+    assert lib.elitekv_stream_read(FAKE, 24, FAKE, None) == ekv.EALIGN
+    assert lib.elitekv_stream_read(FAKE, 0, FAKE, None) == ekv.OK
