@@ -22,6 +22,7 @@ static int check_dims(const elitekv_dims* d) {
 static inline size_t elem_bytes(const elitekv_dims* d) { return d->dtype == ELITEKV_FP32 ? 4 : 2; }
 
 constexpr int kMaxSplits = 1024;
+constexpr int kComputeUnits = 256;  // MI355X
 constexpr int kTargetGroups = 1024;   // generic path: work-groups wanted in flight
 
 static int32_t auto_splits_generic(const elitekv_dims* d, int64_t B, int64_t max_seq) {
@@ -41,20 +42,45 @@ static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_
   if (B < 0 || max_seq < 0 || n_splits < 0) return ELITEKV_EINVAL;
   if (d->d_c > 4096 || d->head_dim > 256 || n_splits > kMaxSplits) return ELITEKV_EUNSUPPORTED;
   memset(p, 0, sizeof(*p));
-  p->mfma = 0;
-  p->head_groups = 1;
   const int64_t Bq = B > 0 ? B : 1;
-  p->n_splits = n_splits > 0 ? n_splits : auto_splits_generic(d, Bq, max_seq > 0 ? max_seq : 1);
-  int64_t chunk = (max_seq + p->n_splits - 1) / p->n_splits;
-  if (chunk < 1) chunk = 1;
-  p->chunk = (int32_t)chunk;
-  const size_t nh = d->n_heads, dc = d->d_c, ns = p->n_splits, Bz = (size_t)B;
+  const int64_t seq = max_seq > 0 ? max_seq : 1;
+  const size_t nh = d->n_heads, dc = d->d_c, Bz = (size_t)B;
   size_t off = 0;
   p->off_qe = off; off = align_up(off + Bz * nh * 2 * d->r * sizeof(float), 256);
-  p->off_qt = off; off = align_up(off + Bz * nh * dc * sizeof(float), 256);
-  p->off_m = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
-  p->off_l = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
-  p->off_u = off;  off = align_up(off + Bz * ns * nh * dc * sizeof(float), 256);
+  if (decode_mfma_supported(*d)) {
+    // one work-group per (split, group of 32 heads, batch row); one group fills a compute unit
+    p->mfma = 1;
+    p->head_groups = (d->n_heads + 31) / 32;
+    int64_t ns = n_splits;
+    if (ns == 0) {
+      ns = (kComputeUnits + Bq * p->head_groups - 1) / (Bq * p->head_groups);
+      const int64_t cap = (seq + 31) / 32;
+      if (ns > cap) ns = cap;
+      if (ns > kMaxSplits) ns = kMaxSplits;
+      if (ns < 1) ns = 1;
+    }
+    p->n_splits = (int32_t)ns;
+    int64_t chunk = (seq + ns - 1) / ns;
+    chunk = (chunk + 31) / 32 * 32;
+    p->chunk = (int32_t)chunk;
+    const size_t np = Bz * (size_t)ns * p->head_groups;
+    p->off_qt = off; off = align_up(off + Bz * nh * dc * 2, 256);
+    p->off_m = off;  off = align_up(off + np * 32 * sizeof(float), 256);
+    p->off_l = off;  off = align_up(off + np * 32 * sizeof(float), 256);
+    p->off_u = off;  off = align_up(off + np * dc * 32 * sizeof(float), 256);
+  } else {
+    p->mfma = 0;
+    p->head_groups = 1;
+    p->n_splits = n_splits > 0 ? n_splits : auto_splits_generic(d, Bq, seq);
+    int64_t chunk = (seq + p->n_splits - 1) / p->n_splits;
+    if (chunk < 1) chunk = 1;
+    p->chunk = (int32_t)chunk;
+    const size_t ns = p->n_splits;
+    p->off_qt = off; off = align_up(off + Bz * nh * dc * sizeof(float), 256);
+    p->off_m = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
+    p->off_l = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
+    p->off_u = off;  off = align_up(off + Bz * ns * nh * dc * sizeof(float), 256);
+  }
   p->off_ubar = off;
   p->off_opart = off;
   p->off_cnt = off;
@@ -204,7 +230,8 @@ static int decode_impl(const elitekv_dims* dims, const void* q, const int32_t* q
   a.batch_stride_rows = batch_stride_rows; a.W_uk = W_uk; a.W_uv = W_uv; a.elite_idx = elite_idx;
   a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows; a.out = out; a.ws = (char*)ws;
   a.ev_before = (hipEvent_t)ev_before; a.ev_after = (hipEvent_t)ev_after;
-  const hipError_t e = launch_decode_generic(a, p, (hipStream_t)hip_stream);
+  const hipError_t e = p.mfma ? launch_decode_mfma(a, p, (hipStream_t)hip_stream)
+                             : launch_decode_generic(a, p, (hipStream_t)hip_stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
 }
 

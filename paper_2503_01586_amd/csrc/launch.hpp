@@ -74,6 +74,8 @@ struct MhaArgs {
 
 hipError_t launch_append_generic(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_generic(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
+bool decode_mfma_supported(const elitekv_dims& d);
+hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
 

@@ -97,6 +97,9 @@ DECODE_CASES = {
     "bf16_7b_12pct": (shape(64, 32, 128, 4, 768, "bf16"), [130, 64], [0, 3]),
     "bf16_13b": (shape(64, 40, 128, 8, 1920, "bf16"), [97, 160], [0, 2]),
     "bf16_small_heads": (shape(64, 8, 64, 4, 128, "bf16"), [70], [0, 2]),
+    "bf16_few_heads_256": (shape(64, 8, 64, 4, 256, "bf16"), [70, 33, 0], [0, 2]),
+    "bf16_two_head_groups": (shape(64, 40, 128, 8, 1536, "bf16"), [97, 160], [0, 2]),
+    "bf16_7b_longer": (shape(64, 32, 128, 8, 1536, "bf16"), [1500], [0, 1, 7, 47]),
 }
 
 
