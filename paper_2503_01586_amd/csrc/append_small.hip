@@ -1,0 +1,167 @@
+// Cache append for a handful of tokens (the per-step append of a decoding batch): the weights
+// [W_ke | W_dkv] are streamed from HBM exactly once, split over column blocks and over the
+// contraction dimension so that every compute unit pulls a share; a second small kernel sums
+// the contraction splits, applies the selective RoPE and writes the cache rows.
+//   (Section 3.1, cache contents of a RoPElite model; Section 3.2, c = x A^{kv}, W^k_{e,h}.)
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace ekv {
+
+constexpr int kAsThreads = 256;
+constexpr int kAsCols = 64;       // output columns per work-group: one 128-byte line of a bf16 weight row
+constexpr int kAsTokens = 8;      // tokens per work-group pass
+
+// grid (column blocks, contraction splits, token tiles)
+__global__ __launch_bounds__(kAsThreads) void append_small_kernel(
+    const bf16_t* __restrict__ x, int64_t T, const bf16_t* __restrict__ W_ke,
+    const bf16_t* __restrict__ W_dkv, float* __restrict__ partial, int d, int NE, int d_c, int kc) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // [kc][kAsTokens]
+  __shared__ float red[4][8][kAsTokens][8];                    // [wave][column chunk][token][8 cols]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rg = lane >> 3, cchunk = lane & 7;
+  const int N = NE + d_c;
+  const int n0 = blockIdx.x * kAsCols;
+  const int k0 = blockIdx.y * kc;
+  const int64_t t0 = (int64_t)blockIdx.z * kAsTokens;
+
+  for (int e = tid; e < kc * kAsTokens; e += kAsThreads) {
+    const int kk = e / kAsTokens, tt = e % kAsTokens;
+    const int64_t t = t0 + tt;
+    xs[e] = (t < T && k0 + kk < d) ? ld(x, t * d + k0 + kk) : 0.f;
+  }
+  __syncthreads();
+
+  const bf16_t* wbase;
+  int64_t wstride;
+  if (n0 < NE) { wbase = W_ke + n0 + cchunk * 8; wstride = NE; }
+  else { wbase = W_dkv + (n0 - NE) + cchunk * 8; wstride = d_c; }
+
+  float acc[kAsTokens][8];
+#pragma unroll
+  for (int t = 0; t < kAsTokens; ++t)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[t][i] = 0.f;
+
+  const int steps = kc / 32;
+#pragma unroll 4
+  for (int s = 0; s < steps; ++s) {
+    const int kk = s * 32 + wave * 8 + rg;
+    const int k = k0 + kk;
+    uint4 wv = make_uint4(0, 0, 0, 0);
+    if (k < d) wv = *reinterpret_cast<const uint4*>(wbase + (int64_t)k * wstride);
+    const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w};
+    float w[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      w[2 * i] = __uint_as_float(ww[i] << 16);
+      w[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
+    }
+    const float4 xa = *reinterpret_cast<const float4*>(xs + kk * kAsTokens);
+    const float4 xb = *reinterpret_cast<const float4*>(xs + kk * kAsTokens + 4);
+    const float xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+#pragma unroll
+    for (int t = 0; t < kAsTokens; ++t)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[t][i] = fmaf(xv[t], w[i], acc[t][i]);
+  }
+  // sum over the 8 row groups of the wave, then over the 4 waves
+#pragma unroll
+  for (int t = 0; t < kAsTokens; ++t)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float v = acc[t][i];
+      v += __shfl_xor(v, 8, kWave);
+      v += __shfl_xor(v, 16, kWave);
+      v += __shfl_xor(v, 32, kWave);
+      acc[t][i] = v;
+    }
+  if (rg == 0) {
+#pragma unroll
+    for (int t = 0; t < kAsTokens; ++t)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) red[wave][cchunk][t][i] = acc[t][i];
+  }
+  __syncthreads();
+  // 8 tokens x 64 columns = 512 sums, two per thread
+  for (int e = tid; e < kAsTokens * kAsCols; e += kAsThreads) {
+    const int tt = e / kAsCols, c = e % kAsCols;
+    const int64_t t = t0 + tt;
+    if (t < T) {
+      const float v = red[0][c >> 3][tt][c & 7] + red[1][c >> 3][tt][c & 7] + red[2][c >> 3][tt][c & 7] +
+                      red[3][c >> 3][tt][c & 7];
+      partial[((int64_t)blockIdx.y * T + t) * N + n0 + c] = v;
+    }
+  }
+}
+
+// grid (T, column blocks of 256): sum the contraction splits, rotate the elite pairs, store
+__global__ __launch_bounds__(256) void append_finish_kernel(
+    const float* __restrict__ partial, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot,
+    int64_t T, const int32_t* __restrict__ elite_idx, bf16_t* __restrict__ ke_plane,
+    bf16_t* __restrict__ c_plane, int64_t plane_rows, int n_h, int d_h, int r, int d_c, int ksplit,
+    double rope_base) {
+  const int NE = 2 * r * n_h, N = NE + d_c;
+  const int64_t t = blockIdx.x;
+  const int n = blockIdx.y * 256 + threadIdx.x;
+  const bool col_ok = n < N;
+  float mine = 0.f;
+  if (col_ok)
+    for (int s = 0; s < ksplit; ++s) mine += partial[((int64_t)s * T + t) * N + n];
+  const float other = __shfl_xor(mine, 1, kWave);
+  if (!col_ok) return;
+  const int64_t row = slot[t];
+  if (row < 0 || row >= plane_rows) return;
+  if (n < NE) {
+    const int h = n / (2 * r), j = (n % (2 * r)) >> 1;
+    int chunk = elite_idx[h * r + j];
+    chunk = min(max(chunk, 0), d_h / 2 - 1);
+    double sn, cs;
+    sincos((double)pos[t] * rope_theta(rope_base, chunk, d_h), &sn, &cs);
+    const float c = (float)cs, s = (float)sn;
+    const float o = (n & 1) ? (other * s + mine * c) : (mine * c - other * s);
+    st(ke_plane, row * NE + n, o);
+  } else {
+    st(c_plane, row * d_c + (n - NE), mine);
+  }
+}
+
+bool append_small_supported(const elitekv_dims& d, int64_t T) {
+  if (d.dtype != ELITEKV_BF16 || T > 64) return false;
+  const int NE = 2 * d.r * d.n_heads;
+  return NE % kAsCols == 0 && d.d_c % kAsCols == 0;
+}
+
+// contraction splits so that (column blocks x splits) is about two work-groups per compute unit
+static int append_small_ksplit(const elitekv_dims& d) {
+  const int blocks = (2 * d.r * d.n_heads + d.d_c) / kAsCols;
+  int ks = 1;
+  while (ks < 64 && blocks * ks < 512 && (d.d_model + ks * 2 - 1) / (ks * 2) >= 64) ks <<= 1;
+  return ks;
+}
+
+size_t append_small_workspace(const elitekv_dims& d, int64_t T) {
+  return (size_t)append_small_ksplit(d) * (size_t)T * (size_t)(2 * d.r * d.n_heads + d.d_c) * sizeof(float);
+}
+
+hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  const int NE = 2 * d.r * d.n_heads, N = NE + d.d_c;
+  const int ks = append_small_ksplit(d);
+  int kc = (d.d_model + ks - 1) / ks;
+  kc = (kc + 31) / 32 * 32;
+  float* partial = (float*)a.ws;
+  const dim3 grid(N / kAsCols, ks, (unsigned)((a.T + kAsTokens - 1) / kAsTokens));
+  const size_t sm = (size_t)kc * kAsTokens * sizeof(float);
+  append_small_kernel<<<grid, kAsThreads, sm, stream>>>((const bf16_t*)a.x, a.T, (const bf16_t*)a.W_ke,
+                                                        (const bf16_t*)a.W_dkv, partial, d.d_model, NE,
+                                                        d.d_c, kc);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  append_finish_kernel<<<dim3((unsigned)a.T, (N + 255) / 256), 256, 0, stream>>>(
+      partial, a.pos, a.slot, a.T, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
+      d.n_heads, d.head_dim, d.r, d.d_c, ks, d.rope_base);
+  return hipGetLastError();
+}
+
+}  // namespace ekv

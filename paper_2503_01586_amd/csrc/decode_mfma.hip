@@ -37,9 +37,9 @@ struct AttnMfmaParams {
   const float* qe;        // [B, n_h, 2r]   rotated, scaled elite query
   const bf16_t* qt;       // [B, n_h, d_c]  absorbed, scaled latent query
   const int32_t* seq_len;
-  float* part_m;          // [B, n_splits, HG, 32]
-  float* part_l;          // [B, n_splits, HG, 32]
-  float* part_u;          // [B, n_splits, HG, d_c, 32]
+  float* part_m;          // [B, n_splits, HG*32]        split maxima (log2 domain)
+  float* part_l;          // [B, n_splits, HG*32]        split sums
+  bf16_t* part_u;         // [B, n_splits, HG*32, d_c]   split latent accumulators, head-major
   int n_h, d_c, n_splits, chunk, head_groups;
   int64_t max_seq_len, batch_stride_rows, plane_rows;
 };
@@ -96,12 +96,12 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   len = max(len, (int64_t)0);
   const int64_t t0 = (int64_t)split * p.chunk;
   const int64_t t_end = min(t0 + p.chunk, len);
-  const int64_t pidx = ((int64_t)b * p.n_splits + split) * p.head_groups + hg;
+  const int64_t pidx = ((int64_t)b * p.n_splits + split) * (p.head_groups * 32) + hg * 32;
 
   if (t0 >= t_end) {   // empty split: the merge skips it (l == 0)
     if (wave == 0 && g == 0) {
-      p.part_m[pidx * 32 + n] = -INFINITY;
-      p.part_l[pidx * 32 + n] = 0.f;
+      p.part_m[pidx + n] = -INFINITY;
+      p.part_l[pidx + n] = 0.f;
     }
     return;
   }
@@ -299,136 +299,33 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   // ---- write this split's partial (m, l, U)
   const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
   if (wave == 0 && g == 0) {
-    p.part_m[pidx * 32 + n] = m_run;
-    p.part_l[pidx * 32 + n] = head_ok ? l_tot : 0.f;
+    p.part_m[pidx + n] = m_run;
+    p.part_l[pidx + n] = head_ok ? l_tot : 0.f;
   }
-  float* up = p.part_u + pidx * (int64_t)p.d_c * 32 + n;
+  // U goes out head-major in bf16.  The accumulators hold, per lane, one head and scattered
+  // columns; they are transposed through LDS (free now) so that global stores are row-contiguous.
+  constexpr int TSTR = DC_W * 2 + 16;                       // bytes per head row in LDS
+  static_assert(NW * 32 * TSTR <= L::LDS_BYTES, "transpose staging exceeds the LDS allocation");
+  __syncthreads();                                          // every wave is done with its tile slice
+  char* tt = smem + wave * (32 * TSTR);
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int col = wave * DC_W + ct * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-      up[(int64_t)col * 32] = uacc[ct][v];
+    for (int j = 0; j < 4; ++j) {
+      uint2 pk;
+      pk.x = (uint32_t)f32_to_bf16_bits(uacc[ct][4 * j]) | ((uint32_t)f32_to_bf16_bits(uacc[ct][4 * j + 1]) << 16);
+      pk.y = (uint32_t)f32_to_bf16_bits(uacc[ct][4 * j + 2]) | ((uint32_t)f32_to_bf16_bits(uacc[ct][4 * j + 3]) << 16);
+      *reinterpret_cast<uint2*>(tt + n * TSTR + (ct * 32 + 8 * j + 4 * g) * 2) = pk;
     }
   }
-}
-
-// ---------------------------------------------------------------------------------------------
-// query preparation for the MFMA path: rotated elite query (fp32) and absorbed latent query (bf16)
-// ---------------------------------------------------------------------------------------------
-constexpr int kPrepThreads = 256;
-
-__global__ __launch_bounds__(kPrepThreads) void qprep_mfma_kernel(
-    const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos, const bf16_t* __restrict__ W_uk,
-    const int32_t* __restrict__ elite_idx, float* __restrict__ qe, bf16_t* __restrict__ qt, int n_h,
-    int d_h, int r, int d_c, double rope_base, float scale_log2e) {
-  __shared__ float q_ne[256];
-  __shared__ int is_elite[128];
-  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const int nd = d_h - 2 * r;
-  const bf16_t* qrow = q + ((int64_t)b * n_h + h) * d_h;
-  for (int i = tid; i < d_h / 2; i += kPrepThreads) is_elite[i] = 0;
-  __syncthreads();
-  for (int j = tid; j < r; j += kPrepThreads) {
-    const int i = elite_idx[h * r + j];
-    if (i >= 0 && i < d_h / 2) is_elite[i] = 1;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    int cnt = 0;
-    for (int i = 0; i < d_h / 2; ++i) {
-      if (!is_elite[i]) {
-        if (cnt + 1 < nd) {
-          q_ne[cnt] = ld(qrow, 2 * i) * scale_log2e;
-          q_ne[cnt + 1] = ld(qrow, 2 * i + 1) * scale_log2e;
-        }
-        cnt += 2;
-      }
-    }
-    for (; cnt < nd; ++cnt) q_ne[cnt] = 0.f;
-  }
-  for (int j = tid; j < r; j += kPrepThreads) {
-    int i = elite_idx[h * r + j];
-    i = min(max(i, 0), d_h / 2 - 1);
-    double sn, cs;
-    sincos((double)q_pos[b] * rope_theta(rope_base, i, d_h), &sn, &cs);
-    const float u = ld(qrow, 2 * i), v = ld(qrow, 2 * i + 1), c = (float)cs, s = (float)sn;
-    float* o = qe + ((int64_t)b * n_h + h) * 2 * r;
-    o[2 * j] = (u * c - v * s) * scale_log2e;
-    o[2 * j + 1] = (u * s + v * c) * scale_log2e;
-  }
-  __syncthreads();
-  bf16_t* qt_row = qt + ((int64_t)b * n_h + h) * d_c;
-  for (int k = tid; k < d_c; k += kPrepThreads) {
-    const bf16_t* w = W_uk + ((int64_t)k * n_h + h) * nd;
-    float acc = 0.f;
-    for (int j = 0; j < nd; ++j) acc = fmaf(q_ne[j], ld(w, j), acc);
-    st(qt_row, k, acc);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// merge of the split partials + W_uv up-projection for the MFMA path's partial layout
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void merge_upproj_mfma_kernel(
-    const float* __restrict__ part_m, const float* __restrict__ part_l,
-    const float* __restrict__ part_u, const bf16_t* __restrict__ W_uv, bf16_t* __restrict__ out,
-    int n_h, int d_h, int d_c, int n_splits, int head_groups) {
-  extern __shared__ float smf[];
-  float* ubar = smf;              // [d_c]
-  float* w = ubar + d_c;          // [n_splits]
-  float* red = w + n_splits;      // [256]
-  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const int hg = h >> 5, hn = h & 31;
-  const int64_t pstride = (int64_t)head_groups;              // partial index step per split
-  const int64_t p0 = (int64_t)b * n_splits * head_groups + hg;
-
-  float m = -INFINITY;
-  for (int s = tid; s < n_splits; s += 256) m = fmaxf(m, part_m[(p0 + s * pstride) * 32 + hn]);
-  red[tid] = m;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if (tid < o) red[tid] = fmaxf(red[tid], red[tid + o]);
-    __syncthreads();
-  }
-  m = red[0];
-  __syncthreads();
-  float lsum = 0.f;
-  for (int s = tid; s < n_splits; s += 256) {
-    const float ls = part_l[(p0 + s * pstride) * 32 + hn];
-    const float ws = (ls > 0.f) ? exp2f(part_m[(p0 + s * pstride) * 32 + hn] - m) : 0.f;
-    w[s] = ws;
-    lsum += ws * ls;
-  }
-  red[tid] = lsum;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
-    if (tid < o) red[tid] += red[tid + o];
-    __syncthreads();
-  }
-  const float Lsum = red[0];
-  const float inv = (Lsum > 0.f) ? 1.f / Lsum : 0.f;
-  __syncthreads();
-  for (int k = tid; k < d_c; k += 256) {
-    float a = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-      const float ws = w[s];
-      if (ws != 0.f) a = fmaf(ws, part_u[((p0 + s * pstride) * d_c + k) * 32 + hn], a);
-    }
-    ubar[k] = a * inv;
-  }
-  __syncthreads();
-  const int groups = 256 / d_h;
-  const int j = tid % d_h, gq = tid / d_h;
-  float a = 0.f;
-  if (gq < groups)
-    for (int k = gq; k < d_c; k += groups) a = fmaf(ubar[k], ld(W_uv, ((int64_t)k * n_h + h) * d_h + j), a);
-  red[tid] = a;
-  __syncthreads();
-  if (tid < d_h) {
-    float tot = 0.f;
-    for (int gg = 0; gg < groups; ++gg) tot += red[gg * d_h + tid];
-    st(out, ((int64_t)b * n_h + h) * d_h + tid, tot);
+  constexpr int CPRW = DC_W * 2 / 16;                       // 16-byte chunks per head row
+  char* ubase = reinterpret_cast<char*>(p.part_u) + (pidx * (int64_t)p.d_c + (int64_t)wave * DC_W) * 2;
+#pragma unroll
+  for (int i = 0; i < 32 * CPRW / 64; ++i) {
+    const int idx = i * 64 + lane;
+    const int row = idx / CPRW, ch = idx % CPRW;
+    const uint4 v = *reinterpret_cast<const uint4*>(tt + row * TSTR + ch * 16);
+    *reinterpret_cast<uint4*>(ubase + (int64_t)row * p.d_c * 2 + ch * 16) = v;
   }
 }
 
@@ -450,7 +347,7 @@ static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t 
 
 bool decode_mfma_supported(const elitekv_dims& d) {
   if (d.dtype != ELITEKV_BF16) return false;
-  if (d.head_dim > 256 || (d.head_dim - 2 * d.r) % 8) return false;
+  if ((d.head_dim != 128 && d.head_dim != 64) || (d.head_dim - 2 * d.r) % 8) return false;
   const int two_r = 2 * d.r;
   if (two_r != 8 && two_r != 16) return false;
   return d.d_c == 1536 || d.d_c == 768 || d.d_c == 256;
@@ -465,18 +362,16 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.ke_plane = (const bf16_t*)a.ke_plane; prm.c_plane = (const bf16_t*)a.c_plane;
   prm.qe = qe; prm.qt = qt; prm.seq_len = a.seq_len;
   prm.part_m = (float*)(a.ws + p.off_m); prm.part_l = (float*)(a.ws + p.off_l);
-  prm.part_u = (float*)(a.ws + p.off_u);
+  prm.part_u = (bf16_t*)(a.ws + p.off_u);
   prm.n_h = n_h; prm.d_c = d_c; prm.n_splits = p.n_splits; prm.chunk = p.chunk;
   prm.head_groups = p.head_groups; prm.max_seq_len = a.max_seq_len;
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
-  const float scale_log2e = kLog2e / sqrtf((float)d_h);
 
-  qprep_mfma_kernel<<<dim3(n_h, (unsigned)a.B), kPrepThreads, 0, stream>>>(
-      (const bf16_t*)a.q, a.q_pos, (const bf16_t*)a.W_uk, a.elite_idx, qe, qt, n_h, d_h, r, d_c,
-      d.rope_base, scale_log2e);
+  hipError_t e = launch_qprep_rows(a, qe, qt, (uint32_t*)(a.ws + p.off_cnt), stream);
+  if (e != hipSuccess) return e;
 
   if (a.ev_before) (void)hipEventRecord(a.ev_before, stream);
-  hipError_t e = hipErrorInvalidValue;
+  e = hipErrorInvalidValue;
   const int two_r = 2 * r;
 #define EKV_CASE(DC, NWV, DCW)                                                        \
   if (d_c == DC) {                                                                    \
@@ -490,11 +385,7 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   if (e != hipSuccess) return e;
   if (a.ev_after) (void)hipEventRecord(a.ev_after, stream);
 
-  const size_t sm = sizeof(float) * (size_t)(d_c + p.n_splits + 256);
-  merge_upproj_mfma_kernel<<<dim3(n_h, (unsigned)a.B), 256, sm, stream>>>(
-      prm.part_m, prm.part_l, prm.part_u, (const bf16_t*)a.W_uv, (bf16_t*)a.out, n_h, d_h, d_c,
-      p.n_splits, p.head_groups);
-  return hipGetLastError();
+  return launch_merge_up(a, p, stream);
 }
 
 }  // namespace ekv

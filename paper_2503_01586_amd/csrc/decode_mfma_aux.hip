@@ -1,0 +1,288 @@
+// The kernels around the bf16 MFMA attention kernel:
+//   qprep_rows   : rotated elite query + W_uk absorbed into the rest of the query
+//                  (Section 3.1 score equation, first sum; Section 5, absorption of B^k)
+//   merge_up     : exact log-sum-exp merge of the sequence splits, normalisation, and the W_uv
+//                  up-projection of a chunk of latent columns (Section 3.2, B^v_J)
+//   out_reduce   : sum of the up-projection partials over the latent chunks, cast to bf16
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace ekv {
+
+// ---------------------------------------------------------------------------------------------
+// qprep_rows.  W_uk [d_c, n_h, nd] is a row-major matrix with one row of nd = d_h - 2r weights
+// per (latent column k, head h); thread <-> row, so a work-group streams 256 consecutive rows.
+//   qt[b, h, k] = scale * sum_j q[b, h, nonelite_j] * W_uk[k, h, j]
+// The compacted non-elite query of the batch tile sits in LDS (bf16, as given).
+// ---------------------------------------------------------------------------------------------
+constexpr int kQpThreads = 256;
+constexpr int kQpBatchTile = 8;
+
+__global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
+    const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos, const bf16_t* __restrict__ W_uk,
+    const int32_t* __restrict__ elite_idx, float* __restrict__ qe, bf16_t* __restrict__ qt,
+    uint32_t* __restrict__ counters, int B, int n_h, int d_h, int r, int d_c, double rope_base, float scale_log2e) {
+  extern __shared__ __attribute__((aligned(16))) char qsm[];
+  const int nd = d_h - 2 * r;
+  const int ndp = nd + 8;                                  // padded row: breaks the LDS bank period
+  const int half = d_h / 2;
+  uint16_t* qne = reinterpret_cast<uint16_t*>(qsm);        // [BT][n_h][ndp] bf16 bits
+  int16_t* nepos = reinterpret_cast<int16_t*>(qsm + (size_t)kQpBatchTile * n_h * ndp * 2);  // [n_h][half]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b0 = blockIdx.y * kQpBatchTile;
+  const int bt_n = min(kQpBatchTile, B - b0);
+
+  // position of every non-elite chunk inside the compacted query (-1 for elite chunks); half <= 64
+  for (int h = wave; h < n_h; h += kQpThreads / 64) {
+    bool el = false;
+    for (int j = 0; j < r; ++j) el |= (elite_idx[h * r + j] == lane);
+    const bool live = lane < half && !el;
+    const uint64_t mask = __ballot(live);
+    const int pos = __popcll(mask & ((1ull << lane) - 1ull));
+    if (lane < half) nepos[h * half + lane] = live ? (int16_t)pos : (int16_t)-1;
+  }
+  __syncthreads();
+  const uint32_t* q32 = reinterpret_cast<const uint32_t*>(q);
+  for (int e = tid; e < bt_n * n_h * half; e += kQpThreads) {
+    const int c = e % half, h = (e / half) % n_h, bt = e / (half * n_h);
+    const int pos = nepos[h * half + c];
+    if (pos >= 0)
+      reinterpret_cast<uint32_t*>(qne + ((size_t)bt * n_h + h) * ndp)[pos] =
+          q32[(((int64_t)(b0 + bt) * n_h + h) * d_h) / 2 + c];
+  }
+  // the rotated elite query is written by the first column block only; it also clears the
+  // arrival counters the merge kernel of this call will use
+  if (blockIdx.x == 0) {
+    for (int e = tid; e < bt_n * n_h; e += kQpThreads) counters[(int64_t)b0 * n_h + e] = 0u;
+    for (int e = tid; e < bt_n * n_h * r; e += kQpThreads) {
+      const int j = e % r, h = (e / r) % n_h, b = b0 + e / (r * n_h);
+      int i = elite_idx[h * r + j];
+      i = min(max(i, 0), half - 1);
+      double sn, cs;
+      sincos((double)q_pos[b] * rope_theta(rope_base, i, d_h), &sn, &cs);
+      const bf16_t* qrow = q + ((int64_t)b * n_h + h) * d_h;
+      const float u = ld(qrow, 2 * i), v = ld(qrow, 2 * i + 1), c = (float)cs, s = (float)sn;
+      float* o = qe + ((int64_t)b * n_h + h) * 2 * r;
+      o[2 * j] = (u * c - v * s) * scale_log2e;
+      o[2 * j + 1] = (u * s + v * c) * scale_log2e;
+    }
+  }
+  __syncthreads();
+
+  const int64_t row = (int64_t)blockIdx.x * kQpThreads + tid;
+  if (row >= (int64_t)d_c * n_h) return;
+  const int k = (int)(row / n_h), h = (int)(row % n_h);
+  const uint4* wrow = reinterpret_cast<const uint4*>(W_uk + row * nd);
+  float acc[kQpBatchTile];
+#pragma unroll
+  for (int bt = 0; bt < kQpBatchTile; ++bt) acc[bt] = 0.f;
+  const int nchunk = nd / 8;
+  for (int c = 0; c < nchunk; ++c) {
+    const uint4 wv = wrow[c];
+    const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w};
+    float w[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      w[2 * i] = __uint_as_float(ww[i] << 16);
+      w[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
+    }
+#pragma unroll
+    for (int bt = 0; bt < kQpBatchTile; ++bt) {
+      if (bt < bt_n) {
+        const uint4 qv = *reinterpret_cast<const uint4*>(qne + ((size_t)bt * n_h + h) * ndp + 8 * c);
+        const uint32_t qq[4] = {qv.x, qv.y, qv.z, qv.w};
+        float a = acc[bt];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a = fmaf(w[2 * i], __uint_as_float(qq[i] << 16), a);
+          a = fmaf(w[2 * i + 1], __uint_as_float(qq[i] & 0xffff0000u), a);
+        }
+        acc[bt] = a;
+      }
+    }
+  }
+#pragma unroll
+  for (int bt = 0; bt < kQpBatchTile; ++bt)
+    if (bt < bt_n) st(qt, ((int64_t)(b0 + bt) * n_h + h) * d_c + k, acc[bt] * scale_log2e);
+}
+
+hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, uint32_t* counters,
+                             hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  const int nd = d.head_dim - 2 * d.r;
+  const size_t sm = (size_t)kQpBatchTile * d.n_heads * (nd + 8) * 2 + (size_t)d.n_heads * (d.head_dim / 2) * 2;
+  const int64_t rows = (int64_t)d.d_c * d.n_heads;
+  const dim3 grid((unsigned)((rows + kQpThreads - 1) / kQpThreads),
+                  (unsigned)((a.B + kQpBatchTile - 1) / kQpBatchTile));
+  if (sm > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&qprep_rows_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    if (e != hipSuccess) return e;
+  }
+  qprep_rows_kernel<<<grid, kQpThreads, sm, stream>>>(
+      (const bf16_t*)a.q, a.q_pos, (const bf16_t*)a.W_uk, a.elite_idx, qe, qt, counters, (int)a.B, d.n_heads,
+      d.head_dim, d.r, d.d_c, d.rope_base, kLog2e / sqrtf((float)d.head_dim));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// merge_up.  One work-group per (chunk of CW latent columns, head, batch row):
+//   * exact log-sum-exp merge of the sequence splits for this head (weights from m, l),
+//   * the merged, normalised latent of the chunk's columns,
+//   * its contribution to the up-projection  o[h, :] = ubar[h, :] W_uv[:, h, :]   (B^v_J),
+//   * the last chunk of a head to finish adds the chunk partials in a fixed order and writes out.
+// Partials: part_m / part_l [P, NHP], part_u [P, NHP, d_c] bf16 with P = b * n_splits + s.
+// ---------------------------------------------------------------------------------------------
+template <int CW, int DH>
+__global__ __launch_bounds__(256) void merge_up_kernel(
+    const float* __restrict__ part_m, const float* __restrict__ part_l,
+    const bf16_t* __restrict__ part_u, const bf16_t* __restrict__ W_uv, float* __restrict__ opart,
+    uint32_t* __restrict__ counters, bf16_t* __restrict__ out, int n_h, int nhp, int d_c, int n_splits) {
+  constexpr int LPR = CW / 8;              // lanes that cover one split's row chunk (16 bytes each)
+  constexpr int NG = 256 / LPR;            // split groups working in parallel
+  constexpr int LPW = DH / 8;              // lanes that cover one W_uv row
+  constexpr int RPI = 64 / LPW;            // W_uv rows per wave instruction
+  extern __shared__ __attribute__((aligned(16))) float msm[];
+  float* wsp = msm;                        // [n_splits] merge weights of this head
+  float* red = wsp + n_splits;             // [256] scratch; later [NG][CW] and [4][DH]
+  float* big = red + 256;                  // [NG][CW]
+  float* ubar = big + NG * CW;             // [CW]
+  __shared__ int is_last;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+  const int n_chunks = gridDim.x;
+  const int64_t p0 = (int64_t)b * n_splits;
+
+  float m = -INFINITY;
+  for (int s = tid; s < n_splits; s += 256) m = fmaxf(m, part_m[(p0 + s) * nhp + head]);
+  m = wave_max(m);
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float lsum = 0.f;
+  for (int s = tid; s < n_splits; s += 256) {
+    const float ls = part_l[(p0 + s) * nhp + head];
+    const float w = (ls > 0.f) ? exp2f(part_m[(p0 + s) * nhp + head] - m) : 0.f;
+    wsp[s] = w;
+    lsum += w * ls;
+  }
+  lsum = wave_sum(lsum);
+  if (lane == 0) red[wave] = lsum;
+  __syncthreads();
+  const float Lsum = (red[0] + red[1]) + (red[2] + red[3]);
+  const float inv = (Lsum > 0.f) ? 1.f / Lsum : 0.f;
+
+  // merged latent of this chunk: split groups run in parallel, then a fixed-order sum
+  const int cl = tid % LPR, sg = tid / LPR;
+  const int col0 = chunk * CW;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  if (sg < NG) {
+    const bf16_t* ub = part_u + (p0 * nhp + head) * (int64_t)d_c + col0 + cl * 8;
+    const int64_t sstep = (int64_t)nhp * d_c;
+#pragma unroll 4
+    for (int s = sg; s < n_splits; s += NG) {
+      // an empty split has weight 0 and an unwritten accumulator: load it anyway (the loads
+      // stay independent of the weights) but keep it out of the sum
+      const float w = wsp[s];
+      const bool live = w != 0.f;
+      const uint4 uv = *reinterpret_cast<const uint4*>(ub + s * sstep);
+      const uint32_t uu[4] = {uv.x, uv.y, uv.z, uv.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = fmaf(w, __uint_as_float(uu[i] << 16), acc[2 * i]);
+        const float hi = fmaf(w, __uint_as_float(uu[i] & 0xffff0000u), acc[2 * i + 1]);
+        acc[2 * i] = live ? lo : acc[2 * i];
+        acc[2 * i + 1] = live ? hi : acc[2 * i + 1];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) big[sg * CW + cl * 8 + i] = acc[i];
+  }
+  __syncthreads();
+  for (int c = tid; c < CW; c += 256) {
+    float a = 0.f;
+#pragma unroll 4
+    for (int gq = 0; gq < NG; ++gq) a += big[gq * CW + c];
+    ubar[c] = a * inv;
+  }
+  __syncthreads();
+
+  // up-projection of this chunk: rows k = col0 + kk of W_uv[:, head, :]
+  const int jl = lane % LPW, rr = lane / LPW;
+  float o[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = 0.f;
+  const bf16_t* wb = W_uv + ((int64_t)col0 * n_h + head) * DH + jl * 8;
+#pragma unroll 4
+  for (int kk = wave * RPI + rr; kk < CW; kk += 4 * RPI) {
+    const float u = ubar[kk];
+    const uint4 wv = *reinterpret_cast<const uint4*>(wb + (int64_t)kk * n_h * DH);
+    const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = fmaf(u, __uint_as_float(ww[i] << 16), o[2 * i]);
+      o[2 * i + 1] = fmaf(u, __uint_as_float(ww[i] & 0xffff0000u), o[2 * i + 1]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float v = o[i];
+#pragma unroll
+    for (int off = LPW; off < 64; off <<= 1) v += __shfl_xor(v, off, kWave);
+    o[i] = v;
+  }
+  float* wred = big;                         // [4][DH]
+  if (rr == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wred[wave * DH + jl * 8 + i] = o[i];
+  }
+  __syncthreads();
+  float* op = opart + (((int64_t)b * n_h + head) * n_chunks + chunk) * DH;
+  if (tid < DH) op[tid] = (wred[tid] + wred[DH + tid]) + (wred[2 * DH + tid] + wred[3 * DH + tid]);
+
+  // the last chunk of this (batch row, head) to arrive finishes the output row
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t old = atomicAdd(&counters[(int64_t)b * n_h + head], 1u);
+    is_last = (old == (uint32_t)(n_chunks - 1));
+  }
+  __syncthreads();
+  if (is_last) {
+    __threadfence();
+    if (tid < DH) {
+      const float* pp = opart + ((int64_t)b * n_h + head) * n_chunks * DH + tid;
+      float a = 0.f;
+      for (int c = 0; c < n_chunks; ++c) a += __builtin_nontemporal_load(pp + (int64_t)c * DH);
+      st(out, ((int64_t)b * n_h + head) * DH + tid, a);
+    }
+  }
+}
+
+hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  const float* pm = (const float*)(a.ws + p.off_m);
+  const float* pl = (const float*)(a.ws + p.off_l);
+  const bf16_t* pu = (const bf16_t*)(a.ws + p.off_u);
+  float* opart = (float*)(a.ws + p.off_opart);
+  uint32_t* cnt = (uint32_t*)(a.ws + p.off_cnt);
+  const int cw = p.up_cw;
+  const dim3 grid(d.d_c / cw, d.n_heads, (unsigned)a.B);
+  const int nhp = p.head_groups * 32;
+#define EKV_MU(CW, DH)                                                                              \
+  do {                                                                                              \
+    const size_t sm = sizeof(float) * ((size_t)p.n_splits + 256 + (size_t)(256 / (CW / 8)) * CW + CW); \
+    merge_up_kernel<CW, DH><<<grid, 256, sm, stream>>>(pm, pl, pu, (const bf16_t*)a.W_uv, opart, cnt, \
+                                                       (bf16_t*)a.out, d.n_heads, nhp, d.d_c,        \
+                                                       p.n_splits);                                 \
+  } while (0)
+  if (cw == 192) { if (d.head_dim == 128) EKV_MU(192, 128); else EKV_MU(192, 64); }
+  else { if (d.head_dim == 128) EKV_MU(64, 128); else EKV_MU(64, 64); }
+#undef EKV_MU
+  return hipGetLastError();
+}
+
+}  // namespace ekv

@@ -41,6 +41,7 @@ static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_
   if (st) return st;
   if (B < 0 || max_seq < 0 || n_splits < 0) return ELITEKV_EINVAL;
   if (d->d_c > 4096 || d->head_dim > 256 || n_splits > kMaxSplits) return ELITEKV_EUNSUPPORTED;
+  if (B > 65535) return ELITEKV_EUNSUPPORTED;
   memset(p, 0, sizeof(*p));
   const int64_t Bq = B > 0 ? B : 1;
   const int64_t seq = max_seq > 0 ? max_seq : 1;
@@ -67,7 +68,12 @@ static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_
     p->off_qt = off; off = align_up(off + Bz * nh * dc * 2, 256);
     p->off_m = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_l = off;  off = align_up(off + np * 32 * sizeof(float), 256);
-    p->off_u = off;  off = align_up(off + np * dc * 32 * sizeof(float), 256);
+    p->off_u = off;  off = align_up(off + np * 32 * dc * 2, 256);
+    p->up_cw = (d->d_c % 192 == 0) ? 192 : 64;
+    p->off_opart = off;
+    off = align_up(off + Bz * nh * (size_t)(d->d_c / p->up_cw) * d->head_dim * sizeof(float), 256);
+    p->off_cnt = off;
+    off = align_up(off + Bz * nh * sizeof(uint32_t), 256);
   } else {
     p->mfma = 0;
     p->head_groups = 1;
@@ -81,9 +87,6 @@ static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_
     p->off_l = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
     p->off_u = off;  off = align_up(off + Bz * ns * nh * dc * sizeof(float), 256);
   }
-  p->off_ubar = off;
-  p->off_opart = off;
-  p->off_cnt = off;
   p->total = off;
   return ELITEKV_OK;
 }
@@ -164,6 +167,7 @@ int elitekv_validate_elite_idx(const elitekv_dims* dims, const int32_t* idx_host
 
 size_t elitekv_append_workspace_bytes(const elitekv_dims* dims, int64_t T) {
   if (check_dims(dims) || T < 0) return 0;
+  if (T > 0 && append_small_supported(*dims, T)) return align_up(append_small_workspace(*dims, T), 256);
   return 0;
 }
 
@@ -188,7 +192,8 @@ int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, 
   a.dims = *dims; a.x = x; a.pos = pos; a.slot = slot; a.T = T; a.W_ke = W_ke; a.W_dkv = W_dkv;
   a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows;
   a.ws = (char*)ws;
-  const hipError_t e = launch_append_generic(a, (hipStream_t)hip_stream);
+  const hipError_t e = append_small_supported(*dims, T) ? launch_append_small(a, (hipStream_t)hip_stream)
+                                                        : launch_append_generic(a, (hipStream_t)hip_stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
 }
 

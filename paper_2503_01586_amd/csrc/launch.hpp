@@ -15,6 +15,7 @@ struct DecodePlan {
   int32_t chunk;        // cached tokens per split
   int32_t mfma;         // 1: bf16 MFMA kernels, 0: generic VALU kernels
   int32_t head_groups;  // MFMA path: groups of up to 32 heads
+  int32_t up_cw;        // MFMA path: latent columns per merge/up-projection work-group
   size_t off_qe;        // rotated, scaled elite query      fp32 [B, n_h, 2r]
   size_t off_qt;        // absorbed, scaled latent query    fp32 [B, n_h, d_c] (generic) / bf16 (mfma)
   size_t off_m;         // split maxima (log2 domain)       fp32 [B, n_splits, n_h_pad]
@@ -73,8 +74,15 @@ struct MhaArgs {
 };
 
 hipError_t launch_append_generic(const AppendArgs& a, hipStream_t stream);
+bool append_small_supported(const elitekv_dims& d, int64_t T);
+size_t append_small_workspace(const elitekv_dims& d, int64_t T);
+hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_generic(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 bool decode_mfma_supported(const elitekv_dims& d);
+struct bf16_t;
+hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, uint32_t* counters,
+                             hipStream_t stream);
+hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);

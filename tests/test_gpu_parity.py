@@ -31,6 +31,9 @@ APPEND_CASES = {
     "bf16_7b_12pct": (shape(4096, 32, 128, 4, 768, "bf16"), 33, 2047),
     "bf16_13b_rows": (shape(5120, 40, 128, 8, 1920, "bf16"), 19, 8191),
     "bf16_one_token": (shape(512, 8, 64, 4, 128, "bf16"), 1, 77),
+    "bf16_7b_decode_step": (shape(4096, 32, 128, 8, 1536, "bf16"), 8, 32767),
+    "bf16_7b_64_tokens": (shape(4096, 32, 128, 8, 1536, "bf16"), 64, 4095),
+    "bf16_odd_hidden": (shape(1000, 32, 128, 8, 1536, "bf16"), 5, 100),
 }
 
 
