@@ -5,17 +5,18 @@
 // share the latent c), so each cached row is read from HBM exactly once and serves both the key
 // role (scores) and the value role (latent accumulation):
 //
-//   scores   S^T[token, head] = C[token, :] . Qt[head, :]        A = latent tile, B = absorbed query
-//            + per-head elite term  ke[token, head, :] . qe[head, :]   (VALU, 2r-wide)
+//   scores   S^T[token, head] = C[token, :] . Qt[head, :]      16x16x32 MFMA, A = latent tile rows,
+//            B = absorbed query;  + per-head elite term ke[token, head, :] . qe[head, :]  (VALU)
 //            (Section 3.1 score equation with W_uk absorbed into the query, Section 5)
 //   softmax  online, in the log2 domain (the query is pre-scaled by log2(e)/sqrt(d_h))
-//   values   U^T[col, head] += C^T[col, token] . P^T[token, head]   A = the SAME tile read
-//            transposed from LDS, B = the probabilities straight from the score registers
+//   values   U^T[col, head] += C^T[col, token] . P^T[token, head]   32x32x16 MFMA, A = the SAME
+//            tile read transposed from LDS, B = the probabilities
 //
-// The latent dimension is split over the NW waves of the group (DC_W columns each): a wave holds
-// its slice of the absorbed query and of U in registers, computes partial scores over its slice,
-// and the waves exchange partial scores through LDS once per 32-token tile.  Tiles are brought in
-// with direct global->LDS loads (16 bytes per lane), one private LDS slice per wave.
+// The latent dimension is split over the NW waves of the group (DC_W columns each): a wave keeps
+// its slice of the absorbed query and of U in registers and computes partial scores over its
+// slice; the waves exchange partial scores through LDS once per 16-token tile.  Tiles come in
+// through direct global->LDS loads into a private slice per wave, double-buffered: the loads of
+// tile i+1 are in flight while tile i is computed.
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -29,7 +30,7 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
 
-constexpr int kTile = 32;   // cached tokens per tile = the MFMA M dimension
+constexpr int kTile = 16;   // cached tokens per tile
 
 struct AttnMfmaParams {
   const bf16_t* ke_plane;
@@ -44,58 +45,95 @@ struct AttnMfmaParams {
   int64_t max_seq_len, batch_stride_rows, plane_rows;
 };
 
-// LDS layout of one wave's tile slice (32 tokens x DC_W latent columns, bf16): blocks of
+// LDS layout of one wave's tile slice (16 tokens x DC_W latent columns, bf16): blocks of
 // 8 rows x 128 bytes (1 KiB, exactly what one direct-to-LDS load of 64 lanes x 16 bytes fills),
 // block (rb, cb) at ((rb * NCB) + cb) KiB.  Inside a block the 16-byte chunk index is XOR-ed with
 // swz(row) = ((row & 3) << 1) | ((row >> 2) & 1): eight rows read at one logical chunk hit eight
 // different bank groups (row-wise b128 reads), and the 4 rows x 32 bytes a transposed b64 read
 // covers hit four different 32-byte bank groups.
-template <int NW, int DC_W>
+template <int NW, int DC_W, int TWO_R>
 struct AttnMfmaLayout {
   static_assert(DC_W % 64 == 0, "a wave's latent slice must be a whole number of 128-byte blocks");
-  static_assert(16 % NW == 0, "the 16 score registers are divided evenly among the waves");
-  static constexpr int KS = DC_W / 16;                      // score k-steps per wave
+  static_assert(NW == 2 || NW == 4 || NW == 8, "16 tokens are divided evenly among the waves");
+  static constexpr int KS = DC_W / 32;                      // score k-steps per wave (K = 32)
   static constexpr int CT = DC_W / 32;                      // 32-column accumulator tiles per wave
   static constexpr int NCB = DC_W / 64;                     // 128-byte column blocks per row
-  static constexpr int NLOAD = 4 * NCB;                     // direct-to-LDS loads per tile per wave
+  static constexpr int NLOAD = 2 * NCB;                     // direct-to-LDS loads per tile per wave
   static constexpr int WTILE = NLOAD * 1024;                // LDS bytes of one wave's tile slice
-  static constexpr int VPW = 16 / NW;                       // score registers each wave finalises
-  static constexpr int X1 = NW * 16 * 64 * 4;               // stage-1 exchange: every wave's partials
-  static constexpr int X2 = 16 * 64 * 4;                    // stage-2 exchange: the final scores
-  static constexpr int LDS_BYTES = NW * WTILE + X1 + X2;
+  static constexpr int TILE_BYTES = NW * WTILE;             // one buffer
+  static constexpr int TPW = kTile / NW;                    // tokens each wave finalises
+  static constexpr int EPL = TPW / 2;                       // ... per lane (lanes 0-31 / 32-63 alternate)
+  static constexpr int X1_ROW = 33;                         // floats per token row (padded)
+  static constexpr int X1 = NW * kTile * X1_ROW * 4;        // stage 1: every wave's partial scores
+  static constexpr int X2_ROW = 20;                         // floats per head row (16 tokens, padded)
+  static constexpr int X2 = 32 * X2_ROW * 4;                // stage 2: the final scores
+  // elite keys of a tile: per wave the TPW tokens it finalises x the 32 heads of the group
+  static constexpr int KE_ROW = 32 * TWO_R * 2;             // bytes of one token's group row
+  static constexpr int KE_CPT = KE_ROW / 16;                // 16-byte chunks per token
+  static constexpr int NKE = (TPW * KE_CPT + 63) / 64;      // direct-to-LDS loads per tile per wave
+  static constexpr int KE_W = NKE * 1024;                   // LDS bytes of one wave's elite slice
+  static constexpr int KE_BYTES = NW * KE_W;                // one buffer
+  static constexpr int KE_OFF = 2 * TILE_BYTES;
+  static constexpr int X1_OFF = KE_OFF + 2 * KE_BYTES;
+  static constexpr int X2_OFF = X1_OFF + (X1 + 15) / 16 * 16;
+  static constexpr int LDS_BYTES = X2_OFF + X2;
   static_assert(LDS_BYTES <= 160 * 1024, "exceeds the 160 KiB of LDS of a gfx950 compute unit");
 };
 
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ int tile_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  bf16x2 v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
 }
 
-__device__ __forceinline__ int tile_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// One direct global->LDS load: every lane fetches 16 bytes from its own global address; lane l's
+// data lands at lds_base + l*16.  Issued through inline assembly so that the waits on these loads
+// stay entirely under the kernel's control (vmcnt counting, see the tile loop).
+template <int OFF>
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off offset:%2"
+               :
+               : "s"(lds_base), "v"(gptr), "n"(OFF)
+               : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
 
 // log2-domain slack before the running maximum is raised: probabilities stay below 2^8
 constexpr float kRescaleSlack = 8.f;
 
 template <int NW, int DC_W, int TWO_R>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams p) {
-  using L = AttnMfmaLayout<NW, DC_W>;
-  constexpr int KS = L::KS, CT = L::CT, NCB = L::NCB, VPW = L::VPW;
+  using L = AttnMfmaLayout<NW, DC_W, TWO_R>;
+  constexpr int KS = L::KS, CT = L::CT, NCB = L::NCB, EPL = L::EPL, TPW = L::TPW;
   constexpr int KCH = TWO_R / 8;                 // 16-byte chunks of one head's elite key
+  constexpr int IN_FLIGHT = L::NLOAD + L::NKE;   // direct-to-LDS loads one tile issues per wave
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
   const int split = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
-  char* ctile = smem + wave * L::WTILE;
-  float* x1 = reinterpret_cast<float*>(smem + NW * L::WTILE);
-  float* x2 = reinterpret_cast<float*>(smem + NW * L::WTILE + L::X1);
+  char* ctile0 = smem + wave * L::WTILE;                 // buffer 0; buffer 1 is TILE_BYTES further
+  char* ketile0 = smem + L::KE_OFF + wave * L::KE_W;     // buffer 0; buffer 1 is KE_BYTES further
+  float* x1 = reinterpret_cast<float*>(smem + L::X1_OFF);
+  float* x2 = reinterpret_cast<float*>(smem + L::X2_OFF);
 
   const int64_t row0 = (int64_t)b * p.batch_stride_rows;
   int64_t len = p.seq_len[b];
   len = min(len, p.max_seq_len);
   len = min(len, p.plane_rows - row0);
   len = max(len, (int64_t)0);
-  const int64_t t0 = (int64_t)split * p.chunk;
-  const int64_t t_end = min(t0 + p.chunk, len);
+  // Split s takes the 16-token tiles s, s + n_splits, s + 2 n_splits, ...: at any moment the
+  // work-groups of a batch row read one contiguous window of the planes that moves through the
+  // sequence (DRAM-page friendly); the softmax does not care about token order.
+  const int64_t t0 = (int64_t)split * kTile;
+  const int64_t t_end = len;
+  const int64_t t_step = (int64_t)p.n_splits * kTile;
   const int64_t pidx = ((int64_t)b * p.n_splits + split) * (p.head_groups * 32) + hg * 32;
 
   if (t0 >= t_end) {   // empty split: the merge skips it (l == 0)
@@ -110,23 +148,30 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   const bool head_ok = head < p.n_h;
   const int head_c = head_ok ? head : p.n_h - 1;
 
-  // this wave's slice of the absorbed query, as the B operand of the score MFMAs
-  bf16x8 Qb[KS];
-  {
-    const bf16_t* qrow = p.qt + ((int64_t)b * p.n_h + head_c) * p.d_c + wave * DC_W + 8 * g;
+  // this wave's slice of the absorbed query as the B operand of the 16x16x32 score MFMAs:
+  // lane l holds head hh*16 + l%16, latent columns 32*ks + 8*(l/16) .. +8
+  const int i16 = lane & 15, q16 = lane >> 4;
+  bf16x8 Qb[KS][2];
+  float qe[TWO_R > 0 ? TWO_R : 1];
+  auto load_query = [&]() {
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    const int hq = hg * 32 + hh * 16 + i16;
+    const bool ok = hq < p.n_h;
+    const bf16_t* qrow = p.qt + ((int64_t)b * p.n_h + (ok ? hq : p.n_h - 1)) * p.d_c + wave * DC_W + 8 * q16;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      s16x8 v = *reinterpret_cast<const s16x8*>(qrow + 16 * ks);
-      if (!head_ok) v = (s16x8)(0);
-      Qb[ks] = __builtin_bit_cast(bf16x8, v);
+      s16x8 v = *reinterpret_cast<const s16x8*>(qrow + 32 * ks);
+      if (!ok) v = (s16x8)(0);
+      Qb[ks][hh] = __builtin_bit_cast(bf16x8, v);
     }
   }
-  float qe[TWO_R > 0 ? TWO_R : 1];
   if (TWO_R > 0) {
     const float* qer = p.qe + ((int64_t)b * p.n_h + head_c) * TWO_R;
 #pragma unroll
     for (int j = 0; j < TWO_R; ++j) qe[j] = head_ok ? qer[j] : 0.f;
   }
+  };
 
   f32x16 uacc[CT];
 #pragma unroll
@@ -140,83 +185,79 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   const int ld_row = lane >> 3;
   const char* cbase = reinterpret_cast<const char*>(p.c_plane) + (int64_t)wave * DC_W * 2 +
                       (((lane & 7) ^ tile_swz(ld_row)) << 4);
-  const char* kbase = reinterpret_cast<const char*>(p.ke_plane) + (int64_t)head_c * TWO_R * 2;
+  // elite-key loader: slot c = i*64 + lane of the wave's slice is (token c / KE_CPT, chunk c % KE_CPT)
+  const char* kbase = reinterpret_cast<const char*>(p.ke_plane);
 
-  // LDS read addresses that do not change from tile to tile
-  // score A operand: row n, logical chunk 2*ks + g  ->  block (n/8, ks/4), in-block chunk 2*(ks%4)+g
-  const char* a_row = ctile + (n >> 3) * (NCB * 1024) + (n & 7) * 128;
-  const int a_swz = tile_swz(n & 7);
-  // value A operand (transposed b64 read): lane (q16, s16) addresses row 8*j + 4*(q16/2) + s16/4,
-  // 4 columns at 32*ct + 16*(q16%2) + 4*(s16%4)
-  const int q16 = lane >> 4, s16 = lane & 15;
-  const int tr_r8 = 4 * (q16 >> 1) + (s16 >> 2);                  // row inside its 8-row block
-  const int tr_swz = tile_swz(tr_r8);
-  const int tr_lo = ((q16 & 1) << 1) | ((s16 & 3) >> 1);          // chunk inside a 32-column group
-  const char* tr_row = ctile + tr_r8 * 128 + ((s16 & 1) << 3);
-  const int tr_c0 = (tr_lo ^ tr_swz) << 4;                        // even ct: in-block chunks 0..3
-  const int tr_c1 = ((4 | tr_lo) ^ tr_swz) << 4;                  // odd ct: in-block chunks 4..7
-
-  uint4 kreg[VPW][KCH > 0 ? KCH : 1];
-
-  auto issue_tile = [&](int64_t tile_t0) {
+  // LDS read offsets (inside a wave's tile slice) that do not change from tile to tile.
+  // score A operand: token row i16, logical chunk 4*ks + q16 -> block (i16/8, ks/2)
+  const int a_off = (i16 >> 3) * (NCB * 1024) + (i16 & 7) * 128;
+  const int a_swz = tile_swz(i16 & 7);
+  const int a_c0 = a_off + ((q16 ^ a_swz) << 4);                // even ks: in-block chunks 0..3
+  const int a_c1 = a_off + (((4 | q16) ^ a_swz) << 4);          // odd ks:  in-block chunks 4..7
+  // value A operand (transposed b64 read): 16-lane group q16 serves tokens 8*(q16/2) + {0..3 | 4..7}
+  // and columns 32*ct + 16*(q16%2) + ..; source lane s supplies row s/4, 4 columns at 4*(s%4)
+  const int tr_lo = ((q16 & 1) << 1) | ((i16 & 3) >> 1);        // 16-byte chunk inside the 32 columns
+  const int tr_base = (q16 >> 1) * (NCB * 1024) + ((i16 & 1) << 3);
+  int tr_off[2][2];                                             // [rows 0-3 | 4-7][ct parity]
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
+  for (int e = 0; e < 2; ++e) {
+    const int r8 = 4 * e + (i16 >> 2);
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+      tr_off[e][par] = tr_base + r8 * 128 + ((((par << 2) | tr_lo) ^ tile_swz(r8)) << 4);
+  }
+  // stage-2 ownership: this wave finalises tokens wave*TPW + g + 2*e (e < EPL) for head n
+  const int own_t0 = wave * TPW + g;
+
+  auto issue = [&](int64_t tile_t0, char* ctile, char* ketile) {
+    const uint32_t cl = __builtin_amdgcn_readfirstlane(lds_addr(ctile));
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
       const int64_t t = min(tile_t0 + rb * 8 + ld_row, t_end - 1);
       const char* gp = cbase + (row0 + t) * crow_bytes;
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb)
-        __builtin_amdgcn_global_load_lds(gp + cb * 128, (lds_void_t*)(ctile + (rb * NCB + cb) * 1024), 16,
-                                         0, 0);
+      for (int cb = 0; cb < NCB; ++cb) dma16<0>(gp + cb * 128, cl + (rb * NCB + cb) * 1024);
     }
-  };
-  // the wave finalises score registers v = wave*VPW + e: token 8*(v/4) + 4*g + v%4 of the tile
-  auto issue_ke = [&](int64_t tile_t0) {
     if (TWO_R > 0) {
+      const uint32_t kl = __builtin_amdgcn_readfirstlane(lds_addr(ketile));
 #pragma unroll
-      for (int e = 0; e < VPW; ++e) {
-        const int v = wave * VPW + e;
-        const int64_t t = min(tile_t0 + 8 * (v >> 2) + 4 * g + (v & 3), t_end - 1);
-        const uint4* kp = reinterpret_cast<const uint4*>(kbase + (row0 + t) * krow_bytes);
-#pragma unroll
-        for (int c = 0; c < KCH; ++c) kreg[e][c] = kp[c];
+      for (int i = 0; i < L::NKE; ++i) {
+        const int c = i * 64 + lane;
+        const int tl = min(c / L::KE_CPT, TPW - 1), ch = c % L::KE_CPT;
+        const int hd = min(hg * 32 + ch / KCH, p.n_h - 1);
+        const int64_t t = min(tile_t0 + wave * TPW + tl, t_end - 1);
+        dma16<0>(kbase + (row0 + t) * krow_bytes + ((int64_t)hd * KCH + ch % KCH) * 16, kl + i * 1024);
       }
     }
   };
 
-  issue_tile(t0);
-  issue_ke(t0);
-
-  for (int64_t tile = t0; tile < t_end; tile += kTile) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-
-    // ---- scores over this wave's latent slice (two accumulators break the dependency chain)
-    f32x16 sacc0 = (f32x16)(0.f), sacc1 = (f32x16)(0.f);
+  auto compute = [&](int64_t tile, const char* ctile, const char* ketile) {
+    // ---- partial scores over this wave's latent slice, two head halves
+    f32x4 sd[2] = {(f32x4)(0.f), (f32x4)(0.f)};
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const int inb = ((2 * (ks & 3) + g) ^ a_swz) << 4;
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_row + (ks >> 2) * 1024 + inb);
-      if (ks & 1) sacc1 = mfma32(a, Qb[ks], sacc1);
-      else sacc0 = mfma32(a, Qb[ks], sacc0);
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(ctile + (ks >> 1) * 1024 + ((ks & 1) ? a_c1 : a_c0));
+      sd[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Qb[ks][0], sd[0], 0, 0, 0);
+      sd[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Qb[ks][1], sd[1], 0, 0, 0);
     }
-    const f32x16 sacc = sacc0 + sacc1;
-    // ---- stage 1: every wave publishes its partial scores, grouped by finalising wave
+    // ---- stage 1: publish them as x1[wave][token][head]; lane holds tokens 4*q16 + v, head hh*16 + i16
     {
-      float* xw = x1 + (wave * NW) * (64 * VPW) + lane * VPW;
+      float* xw = x1 + (wave * kTile + 4 * q16) * L::X1_ROW + i16;
 #pragma unroll
-      for (int o = 0; o < NW; ++o) {
+      for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-        for (int e = 0; e < VPW; ++e) xw[o * (64 * VPW) + e] = sacc[o * VPW + e];
-      }
+        for (int v = 0; v < 4; ++v) xw[v * L::X1_ROW + hh * 16] = sd[hh][v];
     }
-    // elite term of the registers this wave finalises (overlaps the barrier)
-    float fin[VPW];
+    // elite term of the (token, head) pairs this wave finalises (overlaps the barrier)
+    float fin[EPL];
 #pragma unroll
-    for (int e = 0; e < VPW; ++e) {
+    for (int e = 0; e < EPL; ++e) {
       float d = 0.f;
       if (TWO_R > 0) {
 #pragma unroll
         for (int c = 0; c < KCH; ++c) {
-          const uint32_t w[4] = {kreg[e][c].x, kreg[e][c].y, kreg[e][c].z, kreg[e][c].w};
+          const uint4 kv = *reinterpret_cast<const uint4*>(ketile + (((g + 2 * e) * L::KE_CPT + n * KCH + c) << 4));
+          const uint32_t w[4] = {kv.x, kv.y, kv.z, kv.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             d = fmaf(qe[8 * c + 2 * i], __uint_as_float(w[i] << 16), d);
@@ -226,48 +267,41 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
       }
       fin[e] = d;
     }
-    const int64_t next = tile + kTile;
-    if (next < t_end) issue_ke(next);     // the elite-key registers are free again
     __syncthreads();
-    // ---- stage 2: sum the NW partials of this wave's registers in a fixed order, publish
+    // ---- stage 2: sum the NW partials in a fixed order, publish as x2[head][token]
 #pragma unroll
-    for (int w2 = 0; w2 < NW; ++w2) {
-      const float* xr = x1 + (w2 * NW + wave) * (64 * VPW) + lane * VPW;
+    for (int e = 0; e < EPL; ++e) {
+      const int tok = own_t0 + 2 * e;
 #pragma unroll
-      for (int e = 0; e < VPW; ++e) fin[e] += xr[e];
+      for (int w2 = 0; w2 < NW; ++w2) fin[e] += x1[(w2 * kTile + tok) * L::X1_ROW + n];
+      x2[n * L::X2_ROW + tok] = fin[e];
     }
+    __syncthreads();
+    // ---- online softmax; lane = head n, tokens 8*g + j
+    float s[8];
     {
-      float* xw = x2 + wave * (64 * VPW) + lane * VPW;
-#pragma unroll
-      for (int e = 0; e < VPW; ++e) xw[e] = fin[e];
+      const f32x4 lo = *reinterpret_cast<const f32x4*>(x2 + n * L::X2_ROW + 8 * g);
+      const f32x4 hi = *reinterpret_cast<const f32x4*>(x2 + n * L::X2_ROW + 8 * g + 4);
+      s[0] = lo[0]; s[1] = lo[1]; s[2] = lo[2]; s[3] = lo[3];
+      s[4] = hi[0]; s[5] = hi[1]; s[6] = hi[2]; s[7] = hi[3];
     }
-    __syncthreads();
-    float s[16];
-#pragma unroll
-    for (int o = 0; o < NW; ++o) {
-      const float* xr = x2 + o * (64 * VPW) + lane * VPW;
-#pragma unroll
-      for (int e = 0; e < VPW; ++e) s[o * VPW + e] = xr[e];
-    }
-    // ---- online softmax; lane = head n, half g; register v = token 8*(v/4) + 4*g + v%4
     float tmax = -INFINITY;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int64_t t = tile + 8 * (v >> 2) + 4 * g + (v & 3);
-      s[v] = (t < t_end) ? s[v] : -INFINITY;
-      tmax = fmaxf(tmax, s[v]);
+    for (int j = 0; j < 8; ++j) {
+      s[j] = (tile + 8 * g + j < t_end) ? s[j] : -INFINITY;
+      tmax = fmaxf(tmax, s[j]);
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
     // the reference maximum is raised only when a score exceeds it by more than the slack
     const float m_new = (tmax > m_run + kRescaleSlack || m_run == -INFINITY) ? tmax : m_run;
     const float alpha = exp2f(m_run - m_new);
     float psum = 0.f;
-    bf16x8 P[2];
+    bf16x8 P;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const float pv = exp2f(s[v] - m_new);
+    for (int j = 0; j < 8; ++j) {
+      const float pv = exp2f(s[j] - m_new);
       psum += pv;
-      P[v >> 3][v & 7] = (__bf16)pv;
+      P[j] = (__bf16)pv;
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
@@ -275,25 +309,41 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) uacc[ct] *= alpha;
     }
-
     // ---- latent accumulation: U^T += C^T P^T, the tile read transposed from LDS
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-      const char* trp = tr_row + (ct >> 1) * 1024 + ((ct & 1) ? tr_c1 : tr_c0);
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2) {
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(trp + (2 * h2) * (NCB * 1024)));
-        const s16x4 hi =
-            __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(trp + (2 * h2 + 1) * (NCB * 1024)));
-        const s16x8 a16 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        uacc[ct] = mfma32(__builtin_bit_cast(bf16x8, a16), P[h2], uacc[ct]);
-      }
+      const char* trp = ctile + (ct >> 1) * 1024;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(trp + tr_off[0][ct & 1]));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(trp + tr_off[1][ct & 1]));
+      const s16x8 a16 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      uacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a16), P, uacc[ct], 0, 0, 0);
     }
-    // the tile slice is consumed: refill it with the next tile
-    if (next < t_end) {
+  };
+
+  // two tiles per trip so that buffer and register-set indices are compile-time
+  char* ctile1 = ctile0 + L::TILE_BYTES;
+  char* ketile1 = ketile0 + L::KE_BYTES;
+  issue(t0, ctile0, ketile0);
+  load_query();   // after the first tile's loads are in flight
+  for (int64_t tile = t0; tile < t_end; tile += 2 * t_step) {
+    const int64_t t1 = tile + t_step, t2 = tile + 2 * t_step;
+    if (t1 < t_end) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // buffer 1 was last read one tile ago
+      issue(t1, ctile1, ketile1);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IN_FLIGHT) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    compute(tile, ctile0, ketile0);
+    if (t1 >= t_end) break;
+    if (t2 < t_end) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      issue_tile(next);
+      issue(t2, ctile0, ketile0);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IN_FLIGHT) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
+    compute(t1, ctile1, ketile1);
   }
 
   // ---- write this split's partial (m, l, U)
@@ -306,15 +356,15 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   // columns; they are transposed through LDS (free now) so that global stores are row-contiguous.
   constexpr int TSTR = DC_W * 2 + 16;                       // bytes per head row in LDS
   static_assert(NW * 32 * TSTR <= L::LDS_BYTES, "transpose staging exceeds the LDS allocation");
-  __syncthreads();                                          // every wave is done with its tile slice
+  __syncthreads();                                          // every wave is done with its tile slices
   char* tt = smem + wave * (32 * TSTR);
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16_bits(uacc[ct][4 * j]) | ((uint32_t)f32_to_bf16_bits(uacc[ct][4 * j + 1]) << 16);
-      pk.y = (uint32_t)f32_to_bf16_bits(uacc[ct][4 * j + 2]) | ((uint32_t)f32_to_bf16_bits(uacc[ct][4 * j + 3]) << 16);
+      pk.x = pack_bf16x2(uacc[ct][4 * j], uacc[ct][4 * j + 1]);
+      pk.y = pack_bf16x2(uacc[ct][4 * j + 2], uacc[ct][4 * j + 3]);
       *reinterpret_cast<uint2*>(tt + n * TSTR + (ct * 32 + 8 * j + 4 * g) * 2) = pk;
     }
   }
@@ -332,7 +382,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
 // ---------------------------------------------------------------------------------------------
 template <int NW, int DC_W, int TWO_R>
 static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t stream) {
-  using L = AttnMfmaLayout<NW, DC_W>;
+  using L = AttnMfmaLayout<NW, DC_W, TWO_R>;
   static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<NW, DC_W, TWO_R>),
@@ -355,7 +405,6 @@ bool decode_mfma_supported(const elitekv_dims& d) {
 
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
-  const int n_h = d.n_heads, d_h = d.head_dim, r = d.r, d_c = d.d_c;
   float* qe = (float*)(a.ws + p.off_qe);
   bf16_t* qt = (bf16_t*)(a.ws + p.off_qt);
   AttnMfmaParams prm;
@@ -363,7 +412,7 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.qe = qe; prm.qt = qt; prm.seq_len = a.seq_len;
   prm.part_m = (float*)(a.ws + p.off_m); prm.part_l = (float*)(a.ws + p.off_l);
   prm.part_u = (bf16_t*)(a.ws + p.off_u);
-  prm.n_h = n_h; prm.d_c = d_c; prm.n_splits = p.n_splits; prm.chunk = p.chunk;
+  prm.n_h = d.n_heads; prm.d_c = d.d_c; prm.n_splits = p.n_splits; prm.chunk = p.chunk;
   prm.head_groups = p.head_groups; prm.max_seq_len = a.max_seq_len;
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
 
@@ -372,9 +421,9 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
 
   if (a.ev_before) (void)hipEventRecord(a.ev_before, stream);
   e = hipErrorInvalidValue;
-  const int two_r = 2 * r;
+  const int two_r = 2 * d.r;
 #define EKV_CASE(DC, NWV, DCW)                                                        \
-  if (d_c == DC) {                                                                    \
+  if (d.d_c == DC) {                                                                  \
     e = two_r == 16 ? launch_attn<NWV, DCW, 16>(prm, a.B, stream)                     \
                     : launch_attn<NWV, DCW, 8>(prm, a.B, stream);                     \
   }

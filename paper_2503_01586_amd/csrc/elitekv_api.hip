@@ -55,7 +55,7 @@ static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_
     int64_t ns = n_splits;
     if (ns == 0) {
       ns = (kComputeUnits + Bq * p->head_groups - 1) / (Bq * p->head_groups);
-      const int64_t cap = (seq + 31) / 32;
+      const int64_t cap = (seq + 15) / 16;
       if (ns > cap) ns = cap;
       if (ns > kMaxSplits) ns = kMaxSplits;
       if (ns < 1) ns = 1;
