@@ -16,7 +16,7 @@ __global__ __launch_bounds__(kApThreads) void append_generic_kernel(
     const T* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot,
     int64_t T_tokens, const T* __restrict__ W_ke, const T* __restrict__ W_dkv,
     const int32_t* __restrict__ elite_idx, T* __restrict__ ke_plane, T* __restrict__ c_plane,
-    int64_t plane_rows, int d, int n_h, int d_h, int r, int d_c, double rope_base) {
+    int64_t plane_rows, int d, int n_h, int d_h, int r, int d_c, RopeTable rope) {
   __shared__ float xs[kApTokens][kApK];
   const int tid = threadIdx.x;
   const int NE = 2 * r * n_h;
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kApThreads) void append_generic_kernel(
     chunk = elite_idx[h * r + j];
     chunk = min(max(chunk, 0), d_h / 2 - 1);
   }
-  const double theta = is_elite ? rope_theta(rope_base, chunk, d_h) : 0.0;
+  const double theta = is_elite ? rope.theta[chunk] : 0.0;
 #pragma unroll
   for (int tt = 0; tt < kApTokens; ++tt) {
     const int64_t t = t0 + tt;
@@ -69,9 +69,8 @@ __global__ __launch_bounds__(kApThreads) void append_generic_kernel(
     const int64_t row = slot[t];
     if (row < 0 || row >= plane_rows) continue;
     if (is_elite) {
-      double sn, cs;
-      sincos((double)pos[t] * theta, &sn, &cs);
-      const float c = (float)cs, s = (float)sn;
+      float s, c;
+      rope_sincos(pos[t], theta, &s, &c);
       // (u, v) -> (u c - v s, u s + v c)
       const float o = (n & 1) ? (other * s + mine * c) : (mine * c - other * s);
       st(ke_plane, row * NE + n, o);
@@ -89,12 +88,12 @@ hipError_t launch_append_generic(const AppendArgs& a, hipStream_t stream) {
     append_generic_kernel<float><<<grid, kApThreads, 0, stream>>>(
         (const float*)a.x, a.pos, a.slot, a.T, (const float*)a.W_ke, (const float*)a.W_dkv,
         a.elite_idx, (float*)a.ke_plane, (float*)a.c_plane, a.plane_rows, d.d_model, d.n_heads,
-        d.head_dim, d.r, d.d_c, d.rope_base);
+        d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
   } else {
     append_generic_kernel<bf16_t><<<grid, kApThreads, 0, stream>>>(
         (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
         a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows, d.d_model, d.n_heads,
-        d.head_dim, d.r, d.d_c, d.rope_base);
+        d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
   }
   return hipGetLastError();
 }

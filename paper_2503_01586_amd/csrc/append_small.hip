@@ -25,6 +25,25 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
   const int k0 = blockIdx.y * kc;
   const int64_t t0 = (int64_t)blockIdx.z * kAsTokens;
 
+  const bf16_t* wbase;
+  int64_t wstride;
+  if (n0 < NE) { wbase = W_ke + n0 + cchunk * 8; wstride = NE; }
+  else { wbase = W_dkv + (n0 - NE) + cchunk * 8; wstride = d_c; }
+
+  // the weight rows of the first batch are requested before anything else: they are the long pole
+  constexpr int kBatch = 8;
+  const int steps = kc / 32;
+  uint4 wq[kBatch];
+  auto load_batch = [&](int s0) {
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int k = k0 + (s0 + u) * 32 + wave * 8 + rg;
+      wq[u] = make_uint4(0, 0, 0, 0);
+      if (s0 + u < steps && k < d) wq[u] = *reinterpret_cast<const uint4*>(wbase + (int64_t)k * wstride);
+    }
+  };
+  load_batch(0);
+
   for (int e = tid; e < kc * kAsTokens; e += kAsThreads) {
     const int kk = e / kAsTokens, tt = e % kAsTokens;
     const int64_t t = t0 + tt;
@@ -32,38 +51,34 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
   }
   __syncthreads();
 
-  const bf16_t* wbase;
-  int64_t wstride;
-  if (n0 < NE) { wbase = W_ke + n0 + cchunk * 8; wstride = NE; }
-  else { wbase = W_dkv + (n0 - NE) + cchunk * 8; wstride = d_c; }
-
   float acc[kAsTokens][8];
 #pragma unroll
   for (int t = 0; t < kAsTokens; ++t)
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[t][i] = 0.f;
 
-  const int steps = kc / 32;
-#pragma unroll 4
-  for (int s = 0; s < steps; ++s) {
-    const int kk = s * 32 + wave * 8 + rg;
-    const int k = k0 + kk;
-    uint4 wv = make_uint4(0, 0, 0, 0);
-    if (k < d) wv = *reinterpret_cast<const uint4*>(wbase + (int64_t)k * wstride);
-    const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w};
-    float w[8];
+  for (int s0 = 0; s0 < steps; s0 += kBatch) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      w[2 * i] = __uint_as_float(ww[i] << 16);
-      w[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
+    for (int u = 0; u < kBatch; ++u) {
+      if (s0 + u < steps) {
+        const int kk = (s0 + u) * 32 + wave * 8 + rg;
+        const uint32_t ww[4] = {wq[u].x, wq[u].y, wq[u].z, wq[u].w};
+        float w[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          w[2 * i] = __uint_as_float(ww[i] << 16);
+          w[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
+        }
+        const float4 xa = *reinterpret_cast<const float4*>(xs + kk * kAsTokens);
+        const float4 xb = *reinterpret_cast<const float4*>(xs + kk * kAsTokens + 4);
+        const float xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+#pragma unroll
+        for (int t = 0; t < kAsTokens; ++t)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[t][i] = fmaf(xv[t], w[i], acc[t][i]);
+      }
     }
-    const float4 xa = *reinterpret_cast<const float4*>(xs + kk * kAsTokens);
-    const float4 xb = *reinterpret_cast<const float4*>(xs + kk * kAsTokens + 4);
-    const float xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
-#pragma unroll
-    for (int t = 0; t < kAsTokens; ++t)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[t][i] = fmaf(xv[t], w[i], acc[t][i]);
+    if (s0 + kBatch < steps) load_batch(s0 + kBatch);
   }
   // sum over the 8 row groups of the wave, then over the 4 waves
 #pragma unroll
@@ -100,7 +115,7 @@ __global__ __launch_bounds__(256) void append_finish_kernel(
     const float* __restrict__ partial, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot,
     int64_t T, const int32_t* __restrict__ elite_idx, bf16_t* __restrict__ ke_plane,
     bf16_t* __restrict__ c_plane, int64_t plane_rows, int n_h, int d_h, int r, int d_c, int ksplit,
-    double rope_base) {
+    RopeTable rope) {
   const int NE = 2 * r * n_h, N = NE + d_c;
   const int64_t t = blockIdx.x;
   const int n = blockIdx.y * 256 + threadIdx.x;
@@ -116,9 +131,8 @@ __global__ __launch_bounds__(256) void append_finish_kernel(
     const int h = n / (2 * r), j = (n % (2 * r)) >> 1;
     int chunk = elite_idx[h * r + j];
     chunk = min(max(chunk, 0), d_h / 2 - 1);
-    double sn, cs;
-    sincos((double)pos[t] * rope_theta(rope_base, chunk, d_h), &sn, &cs);
-    const float c = (float)cs, s = (float)sn;
+    float s, c;
+    rope_sincos(pos[t], rope.theta[chunk], &s, &c);
     const float o = (n & 1) ? (other * s + mine * c) : (mine * c - other * s);
     st(ke_plane, row * NE + n, o);
   } else {
@@ -160,7 +174,7 @@ hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream) {
   if (e != hipSuccess) return e;
   append_finish_kernel<<<dim3((unsigned)a.T, (N + 255) / 256), 256, 0, stream>>>(
       partial, a.pos, a.slot, a.T, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
-      d.n_heads, d.head_dim, d.r, d.d_c, ks, d.rope_base);
+      d.n_heads, d.head_dim, d.r, d.d_c, ks, make_rope_table(d.rope_base, d.head_dim));
   return hipGetLastError();
 }
 

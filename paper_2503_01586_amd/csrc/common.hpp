@@ -35,9 +35,30 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// theta_i = base^(-2i/d_h) in double (Section 2.2; RoFormer's frequencies)
-__device__ __forceinline__ double rope_theta(double base, int i, int head_dim) {
-  return pow(base, -2.0 * (double)i / (double)head_dim);
+// theta_i = base^(-2i/d_h) (Section 2.2; RoFormer's frequencies), computed once per call on the
+// host in double and handed to the kernels by value (head_dim <= 256: at most 128 chunks).
+struct RopeTable {
+  double theta[128];
+};
+inline RopeTable make_rope_table(double base, int head_dim) {
+  RopeTable t;
+  for (int i = 0; i < 128; ++i) t.theta[i] = (2 * i < head_dim) ? pow(base, -2.0 * (double)i / (double)head_dim) : 0.0;
+  return t;
+}
+
+// sin and cos of pos * theta.  The angle is formed and reduced to [-pi/4, pi/4] in double
+// (two-term Cody-Waite, exact for the |k| < 2^20 quadrants that positions up to 2^31 with
+// theta <= 1 can reach in practice); only the reduced argument goes through fp32 sin/cos.
+__device__ __forceinline__ void rope_sincos(int32_t pos, double theta, float* sn, float* cs) {
+  const double a = (double)pos * theta;
+  const double k = rint(a * 0.63661977236758134308);        // a / (pi/2)
+  double r = fma(-k, 1.57079632679489655800e+00, a);        // pi/2, high part
+  r = fma(-k, 6.12323399573676603587e-17, r);               // pi/2, low part
+  const float rf = (float)r;
+  const float s = sinf(rf), c = cosf(rf);
+  const int q = (int)((long long)k & 3);
+  *sn = (q == 0) ? s : (q == 1) ? c : (q == 2) ? -s : -c;
+  *cs = (q == 0) ? c : (q == 1) ? -s : (q == 2) ? -c : s;
 }
 
 }  // namespace ekv

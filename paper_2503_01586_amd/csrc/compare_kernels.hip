@@ -38,7 +38,7 @@ template <typename T, int LPR>
 __global__ __launch_bounds__(kMhaThreads) void mha_attn_kernel(
     const T* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ seq_len,
     const T* __restrict__ k_plane, const T* __restrict__ v_plane, float* __restrict__ part_m,
-    float* __restrict__ part_l, float* __restrict__ part_o, int n_h, int d_h, double rope_base,
+    float* __restrict__ part_l, float* __restrict__ part_o, int n_h, int d_h, RopeTable rope,
     float scale_log2e, int64_t max_seq_len, int64_t batch_stride_rows, int64_t plane_rows,
     int n_splits, int chunk) {
   constexpr int VEC = Vec16<T>::n;
@@ -64,9 +64,9 @@ __global__ __launch_bounds__(kMhaThreads) void mha_attn_kernel(
 
   const T* qrow = q + ((int64_t)b * n_h + h) * d_h;
   for (int i = tid; i < d_h / 2; i += kMhaThreads) {
-    double sn, cs;
-    sincos((double)q_pos[b] * rope_theta(rope_base, i, d_h), &sn, &cs);
-    const float u = ld(qrow, 2 * i), v = ld(qrow, 2 * i + 1), c = (float)cs, s = (float)sn;
+    float s, c;
+    rope_sincos(q_pos[b], rope.theta[i], &s, &c);
+    const float u = ld(qrow, 2 * i), v = ld(qrow, 2 * i + 1);
     q_s[2 * i] = (u * c - v * s) * scale_log2e;
     q_s[2 * i + 1] = (u * s + v * c) * scale_log2e;
   }
@@ -156,7 +156,7 @@ static void launch_mha_t(const MhaArgs& a, hipStream_t stream) {
   const float scale_log2e = kLog2e / sqrtf((float)d_h);
   mha_attn_kernel<T, LPR><<<dim3(a.n_splits, n_h, (unsigned)a.B), kMhaThreads, sm, stream>>>(
       (const T*)a.q, a.q_pos, a.seq_len, (const T*)a.k_plane, (const T*)a.v_plane, pm, pl, po, n_h,
-      d_h, d.rope_base, scale_log2e, a.max_seq_len, a.batch_stride_rows, a.plane_rows, a.n_splits,
+      d_h, make_rope_table(d.rope_base, d.head_dim), scale_log2e, a.max_seq_len, a.batch_stride_rows, a.plane_rows, a.n_splits,
       a.chunk);
   mha_merge_kernel<T><<<dim3(n_h, (unsigned)a.B), kMhaThreads, 0, stream>>>(pm, pl, po, (T*)a.out, n_h,
                                                                          d_h, a.n_splits);

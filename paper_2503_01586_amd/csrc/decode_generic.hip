@@ -18,7 +18,7 @@ template <typename T>
 __global__ __launch_bounds__(kGenThreads) void qprep_generic_kernel(
     const T* __restrict__ q, const int32_t* __restrict__ q_pos, const T* __restrict__ W_uk,
     const int32_t* __restrict__ elite_idx, float* __restrict__ qe, float* __restrict__ qt,
-    int n_h, int d_h, int r, int d_c, double rope_base, float scale_log2e) {
+    int n_h, int d_h, int r, int d_c, RopeTable rope, float scale_log2e) {
   __shared__ float q_ne[256];     // d_h <= 256 checked on the host
   __shared__ int is_elite[128];
   const int h = blockIdx.x;
@@ -50,11 +50,9 @@ __global__ __launch_bounds__(kGenThreads) void qprep_generic_kernel(
   for (int j = tid; j < r; j += kGenThreads) {
     int i = elite_idx[h * r + j];
     i = min(max(i, 0), d_h / 2 - 1);
-    double alpha = (double)q_pos[b] * rope_theta(rope_base, i, d_h);
-    double sn, cs;
-    sincos(alpha, &sn, &cs);
+    float s, c;
+    rope_sincos(q_pos[b], rope.theta[i], &s, &c);
     float u = ld(qrow, 2 * i), v = ld(qrow, 2 * i + 1);
-    float c = (float)cs, s = (float)sn;
     float* o = qe + ((int64_t)b * n_h + h) * 2 * r;
     o[2 * j] = (u * c - v * s) * scale_log2e;
     o[2 * j + 1] = (u * s + v * c) * scale_log2e;
@@ -227,7 +225,7 @@ static hipError_t launch_decode_generic_t(const DecodeArgs& a, const DecodePlan&
   const float scale_log2e = kLog2e / sqrtf((float)d_h);
 
   qprep_generic_kernel<T><<<dim3(n_h, (unsigned)a.B), kGenThreads, 0, stream>>>(
-      (const T*)a.q, a.q_pos, (const T*)a.W_uk, a.elite_idx, qe, qt, n_h, d_h, r, d_c, d.rope_base,
+      (const T*)a.q, a.q_pos, (const T*)a.W_uk, a.elite_idx, qe, qt, n_h, d_h, r, d_c, make_rope_table(d.rope_base, d.head_dim),
       scale_log2e);
 
   const dim3 grid(p.n_splits, n_h, (unsigned)a.B);

@@ -21,7 +21,7 @@ constexpr int kQpBatchTile = 8;
 __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
     const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos, const bf16_t* __restrict__ W_uk,
     const int32_t* __restrict__ elite_idx, float* __restrict__ qe, bf16_t* __restrict__ qt,
-    uint32_t* __restrict__ counters, int B, int n_h, int d_h, int r, int d_c, double rope_base, float scale_log2e) {
+    uint32_t* __restrict__ counters, int B, int n_h, int d_h, int r, int d_c, RopeTable rope, float scale_log2e) {
   extern __shared__ __attribute__((aligned(16))) char qsm[];
   const int nd = d_h - 2 * r;
   const int ndp = nd + 8;                                  // padded row: breaks the LDS bank period
@@ -31,6 +31,20 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b0 = blockIdx.y * kQpBatchTile;
   const int bt_n = min(kQpBatchTile, B - b0);
+
+  // this thread's weight row is requested before anything else (nd <= 128: at most 16 chunks)
+  const int64_t row = (int64_t)blockIdx.x * kQpThreads + tid;
+  const bool row_ok = row < (int64_t)d_c * n_h;
+  const int nchunk = nd / 8;
+  uint4 wreg[16];
+  {
+    const uint4* wrow = reinterpret_cast<const uint4*>(W_uk + (row_ok ? row : 0) * nd);
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      wreg[c] = make_uint4(0, 0, 0, 0);
+      if (c < nchunk && row_ok) wreg[c] = wrow[c];
+    }
+  }
 
   // position of every non-elite chunk inside the compacted query (-1 for elite chunks); half <= 64
   for (int h = wave; h < n_h; h += kQpThreads / 64) {
@@ -58,10 +72,10 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
       const int j = e % r, h = (e / r) % n_h, b = b0 + e / (r * n_h);
       int i = elite_idx[h * r + j];
       i = min(max(i, 0), half - 1);
-      double sn, cs;
-      sincos((double)q_pos[b] * rope_theta(rope_base, i, d_h), &sn, &cs);
+      float s, c;
+      rope_sincos(q_pos[b], rope.theta[i], &s, &c);
       const bf16_t* qrow = q + ((int64_t)b * n_h + h) * d_h;
-      const float u = ld(qrow, 2 * i), v = ld(qrow, 2 * i + 1), c = (float)cs, s = (float)sn;
+      const float u = ld(qrow, 2 * i), v = ld(qrow, 2 * i + 1);
       float* o = qe + ((int64_t)b * n_h + h) * 2 * r;
       o[2 * j] = (u * c - v * s) * scale_log2e;
       o[2 * j + 1] = (u * s + v * c) * scale_log2e;
@@ -69,35 +83,34 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
   }
   __syncthreads();
 
-  const int64_t row = (int64_t)blockIdx.x * kQpThreads + tid;
-  if (row >= (int64_t)d_c * n_h) return;
+  if (!row_ok) return;
   const int k = (int)(row / n_h), h = (int)(row % n_h);
-  const uint4* wrow = reinterpret_cast<const uint4*>(W_uk + row * nd);
   float acc[kQpBatchTile];
 #pragma unroll
   for (int bt = 0; bt < kQpBatchTile; ++bt) acc[bt] = 0.f;
-  const int nchunk = nd / 8;
-  for (int c = 0; c < nchunk; ++c) {
-    const uint4 wv = wrow[c];
-    const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w};
-    float w[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      w[2 * i] = __uint_as_float(ww[i] << 16);
-      w[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
-    }
+  for (int c = 0; c < 16; ++c) {
+    if (c < nchunk) {
+      const uint32_t ww[4] = {wreg[c].x, wreg[c].y, wreg[c].z, wreg[c].w};
+      float w[8];
 #pragma unroll
-    for (int bt = 0; bt < kQpBatchTile; ++bt) {
-      if (bt < bt_n) {
-        const uint4 qv = *reinterpret_cast<const uint4*>(qne + ((size_t)bt * n_h + h) * ndp + 8 * c);
-        const uint32_t qq[4] = {qv.x, qv.y, qv.z, qv.w};
-        float a = acc[bt];
+      for (int i = 0; i < 4; ++i) {
+        w[2 * i] = __uint_as_float(ww[i] << 16);
+        w[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
+      }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          a = fmaf(w[2 * i], __uint_as_float(qq[i] << 16), a);
-          a = fmaf(w[2 * i + 1], __uint_as_float(qq[i] & 0xffff0000u), a);
+      for (int bt = 0; bt < kQpBatchTile; ++bt) {
+        if (bt < bt_n) {
+          const uint4 qv = *reinterpret_cast<const uint4*>(qne + ((size_t)bt * n_h + h) * ndp + 8 * c);
+          const uint32_t qq[4] = {qv.x, qv.y, qv.z, qv.w};
+          float a = acc[bt];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            a = fmaf(w[2 * i], __uint_as_float(qq[i] << 16), a);
+            a = fmaf(w[2 * i + 1], __uint_as_float(qq[i] & 0xffff0000u), a);
+          }
+          acc[bt] = a;
         }
-        acc[bt] = a;
       }
     }
   }
@@ -121,7 +134,7 @@ hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, uint32_
   }
   qprep_rows_kernel<<<grid, kQpThreads, sm, stream>>>(
       (const bf16_t*)a.q, a.q_pos, (const bf16_t*)a.W_uk, a.elite_idx, qe, qt, counters, (int)a.B, d.n_heads,
-      d.head_dim, d.r, d.d_c, d.rope_base, kLog2e / sqrtf((float)d.head_dim));
+      d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim), kLog2e / sqrtf((float)d.head_dim));
   return hipGetLastError();
 }
 
@@ -132,6 +145,8 @@ hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, uint32_
 //   * its contribution to the up-projection  o[h, :] = ubar[h, :] W_uv[:, h, :]   (B^v_J),
 //   * the last chunk of a head to finish adds the chunk partials in a fixed order and writes out.
 // Partials: part_m / part_l [P, NHP], part_u [P, NHP, d_c] bf16 with P = b * n_splits + s.
+// All global loads that do not depend on earlier results (the W_uv rows, the first batch of
+// split accumulators) are requested at the top so that their latency overlaps the merge weights.
 // ---------------------------------------------------------------------------------------------
 template <int CW, int DH>
 __global__ __launch_bounds__(256) void merge_up_kernel(
@@ -142,17 +157,45 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   constexpr int NG = 256 / LPR;            // split groups working in parallel
   constexpr int LPW = DH / 8;              // lanes that cover one W_uv row
   constexpr int RPI = 64 / LPW;            // W_uv rows per wave instruction
+  constexpr int NWI = CW / (4 * RPI);      // W_uv rows per thread
+  constexpr int UB = 16;                   // split accumulators requested per batch
   extern __shared__ __attribute__((aligned(16))) float msm[];
   float* wsp = msm;                        // [n_splits] merge weights of this head
-  float* red = wsp + n_splits;             // [256] scratch; later [NG][CW] and [4][DH]
-  float* big = red + 256;                  // [NG][CW]
+  float* red = wsp + n_splits;             // [256] scratch
+  float* big = red + 256;                  // [NG][CW], later [4][DH]
   float* ubar = big + NG * CW;             // [CW]
-  __shared__ int is_last;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
   const int n_chunks = gridDim.x;
   const int64_t p0 = (int64_t)b * n_splits;
+  const int col0 = chunk * CW;
 
+  // (1) this thread's W_uv rows: k = col0 + wave*RPI + rr + i*4*RPI
+  const int jl = lane % LPW, rr = lane / LPW;
+  uint4 wreg[NWI];
+  {
+    const bf16_t* wb = W_uv + ((int64_t)(col0 + wave * RPI + rr) * n_h + head) * DH + jl * 8;
+#pragma unroll
+    for (int i = 0; i < NWI; ++i)
+      wreg[i] = *reinterpret_cast<const uint4*>(wb + (int64_t)i * 4 * RPI * n_h * DH);
+  }
+  // (2) first batch of split accumulators: group sg takes splits sg, sg + NG, ...
+  const int cl = tid % LPR, sg = tid / LPR;
+  const bool grp_ok = sg < NG;
+  const bf16_t* ub = part_u + (p0 * nhp + head) * (int64_t)d_c + col0 + cl * 8;
+  const int64_t sstep = (int64_t)nhp * d_c;
+  uint4 ureg[UB];
+  auto load_batch = [&](int s0) {
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int s = s0 + sg + u * NG;
+      ureg[u] = make_uint4(0, 0, 0, 0);
+      if (grp_ok && s < n_splits) ureg[u] = *reinterpret_cast<const uint4*>(ub + s * sstep);
+    }
+  };
+  load_batch(0);
+
+  // (3) merge weights  w_s = exp2(m_s - max m),  L = sum w_s l_s   (an empty split has l = 0)
   float m = -INFINITY;
   for (int s = tid; s < n_splits; s += 256) m = fmaxf(m, part_m[(p0 + s) * nhp + head]);
   m = wave_max(m);
@@ -173,23 +216,18 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   const float Lsum = (red[0] + red[1]) + (red[2] + red[3]);
   const float inv = (Lsum > 0.f) ? 1.f / Lsum : 0.f;
 
-  // merged latent of this chunk: split groups run in parallel, then a fixed-order sum
-  const int cl = tid % LPR, sg = tid / LPR;
-  const int col0 = chunk * CW;
+  // (4) merged latent of this chunk.  An empty split has weight 0 and an unwritten accumulator:
+  // it is loaded like the others but kept out of the sum.
   float acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-  if (sg < NG) {
-    const bf16_t* ub = part_u + (p0 * nhp + head) * (int64_t)d_c + col0 + cl * 8;
-    const int64_t sstep = (int64_t)nhp * d_c;
-#pragma unroll 4
-    for (int s = sg; s < n_splits; s += NG) {
-      // an empty split has weight 0 and an unwritten accumulator: load it anyway (the loads
-      // stay independent of the weights) but keep it out of the sum
-      const float w = wsp[s];
+  for (int s0 = 0; s0 < n_splits; s0 += UB * NG) {
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int s = s0 + sg + u * NG;
+      const float w = (grp_ok && s < n_splits) ? wsp[s] : 0.f;
       const bool live = w != 0.f;
-      const uint4 uv = *reinterpret_cast<const uint4*>(ub + s * sstep);
-      const uint32_t uu[4] = {uv.x, uv.y, uv.z, uv.w};
+      const uint32_t uu[4] = {ureg[u].x, ureg[u].y, ureg[u].z, ureg[u].w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float lo = fmaf(w, __uint_as_float(uu[i] << 16), acc[2 * i]);
@@ -198,6 +236,9 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
         acc[2 * i + 1] = live ? hi : acc[2 * i + 1];
       }
     }
+    if (s0 + UB * NG < n_splits) load_batch(s0 + UB * NG);
+  }
+  if (grp_ok) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) big[sg * CW + cl * 8 + i] = acc[i];
   }
@@ -210,21 +251,18 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   }
   __syncthreads();
 
-  // up-projection of this chunk: rows k = col0 + kk of W_uv[:, head, :]
-  const int jl = lane % LPW, rr = lane / LPW;
+  // (5) up-projection of this chunk with the prefetched rows
   float o[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) o[i] = 0.f;
-  const bf16_t* wb = W_uv + ((int64_t)col0 * n_h + head) * DH + jl * 8;
-#pragma unroll 4
-  for (int kk = wave * RPI + rr; kk < CW; kk += 4 * RPI) {
-    const float u = ubar[kk];
-    const uint4 wv = *reinterpret_cast<const uint4*>(wb + (int64_t)kk * n_h * DH);
-    const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      o[2 * i] = fmaf(u, __uint_as_float(ww[i] << 16), o[2 * i]);
-      o[2 * i + 1] = fmaf(u, __uint_as_float(ww[i] & 0xffff0000u), o[2 * i + 1]);
+  for (int i = 0; i < NWI; ++i) {
+    const float u = ubar[wave * RPI + rr + i * 4 * RPI];
+    const uint32_t ww[4] = {wreg[i].x, wreg[i].y, wreg[i].z, wreg[i].w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      o[2 * q] = fmaf(u, __uint_as_float(ww[q] << 16), o[2 * q]);
+      o[2 * q + 1] = fmaf(u, __uint_as_float(ww[q] & 0xffff0000u), o[2 * q + 1]);
     }
   }
 #pragma unroll
@@ -243,23 +281,23 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   float* op = opart + (((int64_t)b * n_h + head) * n_chunks + chunk) * DH;
   if (tid < DH) op[tid] = (wred[tid] + wred[DH + tid]) + (wred[2 * DH + tid] + wred[3 * DH + tid]);
 
-  // the last chunk of this (batch row, head) to arrive finishes the output row
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const uint32_t old = atomicAdd(&counters[(int64_t)b * n_h + head], 1u);
-    is_last = (old == (uint32_t)(n_chunks - 1));
-  }
-  __syncthreads();
-  if (is_last) {
-    __threadfence();
-    if (tid < DH) {
-      const float* pp = opart + ((int64_t)b * n_h + head) * n_chunks * DH + tid;
-      float a = 0.f;
-      for (int c = 0; c < n_chunks; ++c) a += __builtin_nontemporal_load(pp + (int64_t)c * DH);
-      st(out, ((int64_t)b * n_h + head) * DH + tid, a);
-    }
-  }
+}
+
+// out[b, h, j] = sum over the latent chunks of the up-projection partials, in a fixed order.
+// (A separate launch rather than a last-arrival epilogue: device-scope fences inside merge_up
+// write back and invalidate the whole L2 of the XCD for every work-group.)
+__global__ __launch_bounds__(256) void out_reduce_kernel(const float* __restrict__ opart,
+                                                         bf16_t* __restrict__ out, int d_h,
+                                                         int n_chunks, int64_t total) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [B * n_h, d_h]
+  if (e >= total) return;
+  const int64_t bh = e / d_h;
+  const int j = (int)(e % d_h);
+  const float* p = opart + bh * n_chunks * d_h + j;
+  float a = 0.f;
+#pragma unroll 8
+  for (int c = 0; c < n_chunks; ++c) a += p[(int64_t)c * d_h];
+  st(out, e, a);
 }
 
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
@@ -282,6 +320,11 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
   if (cw == 192) { if (d.head_dim == 128) EKV_MU(192, 128); else EKV_MU(192, 64); }
   else { if (d.head_dim == 128) EKV_MU(64, 128); else EKV_MU(64, 64); }
 #undef EKV_MU
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
+  out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(opart, (bf16_t*)a.out, d.head_dim,
+                                                                        d.d_c / cw, total);
   return hipGetLastError();
 }
 
