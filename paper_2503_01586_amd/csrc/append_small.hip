@@ -44,10 +44,14 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
   };
   load_batch(0);
 
-  for (int e = tid; e < kc * kAsTokens; e += kAsThreads) {
-    const int kk = e / kAsTokens, tt = e % kAsTokens;
-    const int64_t t = t0 + tt;
-    xs[e] = (t < T && k0 + kk < d) ? ld(x, t * d + k0 + kk) : 0.f;
+  // stage x[t0 .. t0+8, k0 .. k0+kc) as xs[k][token]: per pass a thread takes one k for all tokens
+  for (int kk = tid; kk < kc; kk += kAsThreads) {
+    float xv[kAsTokens];
+#pragma unroll
+    for (int tt = 0; tt < kAsTokens; ++tt)
+      xv[tt] = (t0 + tt < T && k0 + kk < d) ? ld(x, (t0 + tt) * d + k0 + kk) : 0.f;
+#pragma unroll
+    for (int tt = 0; tt < kAsTokens; ++tt) xs[kk * kAsTokens + tt] = xv[tt];
   }
   __syncthreads();
 

@@ -47,9 +47,18 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
   }
 
   // position of every non-elite chunk inside the compacted query (-1 for elite chunks); half <= 64
+  // (elite mask per head built in LDS first: one coalesced read of the index table)
+  uint64_t* emask = reinterpret_cast<uint64_t*>(qsm + (size_t)kQpBatchTile * n_h * ndp * 2 +
+                                                (size_t)n_h * half * 2);          // [n_h]
+  for (int h = tid; h < n_h; h += kQpThreads) emask[h] = 0ull;
+  __syncthreads();
+  for (int e = tid; e < n_h * r; e += kQpThreads) {
+    const int i = elite_idx[e];
+    if (i >= 0 && i < half) atomicOr(reinterpret_cast<unsigned long long*>(&emask[e / r]), 1ull << i);
+  }
+  __syncthreads();
   for (int h = wave; h < n_h; h += kQpThreads / 64) {
-    bool el = false;
-    for (int j = 0; j < r; ++j) el |= (elite_idx[h * r + j] == lane);
+    const bool el = (emask[h] >> lane) & 1ull;
     const bool live = lane < half && !el;
     const uint64_t mask = __ballot(live);
     const int pos = __popcll(mask & ((1ull << lane) - 1ull));
@@ -123,7 +132,8 @@ hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, uint32_
                              hipStream_t stream) {
   const elitekv_dims& d = a.dims;
   const int nd = d.head_dim - 2 * d.r;
-  const size_t sm = (size_t)kQpBatchTile * d.n_heads * (nd + 8) * 2 + (size_t)d.n_heads * (d.head_dim / 2) * 2;
+  const size_t sm = (size_t)kQpBatchTile * d.n_heads * (nd + 8) * 2 + (size_t)d.n_heads * (d.head_dim / 2) * 2 +
+                    (size_t)d.n_heads * 8;
   const int64_t rows = (int64_t)d.d_c * d.n_heads;
   const dim3 grid((unsigned)((rows + kQpThreads - 1) / kQpThreads),
                   (unsigned)((a.B + kQpBatchTile - 1) / kQpBatchTile));
