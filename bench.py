@@ -23,6 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
+# by the readings of a plain copy of known size (profiles/attn_mfma_<workload>.md); workloads that
+# have not been counted report null.
+TRAFFIC_BYTES = {"7b_25_b1_s32768": 160.4e6}
 METRIC = "decode attn HBM GB/s (% of peak) + tokens/s, 7B shape 25% cache, 32K ctx"
 
 
@@ -162,7 +166,7 @@ def main():
         "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
         "roofline": {"bound": "hbm", "kernel": "split attention kernel of elitekv_decode_attn",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES.get(cfg.name),
                      "algorithmic_bytes_per_launch": cache_bytes, "avg_launch_ms": round(k_avg_ms, 5),
                      "median_launch_ms": round(k_ms[len(k_ms) // 2], 5), "min_launch_ms": round(k_ms[0], 5)},
     }
@@ -196,6 +200,18 @@ def comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream, 
     ev.record(e1, stream)
     torch.cuda.synchronize()
     out["stream_read_GBs"] = round(nbytes / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9, 1)
+    # a plain device-to-device copy of known size: the reference the HBM byte counters
+    # (FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc) are scaled by
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev.record(e0, stream)
+    for i in range(10):
+        dst.copy_(src)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    out["copy_256MiB_GBs"] = round(10 * 2 * src.numel() / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9, 1)
+    del src, dst
 
     # uncompressed cache: 2*n_h*d_h elements per token; use as many copies as fit ~2 GiB
     esz = 2 if cfg.dtype == "bf16" else 4

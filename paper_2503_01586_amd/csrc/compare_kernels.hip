@@ -190,14 +190,19 @@ constexpr int kStreamGrid = 2048;
 
 __global__ __launch_bounds__(kStreamThreads) void stream_read_kernel(const uint4* __restrict__ src,
                                                                      size_t n16, uint32_t* sink) {
+  // every block streams one contiguous share, eight 16-byte loads per thread in flight
   uint32_t acc = 0;
-  const size_t stride = (size_t)gridDim.x * kStreamThreads;
-  size_t i = (size_t)blockIdx.x * kStreamThreads + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t lo = per * blockIdx.x, hi = min(lo + per, n16);
+  size_t i = lo + threadIdx.x;
+  for (; i + 7 * kStreamThreads < hi; i += 8 * kStreamThreads) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[i + u * kStreamThreads];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
-  for (; i < n16; i += stride) {
+  for (; i < hi; i += kStreamThreads) {
     const uint4 a = src[i];
     acc ^= a.x ^ a.y ^ a.z ^ a.w;
   }
