@@ -1,0 +1,81 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (automatic
+split count, same strides): the planes are built by the library's own append from seeded hidden
+states, append is checked on sampled rows and decode on sampled (batch row, head) outputs, each
+computed one by one by the float64 oracle from exactly the planes the GPU reads.
+"""
+import numpy as np
+import pytest
+import torch
+
+import elitekv_synth as synth
+import paper_2503_01586_amd as ekv
+from oracle import elitekv_oracle as orc
+
+from gpu_util import DEV, TOL, dev, dims_of, gpu_decode, host64, i32, i64
+
+pytestmark = pytest.mark.gpu
+
+# workload -> sampled batch rows, sampled heads, tokens appended per call
+SAMPLES = {
+    "7b_25_b8_s4096": ([0, 5], [3, 17, 31], 4096),
+    "7b_25_b1_s32768": ([0], [0, 13, 30], 8192),
+    "13b_25_b16_s8192": ([2, 15], [7, 39], 8192),
+    "7b_12_b64_s2048": ([0, 41, 63], [5, 22], 2048),     # prefill-append of 2048 tokens per row
+}
+
+
+@pytest.mark.parametrize("name", list(SAMPLES))
+def test_full_size_append_and_decode(name):
+    cfg = synth.CONFIGS[name]
+    rows_s, heads_s, t_call = SAMPLES[name]
+    B, S, n_h, d_h, r, d_c, d = cfg.batch, cfg.context, cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c, cfg.d_model
+    dt = cfg.dtype
+    dims = dims_of(cfg)
+    rng = synth.rng_for(cfg.index)
+    idx = synth.draw_elite_idx(rng, n_h, d_h, r)
+    W_ke, W_dkv, W_uk, W_uv = synth.draw_weights(rng, d, n_h, d_h, r, d_c)
+    q = synth.draw_query(rng, B, n_h, d_h)
+    Wked, Wdkvd, Wukd, Wuvd, qd = (dev(a, dt) for a in (W_ke, W_dkv, W_uk, W_uv, q))
+    idxd = i32(idx)
+
+    ke = torch.zeros(B * S, n_h, 2 * r, dtype=ekv.torch_dtype(dims), device=DEV)
+    c = torch.zeros(B * S, d_c, dtype=ekv.torch_dtype(dims), device=DEV)
+    ws = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, t_call), 16), dtype=torch.uint8, device=DEV)
+    kept = {}                                       # sampled hidden rows for the append check
+    xrng = synth.rng_for(cfg.index, stream=7)
+    for b in range(B):
+        for t0 in range(0, S, t_call):
+            x = xrng.standard_normal((t_call, d), dtype=np.float32)
+            xd = torch.from_numpy(x).to(ekv.torch_dtype(dims)).to(DEV)
+            pos = torch.arange(t0, t0 + t_call, dtype=torch.int32, device=DEV)
+            slot = torch.arange(b * S + t0, b * S + t0 + t_call, dtype=torch.int64, device=DEV)
+            ekv.elitekv_append(dims, xd, pos, slot, Wked, Wdkvd, idxd, ke, c, ws=ws)
+            if b in rows_s:
+                for tt in (0, t_call // 2 + 1, t_call - 1):
+                    kept[(b, t0 + tt)] = host64(xd[tt:tt + 1])
+    torch.cuda.synchronize()
+
+    # append: sampled rows against the oracle
+    Wke64, Wdkv64 = host64(Wked), host64(Wdkvd)
+    for (b, t), x64 in kept.items():
+        ke_ref, c_ref = orc.append(x64, np.array([t]), Wke64, Wdkv64, idx, d_h, cfg.rope_base)
+        assert orc.max_abs_rel(host64(c[b * S + t]), c_ref[0]) <= TOL[dt]
+        assert orc.max_abs_rel(host64(ke[b * S + t]), ke_ref[0]) <= TOL[dt]
+
+    # decode in the benchmark's launch configuration (automatic splits)
+    q_pos = np.full(B, S - 1)
+    seq = np.full(B, S)
+    out = host64(gpu_decode(dims, qd, i32(q_pos), i32(seq), S, S, Wukd, Wuvd, idxd, ke, c, n_splits=0))
+    assert np.all(np.isfinite(out))
+    Wuk64, Wuv64, q64 = host64(Wukd), host64(Wuvd), host64(qd)
+    refs, gots = [], []
+    for b in rows_s:
+        ke_b = host64(ke[b * S:(b + 1) * S])
+        c_b = host64(c[b * S:(b + 1) * S])
+        ref = orc.decode_attn(q64[b:b + 1], [S - 1], [ke_b], [c_b], [S], Wuk64, Wuv64, idx, d_h, cfg.rope_base,
+                              heads=heads_s)
+        for h in heads_s:
+            refs.append(ref[0, h])
+            gots.append(out[b, h])
+    err = orc.max_abs_rel(np.stack(gots), np.stack(refs))
+    assert err <= TOL[dt], "max-abs-rel %g" % err
