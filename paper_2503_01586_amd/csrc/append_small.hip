@@ -10,20 +10,21 @@ namespace ekv {
 
 constexpr int kAsThreads = 256;
 constexpr int kAsCols = 64;       // output columns per work-group: one 128-byte line of a bf16 weight row
-constexpr int kAsTokens = 8;      // tokens per work-group pass
+constexpr int kAsTokens = 8;      // most tokens per work-group pass
 
-// grid (column blocks, contraction splits, token tiles)
+// grid (column blocks, contraction splits, token tiles); TT = tokens per work-group pass
+template <int TT>
 __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
     const bf16_t* __restrict__ x, int64_t T, const bf16_t* __restrict__ W_ke,
     const bf16_t* __restrict__ W_dkv, float* __restrict__ partial, int d, int NE, int d_c, int kc) {
-  extern __shared__ __attribute__((aligned(16))) float xs[];   // [kc][kAsTokens]
-  __shared__ float red[4][8][kAsTokens][8];                    // [wave][column chunk][token][8 cols]
+  extern __shared__ __attribute__((aligned(16))) float xs[];   // [kc][TT]
+  __shared__ float red[4][8][TT][8];                    // [wave][column chunk][token][8 cols]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rg = lane >> 3, cchunk = lane & 7;
   const int N = NE + d_c;
   const int n0 = blockIdx.x * kAsCols;
   const int k0 = blockIdx.y * kc;
-  const int64_t t0 = (int64_t)blockIdx.z * kAsTokens;
+  const int64_t t0 = (int64_t)blockIdx.z * TT;
 
   const bf16_t* wbase;
   int64_t wstride;
@@ -46,18 +47,18 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
 
   // stage x[t0 .. t0+8, k0 .. k0+kc) as xs[k][token]: per pass a thread takes one k for all tokens
   for (int kk = tid; kk < kc; kk += kAsThreads) {
-    float xv[kAsTokens];
+    float xv[TT];
 #pragma unroll
-    for (int tt = 0; tt < kAsTokens; ++tt)
+    for (int tt = 0; tt < TT; ++tt)
       xv[tt] = (t0 + tt < T && k0 + kk < d) ? ld(x, (t0 + tt) * d + k0 + kk) : 0.f;
 #pragma unroll
-    for (int tt = 0; tt < kAsTokens; ++tt) xs[kk * kAsTokens + tt] = xv[tt];
+    for (int tt = 0; tt < TT; ++tt) xs[kk * TT + tt] = xv[tt];
   }
   __syncthreads();
 
-  float acc[kAsTokens][8];
+  float acc[TT][8];
 #pragma unroll
-  for (int t = 0; t < kAsTokens; ++t)
+  for (int t = 0; t < TT; ++t)
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[t][i] = 0.f;
 
@@ -73,11 +74,11 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
           w[2 * i] = __uint_as_float(ww[i] << 16);
           w[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
         }
-        const float4 xa = *reinterpret_cast<const float4*>(xs + kk * kAsTokens);
-        const float4 xb = *reinterpret_cast<const float4*>(xs + kk * kAsTokens + 4);
-        const float xv[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+        float xv[TT];
 #pragma unroll
-        for (int t = 0; t < kAsTokens; ++t)
+        for (int t = 0; t < TT; ++t) xv[t] = xs[kk * TT + t];
+#pragma unroll
+        for (int t = 0; t < TT; ++t)
 #pragma unroll
           for (int i = 0; i < 8; ++i) acc[t][i] = fmaf(xv[t], w[i], acc[t][i]);
       }
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
   }
   // sum over the 8 row groups of the wave, then over the 4 waves
 #pragma unroll
-  for (int t = 0; t < kAsTokens; ++t)
+  for (int t = 0; t < TT; ++t)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float v = acc[t][i];
@@ -97,13 +98,12 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
     }
   if (rg == 0) {
 #pragma unroll
-    for (int t = 0; t < kAsTokens; ++t)
+    for (int t = 0; t < TT; ++t)
 #pragma unroll
       for (int i = 0; i < 8; ++i) red[wave][cchunk][t][i] = acc[t][i];
   }
   __syncthreads();
-  // 8 tokens x 64 columns = 512 sums, two per thread
-  for (int e = tid; e < kAsTokens * kAsCols; e += kAsThreads) {
+  for (int e = tid; e < TT * kAsCols; e += kAsThreads) {
     const int tt = e / kAsCols, c = e % kAsCols;
     const int64_t t = t0 + tt;
     if (t < T) {
@@ -169,11 +169,15 @@ hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream) {
   int kc = (d.d_model + ks - 1) / ks;
   kc = (kc + 31) / 32 * 32;
   float* partial = (float*)a.ws;
-  const dim3 grid(N / kAsCols, ks, (unsigned)((a.T + kAsTokens - 1) / kAsTokens));
-  const size_t sm = (size_t)kc * kAsTokens * sizeof(float);
-  append_small_kernel<<<grid, kAsThreads, sm, stream>>>((const bf16_t*)a.x, a.T, (const bf16_t*)a.W_ke,
-                                                        (const bf16_t*)a.W_dkv, partial, d.d_model, NE,
-                                                        d.d_c, kc);
+#define EKV_AS(TT)                                                                                   \
+  append_small_kernel<TT><<<dim3(N / kAsCols, ks, (unsigned)((a.T + TT - 1) / TT)), kAsThreads,      \
+                            (size_t)kc * TT * sizeof(float), stream>>>(                             \
+      (const bf16_t*)a.x, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv, partial, d.d_model, NE, d.d_c, kc)
+  if (a.T == 1) EKV_AS(1);
+  else if (a.T == 2) EKV_AS(2);
+  else if (a.T <= 4) EKV_AS(4);
+  else EKV_AS(kAsTokens);
+#undef EKV_AS
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   append_finish_kernel<<<dim3((unsigned)a.T, (N + 255) / 256), 256, 0, stream>>>(

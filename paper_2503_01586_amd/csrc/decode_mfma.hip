@@ -136,11 +136,13 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   const int64_t t_step = (int64_t)p.n_splits * kTile;
   const int64_t pidx = ((int64_t)b * p.n_splits + split) * (p.head_groups * 32) + hg * 32;
 
-  if (t0 >= t_end) {   // empty split: the merge skips it (l == 0)
+  if (t0 >= t_end) {   // empty split: weight 0 in the merge (l == 0), accumulator rows zeroed
     if (wave == 0 && g == 0) {
       p.part_m[pidx + n] = -INFINITY;
       p.part_l[pidx + n] = 0.f;
     }
+    uint4* z = reinterpret_cast<uint4*>(p.part_u + pidx * (int64_t)p.d_c);
+    for (int i = tid; i < 4 * p.d_c; i += NW * 64) z[i] = make_uint4(0, 0, 0, 0);
     return;
   }
 
@@ -416,7 +418,7 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.head_groups = p.head_groups; prm.max_seq_len = a.max_seq_len;
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
 
-  hipError_t e = launch_qprep_rows(a, qe, qt, (uint32_t*)(a.ws + p.off_cnt), stream);
+  hipError_t e = launch_qprep_rows(a, qe, qt, stream);
   if (e != hipSuccess) return e;
 
   if (a.ev_before) (void)hipEventRecord(a.ev_before, stream);

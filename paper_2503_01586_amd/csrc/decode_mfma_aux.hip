@@ -18,24 +18,27 @@ namespace ekv {
 constexpr int kQpThreads = 256;
 constexpr int kQpBatchTile = 8;
 
+// BT = batch rows handled per work-group pass (1, 2, 4 or 8), a template parameter so that the
+// single-row decode does no work for absent rows.
+template <int BT>
 __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
     const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos, const bf16_t* __restrict__ W_uk,
-    const int32_t* __restrict__ elite_idx, float* __restrict__ qe, bf16_t* __restrict__ qt,
-    uint32_t* __restrict__ counters, int B, int n_h, int d_h, int r, int d_c, RopeTable rope, float scale_log2e) {
+    const int32_t* __restrict__ elite_idx, float* __restrict__ qe, bf16_t* __restrict__ qt, int B, int n_h,
+    int d_h, int r, int d_c, RopeTable rope, float scale_log2e) {
   extern __shared__ __attribute__((aligned(16))) char qsm[];
   const int nd = d_h - 2 * r;
   const int ndp = nd + 8;                                  // padded row: breaks the LDS bank period
-  const int half = d_h / 2;
+  const int half = d_h / 2;                                // <= 64 (checked on the host)
   uint16_t* qne = reinterpret_cast<uint16_t*>(qsm);        // [BT][n_h][ndp] bf16 bits
-  int16_t* nepos = reinterpret_cast<int16_t*>(qsm + (size_t)kQpBatchTile * n_h * ndp * 2);  // [n_h][half]
+  uint64_t* emask = reinterpret_cast<uint64_t*>(qsm + (size_t)BT * n_h * ndp * 2);   // [n_h]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b0 = blockIdx.y * kQpBatchTile;
-  const int bt_n = min(kQpBatchTile, B - b0);
+  const int b0 = blockIdx.y * BT;
+  const int bt_n = min(BT, B - b0);
 
-  // this thread's weight row is requested before anything else (nd <= 128: at most 16 chunks)
+  // this thread's weight row (latent column k, head h) is requested before anything else
   const int64_t row = (int64_t)blockIdx.x * kQpThreads + tid;
   const bool row_ok = row < (int64_t)d_c * n_h;
-  const int nchunk = nd / 8;
+  const int nchunk = nd / 8;                               // <= 16
   uint4 wreg[16];
   {
     const uint4* wrow = reinterpret_cast<const uint4*>(W_uk + (row_ok ? row : 0) * nd);
@@ -46,10 +49,8 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
     }
   }
 
-  // position of every non-elite chunk inside the compacted query (-1 for elite chunks); half <= 64
-  // (elite mask per head built in LDS first: one coalesced read of the index table)
-  uint64_t* emask = reinterpret_cast<uint64_t*>(qsm + (size_t)kQpBatchTile * n_h * ndp * 2 +
-                                                (size_t)n_h * half * 2);          // [n_h]
+  // elite mask per head (one coalesced read of the index table), then the compacted non-elite
+  // query: wave <-> head, lane <-> chunk; a ballot gives every non-elite chunk its position
   for (int h = tid; h < n_h; h += kQpThreads) emask[h] = 0ull;
   __syncthreads();
   for (int e = tid; e < n_h * r; e += kQpThreads) {
@@ -57,26 +58,21 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
     if (i >= 0 && i < half) atomicOr(reinterpret_cast<unsigned long long*>(&emask[e / r]), 1ull << i);
   }
   __syncthreads();
+  const uint32_t* q32 = reinterpret_cast<const uint32_t*>(q);
   for (int h = wave; h < n_h; h += kQpThreads / 64) {
-    const bool el = (emask[h] >> lane) & 1ull;
-    const bool live = lane < half && !el;
+    const bool live = lane < half && !((emask[h] >> lane) & 1ull);
     const uint64_t mask = __ballot(live);
     const int pos = __popcll(mask & ((1ull << lane) - 1ull));
-    if (lane < half) nepos[h * half + lane] = live ? (int16_t)pos : (int16_t)-1;
+    if (live) {
+#pragma unroll
+      for (int bt = 0; bt < BT; ++bt)
+        if (bt < bt_n)
+          reinterpret_cast<uint32_t*>(qne + ((size_t)bt * n_h + h) * ndp)[pos] =
+              q32[((int64_t)(b0 + bt) * n_h + h) * half + lane];
+    }
   }
-  __syncthreads();
-  const uint32_t* q32 = reinterpret_cast<const uint32_t*>(q);
-  for (int e = tid; e < bt_n * n_h * half; e += kQpThreads) {
-    const int c = e % half, h = (e / half) % n_h, bt = e / (half * n_h);
-    const int pos = nepos[h * half + c];
-    if (pos >= 0)
-      reinterpret_cast<uint32_t*>(qne + ((size_t)bt * n_h + h) * ndp)[pos] =
-          q32[(((int64_t)(b0 + bt) * n_h + h) * d_h) / 2 + c];
-  }
-  // the rotated elite query is written by the first column block only; it also clears the
-  // arrival counters the merge kernel of this call will use
+  // the rotated elite query is written by the first column block only
   if (blockIdx.x == 0) {
-    for (int e = tid; e < bt_n * n_h; e += kQpThreads) counters[(int64_t)b0 * n_h + e] = 0u;
     for (int e = tid; e < bt_n * n_h * r; e += kQpThreads) {
       const int j = e % r, h = (e / r) % n_h, b = b0 + e / (r * n_h);
       int i = elite_idx[h * r + j];
@@ -93,10 +89,10 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
   __syncthreads();
 
   if (!row_ok) return;
-  const int k = (int)(row / n_h), h = (int)(row % n_h);
-  float acc[kQpBatchTile];
+  const int k = (int)((uint32_t)row / (uint32_t)n_h), h = (int)((uint32_t)row % (uint32_t)n_h);
+  float acc[BT];
 #pragma unroll
-  for (int bt = 0; bt < kQpBatchTile; ++bt) acc[bt] = 0.f;
+  for (int bt = 0; bt < BT; ++bt) acc[bt] = 0.f;
 #pragma unroll
   for (int c = 0; c < 16; ++c) {
     if (c < nchunk) {
@@ -108,44 +104,47 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
         w[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u);
       }
 #pragma unroll
-      for (int bt = 0; bt < kQpBatchTile; ++bt) {
-        if (bt < bt_n) {
-          const uint4 qv = *reinterpret_cast<const uint4*>(qne + ((size_t)bt * n_h + h) * ndp + 8 * c);
-          const uint32_t qq[4] = {qv.x, qv.y, qv.z, qv.w};
-          float a = acc[bt];
+      for (int bt = 0; bt < BT; ++bt) {
+        const uint4 qv = *reinterpret_cast<const uint4*>(qne + ((size_t)bt * n_h + h) * ndp + 8 * c);
+        const uint32_t qq[4] = {qv.x, qv.y, qv.z, qv.w};
+        float a = acc[bt];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            a = fmaf(w[2 * i], __uint_as_float(qq[i] << 16), a);
-            a = fmaf(w[2 * i + 1], __uint_as_float(qq[i] & 0xffff0000u), a);
-          }
-          acc[bt] = a;
+        for (int i = 0; i < 4; ++i) {
+          a = fmaf(w[2 * i], __uint_as_float(qq[i] << 16), a);
+          a = fmaf(w[2 * i + 1], __uint_as_float(qq[i] & 0xffff0000u), a);
         }
+        acc[bt] = a;
       }
     }
   }
 #pragma unroll
-  for (int bt = 0; bt < kQpBatchTile; ++bt)
+  for (int bt = 0; bt < BT; ++bt)
     if (bt < bt_n) st(qt, ((int64_t)(b0 + bt) * n_h + h) * d_c + k, acc[bt] * scale_log2e);
 }
 
-hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, uint32_t* counters,
-                             hipStream_t stream) {
+template <int BT>
+static hipError_t launch_qprep_bt(const DecodeArgs& a, float* qe, bf16_t* qt, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
   const int nd = d.head_dim - 2 * d.r;
-  const size_t sm = (size_t)kQpBatchTile * d.n_heads * (nd + 8) * 2 + (size_t)d.n_heads * (d.head_dim / 2) * 2 +
-                    (size_t)d.n_heads * 8;
+  const size_t sm = (size_t)BT * d.n_heads * (nd + 8) * 2 + (size_t)d.n_heads * 8;   // < 64 KiB for n_h <= 32
   const int64_t rows = (int64_t)d.d_c * d.n_heads;
-  const dim3 grid((unsigned)((rows + kQpThreads - 1) / kQpThreads),
-                  (unsigned)((a.B + kQpBatchTile - 1) / kQpBatchTile));
+  const dim3 grid((unsigned)((rows + kQpThreads - 1) / kQpThreads), (unsigned)((a.B + BT - 1) / BT));
   if (sm > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&qprep_rows_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&qprep_rows_kernel<BT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
     if (e != hipSuccess) return e;
   }
-  qprep_rows_kernel<<<grid, kQpThreads, sm, stream>>>(
-      (const bf16_t*)a.q, a.q_pos, (const bf16_t*)a.W_uk, a.elite_idx, qe, qt, counters, (int)a.B, d.n_heads,
-      d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim), kLog2e / sqrtf((float)d.head_dim));
+  qprep_rows_kernel<BT><<<grid, kQpThreads, sm, stream>>>(
+      (const bf16_t*)a.q, a.q_pos, (const bf16_t*)a.W_uk, a.elite_idx, qe, qt, (int)a.B, d.n_heads, d.head_dim,
+      d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim), kLog2e / sqrtf((float)d.head_dim));
   return hipGetLastError();
+}
+
+hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, hipStream_t stream) {
+  if (a.B == 1) return launch_qprep_bt<1>(a, qe, qt, stream);
+  if (a.B == 2) return launch_qprep_bt<2>(a, qe, qt, stream);
+  if (a.B <= 4) return launch_qprep_bt<4>(a, qe, qt, stream);
+  return launch_qprep_bt<kQpBatchTile>(a, qe, qt, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -226,8 +225,7 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   const float Lsum = (red[0] + red[1]) + (red[2] + red[3]);
   const float inv = (Lsum > 0.f) ? 1.f / Lsum : 0.f;
 
-  // (4) merged latent of this chunk.  An empty split has weight 0 and an unwritten accumulator:
-  // it is loaded like the others but kept out of the sum.
+  // (4) merged latent of this chunk (an empty split has weight 0 and a zero accumulator)
   float acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
@@ -236,14 +234,11 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
     for (int u = 0; u < UB; ++u) {
       const int s = s0 + sg + u * NG;
       const float w = (grp_ok && s < n_splits) ? wsp[s] : 0.f;
-      const bool live = w != 0.f;
       const uint32_t uu[4] = {ureg[u].x, ureg[u].y, ureg[u].z, ureg[u].w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float lo = fmaf(w, __uint_as_float(uu[i] << 16), acc[2 * i]);
-        const float hi = fmaf(w, __uint_as_float(uu[i] & 0xffff0000u), acc[2 * i + 1]);
-        acc[2 * i] = live ? lo : acc[2 * i];
-        acc[2 * i + 1] = live ? hi : acc[2 * i + 1];
+        acc[2 * i] = fmaf(w, __uint_as_float(uu[i] << 16), acc[2 * i]);
+        acc[2 * i + 1] = fmaf(w, __uint_as_float(uu[i] & 0xffff0000u), acc[2 * i + 1]);
       }
     }
     if (s0 + UB * NG < n_splits) load_batch(s0 + UB * NG);

@@ -80,7 +80,7 @@ hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_generic(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 bool decode_mfma_supported(const elitekv_dims& d);
 struct bf16_t;
-hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, uint32_t* counters,
+hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt,
                              hipStream_t stream);
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
