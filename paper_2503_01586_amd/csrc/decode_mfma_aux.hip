@@ -59,16 +59,29 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
   }
   __syncthreads();
   const uint32_t* q32 = reinterpret_cast<const uint32_t*>(q);
-  for (int h = wave; h < n_h; h += kQpThreads / 64) {
-    const bool live = lane < half && !((emask[h] >> lane) & 1ull);
-    const uint64_t mask = __ballot(live);
-    const int pos = __popcll(mask & ((1ull << lane) - 1ull));
-    if (live) {
+  for (int h0 = wave; h0 < n_h; h0 += 8 * (kQpThreads / 64)) {
+    // eight heads per pass: all query loads are issued before any of them is used
+    uint32_t qv[8][BT];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int h = h0 + i * (kQpThreads / 64);
 #pragma unroll
       for (int bt = 0; bt < BT; ++bt)
-        if (bt < bt_n)
-          reinterpret_cast<uint32_t*>(qne + ((size_t)bt * n_h + h) * ndp)[pos] =
-              q32[((int64_t)(b0 + bt) * n_h + h) * half + lane];
+        qv[i][bt] = (h < n_h && bt < bt_n && lane < half) ? q32[((int64_t)(b0 + bt) * n_h + h) * half + lane] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int h = h0 + i * (kQpThreads / 64);
+      if (h < n_h) {                                      // uniform over the wave
+        const bool live = lane < half && !((emask[h] >> lane) & 1ull);
+        const uint64_t mask = __ballot(live);
+        const int pos = __popcll(mask & ((1ull << lane) - 1ull));
+        if (live) {
+#pragma unroll
+          for (int bt = 0; bt < BT; ++bt)
+            reinterpret_cast<uint32_t*>(qne + ((size_t)bt * n_h + h) * ndp)[pos] = qv[i][bt];
+        }
+      }
     }
   }
   // the rotated elite query is written by the first column block only
@@ -167,7 +180,7 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   constexpr int LPW = DH / 8;              // lanes that cover one W_uv row
   constexpr int RPI = 64 / LPW;            // W_uv rows per wave instruction
   constexpr int NWI = CW / (4 * RPI);      // W_uv rows per thread
-  constexpr int UB = 16;                   // split accumulators requested per batch
+  constexpr int UB = 28;                   // split accumulators requested per batch
   extern __shared__ __attribute__((aligned(16))) float msm[];
   float* wsp = msm;                        // [n_splits] merge weights of this head
   float* red = wsp + n_splits;             // [256] scratch
