@@ -42,6 +42,7 @@ struct AttnMfmaParams {
   float* part_l;          // [B, n_splits, HG*32]        split sums
   bf16_t* part_u;         // [B, n_splits, HG*32, d_c]   split latent accumulators, head-major
   int n_h, d_c, n_splits, chunk, head_groups;
+  int batch, pair_map;    // pair_map: 1-D grid, the two head groups of an item share an XCD
   int64_t max_seq_len, batch_stride_rows, plane_rows;
 };
 
@@ -51,14 +52,21 @@ struct AttnMfmaParams {
 // swz(row) = ((row & 3) << 1) | ((row >> 2) & 1): eight rows read at one logical chunk hit eight
 // different bank groups (row-wise b128 reads), and the 4 rows x 32 bytes a transposed b64 read
 // covers hit four different 32-byte bank groups.
+// A slice whose width is an odd multiple of 32 columns ends in one half-width block of
+// 16 rows x 64 bytes (again 1 KiB, one load) behind the full blocks, chunk index XOR-ed with
+// half_swz(row).
+// The elite keys of a tile are double-buffered like the latent tile when the LDS has room for it;
+// otherwise there is one buffer, refilled for the next tile as soon as the wave has read it.
 template <int NW, int DC_W, int TWO_R>
 struct AttnMfmaLayout {
-  static_assert(DC_W % 64 == 0, "a wave's latent slice must be a whole number of 128-byte blocks");
+  static_assert(DC_W % 32 == 0, "a wave's latent slice must be a whole number of 32-column MFMA steps");
   static_assert(NW == 2 || NW == 4 || NW == 8, "16 tokens are divided evenly among the waves");
   static constexpr int KS = DC_W / 32;                      // score k-steps per wave (K = 32)
   static constexpr int CT = DC_W / 32;                      // 32-column accumulator tiles per wave
-  static constexpr int NCB = DC_W / 64;                     // 128-byte column blocks per row
-  static constexpr int NLOAD = 2 * NCB;                     // direct-to-LDS loads per tile per wave
+  static constexpr int NCB = DC_W / 64;                     // full 128-byte column blocks per row
+  static constexpr int HALF = (DC_W % 64) / 32;             // 1: a trailing half-width block
+  static constexpr int NLOAD = 2 * NCB + HALF;              // direct-to-LDS loads per tile per wave
+  static constexpr int HALF_OFF = 2 * NCB * 1024;           // the half-width block inside the slice
   static constexpr int WTILE = NLOAD * 1024;                // LDS bytes of one wave's tile slice
   static constexpr int TILE_BYTES = NW * WTILE;             // one buffer
   static constexpr int TPW = kTile / NW;                    // tokens each wave finalises
@@ -73,14 +81,19 @@ struct AttnMfmaLayout {
   static constexpr int NKE = (TPW * KE_CPT + 63) / 64;      // direct-to-LDS loads per tile per wave
   static constexpr int KE_W = NKE * 1024;                   // LDS bytes of one wave's elite slice
   static constexpr int KE_BYTES = NW * KE_W;                // one buffer
+  static constexpr int kLdsMax = 160 * 1024;                // LDS of a gfx950 compute unit
+  static constexpr int X1_PAD = (X1 + 15) / 16 * 16;
+  static constexpr int KE_BUFS = (2 * TILE_BYTES + 2 * KE_BYTES + X1_PAD + X2 <= kLdsMax) ? 2 : 1;
   static constexpr int KE_OFF = 2 * TILE_BYTES;
-  static constexpr int X1_OFF = KE_OFF + 2 * KE_BYTES;
-  static constexpr int X2_OFF = X1_OFF + (X1 + 15) / 16 * 16;
+  static constexpr int X1_OFF = KE_OFF + KE_BUFS * KE_BYTES;
+  static constexpr int X2_OFF = X1_OFF + X1_PAD;
   static constexpr int LDS_BYTES = X2_OFF + X2;
-  static_assert(LDS_BYTES <= 160 * 1024, "exceeds the 160 KiB of LDS of a gfx950 compute unit");
+  static_assert(LDS_BYTES <= kLdsMax, "exceeds the 160 KiB of LDS of a gfx950 compute unit");
 };
 
 __device__ __forceinline__ int tile_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// half-width block (16 rows x 4 chunks): rows two apart differ in the 32-byte pair they use
+__device__ __forceinline__ int half_swz(int row) { return (((row >> 1) & 1) << 1) | ((row >> 2) & 1); }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -112,14 +125,30 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   using L = AttnMfmaLayout<NW, DC_W, TWO_R>;
   constexpr int KS = L::KS, CT = L::CT, NCB = L::NCB, EPL = L::EPL, TPW = L::TPW;
   constexpr int KCH = TWO_R / 8;                 // 16-byte chunks of one head's elite key
-  constexpr int IN_FLIGHT = L::NLOAD + L::NKE;   // direct-to-LDS loads one tile issues per wave
+  constexpr bool KE2 = L::KE_BUFS == 2 || TWO_R == 0;
+  // direct-to-LDS loads that may still be in flight when a tile is consumed: with two elite-key
+  // buffers the whole next tile, with one only its latent part (its elite keys are requested in
+  // the middle of the current tile, before the latent loads of the tile after)
+  constexpr int IN_FLIGHT = KE2 ? L::NLOAD + (TWO_R > 0 ? L::NKE : 0) : L::NLOAD;
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
-  const int split = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
+  int split = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
+  if (p.pair_map) {
+    // Two head groups read the same latent rows.  Work-groups go to the eight XCDs round-robin by
+    // linear index, so indices i and i + 8 land on the same XCD back to back: they are given the
+    // two head groups of one (split, batch row) item, and the second reader of a row finds it in
+    // that XCD's L2 instead of fetching it from HBM again.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int item = (slot >> 1) * 8 + xcd;
+    if (item >= p.n_splits * p.batch) return;
+    hg = slot & 1;
+    split = item % p.n_splits;
+    b = item / p.n_splits;
+  }
   char* ctile0 = smem + wave * L::WTILE;                 // buffer 0; buffer 1 is TILE_BYTES further
-  char* ketile0 = smem + L::KE_OFF + wave * L::KE_W;     // buffer 0; buffer 1 is KE_BYTES further
+  char* ketile0 = smem + L::KE_OFF + wave * L::KE_W;     // buffer 0; buffer 1 (if any) is KE_BYTES further
   float* x1 = reinterpret_cast<float*>(smem + L::X1_OFF);
   float* x2 = reinterpret_cast<float*>(smem + L::X2_OFF);
 
@@ -187,6 +216,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   const int ld_row = lane >> 3;
   const char* cbase = reinterpret_cast<const char*>(p.c_plane) + (int64_t)wave * DC_W * 2 +
                       (((lane & 7) ^ tile_swz(ld_row)) << 4);
+  const char* hbase = reinterpret_cast<const char*>(p.c_plane) + ((int64_t)wave * DC_W + NCB * 64) * 2 +
+                      (((lane & 3) ^ half_swz(lane >> 2)) << 4);
   // elite-key loader: slot c = i*64 + lane of the wave's slice is (token c / KE_CPT, chunk c % KE_CPT)
   const char* kbase = reinterpret_cast<const char*>(p.ke_plane);
 
@@ -208,10 +239,18 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
     for (int par = 0; par < 2; ++par)
       tr_off[e][par] = tr_base + r8 * 128 + ((((par << 2) | tr_lo) ^ tile_swz(r8)) << 4);
   }
+  // the same two reads inside the half-width block (row-major 16 x 64 bytes)
+  const int ah_off = L::HALF_OFF + i16 * 64 + ((q16 ^ half_swz(i16)) << 4);
+  int trh_off[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const int row = 8 * (q16 >> 1) + 4 * e + (i16 >> 2);
+    trh_off[e] = L::HALF_OFF + row * 64 + ((tr_lo ^ half_swz(row)) << 4) + ((i16 & 1) << 3);
+  }
   // stage-2 ownership: this wave finalises tokens wave*TPW + g + 2*e (e < EPL) for head n
   const int own_t0 = wave * TPW + g;
 
-  auto issue = [&](int64_t tile_t0, char* ctile, char* ketile) {
+  auto issue_c = [&](int64_t tile_t0, char* ctile) {
     const uint32_t cl = __builtin_amdgcn_readfirstlane(lds_addr(ctile));
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
@@ -220,6 +259,13 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) dma16<0>(gp + cb * 128, cl + (rb * NCB + cb) * 1024);
     }
+    if (L::HALF) {   // lane l fills slot (row l/4, position l%4) of the half-width block
+      const int hr = lane >> 2;
+      const int64_t t = min(tile_t0 + hr, t_end - 1);
+      dma16<0>(hbase + (row0 + t) * crow_bytes, cl + L::HALF_OFF);
+    }
+  };
+  auto issue_ke = [&](int64_t tile_t0, char* ketile) {
     if (TWO_R > 0) {
       const uint32_t kl = __builtin_amdgcn_readfirstlane(lds_addr(ketile));
 #pragma unroll
@@ -232,13 +278,19 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
       }
     }
   };
+  auto issue = [&](int64_t tile_t0, char* ctile, char* ketile) {
+    issue_c(tile_t0, ctile);
+    if (KE2) issue_ke(tile_t0, ketile);
+  };
 
-  auto compute = [&](int64_t tile, const char* ctile, const char* ketile) {
+  auto compute = [&](int64_t tile, const char* ctile, char* ketile, int64_t next_tile) {
     // ---- partial scores over this wave's latent slice, two head halves
     f32x4 sd[2] = {(f32x4)(0.f), (f32x4)(0.f)};
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(ctile + (ks >> 1) * 1024 + ((ks & 1) ? a_c1 : a_c0));
+      if (KS > 8 && ks % 4 == 0) asm volatile("" ::: "memory");   // wide slices: bound the operand look-ahead
+      const int aoff = (L::HALF && ks == 2 * NCB) ? ah_off : (ks >> 1) * 1024 + ((ks & 1) ? a_c1 : a_c0);
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(ctile + aoff);
       sd[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Qb[ks][0], sd[0], 0, 0, 0);
       sd[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Qb[ks][1], sd[1], 0, 0, 0);
     }
@@ -270,6 +322,10 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
       fin[e] = d;
     }
     __syncthreads();
+    if (!KE2 && next_tile < t_end) {   // single elite-key buffer: this wave has read its slice
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      issue_ke(next_tile, ketile);
+    }
     // ---- stage 2: sum the NW partials in a fixed order, publish as x2[head][token]
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
@@ -308,15 +364,36 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
     l_run = l_run * alpha + psum;
     m_run = m_new;
     if (__any(alpha != 1.f)) {
+      if (CT > 8) {
+        // Wide slices keep their many accumulator tiles in the accumulation registers (AGPRs).
+        // Rescaling them as ordinary vector arithmetic would make the compiler hold every tile in
+        // VGPRs across the whole loop; the explicit moves pin them to AGPRs instead.
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) uacc[ct] *= alpha;
+        for (int ct = 0; ct < CT; ++ct) {
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            float y, z;
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(y) : "a"(uacc[ct][j]));
+            y *= alpha;
+            asm volatile("v_accvgpr_write_b32 %0, %1\n\ts_nop 2" : "=a"(z) : "v"(y));   // + wait states before an MFMA reads it
+            uacc[ct][j] = z;
+          }
+        }
+      } else {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) uacc[ct] *= alpha;
+      }
     }
     // ---- latent accumulation: U^T += C^T P^T, the tile read transposed from LDS
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-      const char* trp = ctile + (ct >> 1) * 1024;
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(trp + tr_off[0][ct & 1]));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(trp + tr_off[1][ct & 1]));
+      if (CT > 8 && ct % 4 == 0) asm volatile("" ::: "memory");
+      const bool in_half = L::HALF && ct == 2 * NCB;
+      const char* trp = ctile + (in_half ? 0 : (ct >> 1) * 1024);
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_t*)(trp + (in_half ? trh_off[0] : tr_off[0][ct & 1])));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_t*)(trp + (in_half ? trh_off[1] : tr_off[1][ct & 1])));
       const s16x8 a16 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       uacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a16), P, uacc[ct], 0, 0, 0);
     }
@@ -324,8 +401,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
 
   // two tiles per trip so that buffer and register-set indices are compile-time
   char* ctile1 = ctile0 + L::TILE_BYTES;
-  char* ketile1 = ketile0 + L::KE_BYTES;
-  issue(t0, ctile0, ketile0);
+  char* ketile1 = KE2 ? ketile0 + L::KE_BYTES : ketile0;
+  issue_c(t0, ctile0);
+  issue_ke(t0, ketile0);
   load_query();   // after the first tile's loads are in flight
   for (int64_t tile = t0; tile < t_end; tile += 2 * t_step) {
     const int64_t t1 = tile + t_step, t2 = tile + 2 * t_step;
@@ -336,7 +414,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    compute(tile, ctile0, ketile0);
+    compute(tile, ctile0, ketile0, t1);
     if (t1 >= t_end) break;
     if (t2 < t_end) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -345,7 +423,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    compute(t1, ctile1, ketile1);
+    compute(t1, ctile1, ketile1, t2);
   }
 
   // ---- write this split's partial (m, l, U)
@@ -377,7 +455,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
     const int idx = i * 64 + lane;
     const int row = idx / CPRW, ch = idx % CPRW;
     const uint4 v = *reinterpret_cast<const uint4*>(tt + row * TSTR + ch * 16);
-    *reinterpret_cast<uint4*>(ubase + (int64_t)row * p.d_c * 2 + ch * 16) = v;
+    if (hg * 32 + row < p.n_h) *reinterpret_cast<uint4*>(ubase + (int64_t)row * p.d_c * 2 + ch * 16) = v;
   }
 }
 
@@ -392,8 +470,9 @@ static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t 
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  attn_mfma_kernel<NW, DC_W, TWO_R>
-      <<<dim3(prm.n_splits, prm.head_groups, (unsigned)B), NW * 64, L::LDS_BYTES, stream>>>(prm);
+  const dim3 grid = prm.pair_map ? dim3((unsigned)((prm.n_splits * B + 7) / 8 * 16), 1, 1)
+                                 : dim3(prm.n_splits, prm.head_groups, (unsigned)B);
+  attn_mfma_kernel<NW, DC_W, TWO_R><<<grid, NW * 64, L::LDS_BYTES, stream>>>(prm);
   return hipGetLastError();
 }
 
@@ -402,7 +481,7 @@ bool decode_mfma_supported(const elitekv_dims& d) {
   if ((d.head_dim != 128 && d.head_dim != 64) || (d.head_dim - 2 * d.r) % 8) return false;
   const int two_r = 2 * d.r;
   if (two_r != 8 && two_r != 16) return false;
-  return d.d_c == 1536 || d.d_c == 768 || d.d_c == 256;
+  return d.d_c == 1920 || d.d_c == 1536 || d.d_c == 768 || d.d_c == 256;
 }
 
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
@@ -417,6 +496,7 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.n_h = d.n_heads; prm.d_c = d.d_c; prm.n_splits = p.n_splits; prm.chunk = p.chunk;
   prm.head_groups = p.head_groups; prm.max_seq_len = a.max_seq_len;
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
+  prm.batch = (int)a.B; prm.pair_map = p.head_groups == 2 ? 1 : 0;
 
   hipError_t e = launch_qprep_rows(a, qe, qt, stream);
   if (e != hipSuccess) return e;
@@ -429,6 +509,7 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
     e = two_r == 16 ? launch_attn<NWV, DCW, 16>(prm, a.B, stream)                     \
                     : launch_attn<NWV, DCW, 8>(prm, a.B, stream);                     \
   }
+  EKV_CASE(1920, 4, 480)
   EKV_CASE(1536, 8, 192)
   EKV_CASE(768, 4, 192)
   EKV_CASE(256, 4, 64)

@@ -99,6 +99,8 @@ DECODE_CASES = {
     "bf16_7b": (shape(64, 32, 128, 8, 1536, "bf16"), [300, 1, 257], [0, 1, 4]),
     "bf16_7b_12pct": (shape(64, 32, 128, 4, 768, "bf16"), [130, 64], [0, 3]),
     "bf16_13b": (shape(64, 40, 128, 8, 1920, "bf16"), [97, 160], [0, 2]),
+    "bf16_13b_ragged_batch": (shape(64, 40, 128, 8, 1920, "bf16"), [0, 1, 15, 16, 17, 250, 33, 48, 100], [0, 3, 5]),
+    "bf16_13b_r4": (shape(64, 40, 128, 4, 1920, "bf16"), [130, 31], [0, 2]),
     "bf16_small_heads": (shape(64, 8, 64, 4, 128, "bf16"), [70], [0, 2]),
     "bf16_few_heads_256": (shape(64, 8, 64, 4, 256, "bf16"), [70, 33, 0], [0, 2]),
     "bf16_two_head_groups": (shape(64, 40, 128, 8, 1536, "bf16"), [97, 160], [0, 2]),
@@ -137,6 +139,36 @@ def test_decode_matches_oracle_on_same_planes(name):
     # the split count changes rounding only
     for o in outs[1:]:
         assert orc.max_abs_rel(o, outs[0]) <= TOL[dt]
+
+
+@pytest.mark.parametrize("d_c,n_heads", [(1536, 32), (768, 32), (1920, 40)])
+def test_decode_with_scores_that_keep_rising(d_c, n_heads):
+    """The running maximum of the online softmax has to be raised many times along the sequence:
+    the latent rows are multiples g(j) of one direction, so every head's score is g(j) times a
+    per-head constant (rising for some heads, falling for the others)."""
+    sh = shape(64, n_heads, 128, 8, d_c, "bf16")
+    S = 700
+    rng, idx, _, _, W_uk, W_uv, _, q = _draw(sh, 1, 1, 77)
+    ke64, c64 = synth.draw_cache_planes(rng, S, n_heads, sh["r"], d_c)
+    v = rng.standard_normal(d_c)
+    g = np.linspace(0.0, 15.0, S) + 0.3 * np.sin(np.arange(S))
+    c64 = 0.05 * c64 + g[:, None] * v[None, :]
+    dims = dims_of(sh)
+    ked, cd, qd, Wukd, Wuvd = dev(ke64, "bf16"), dev(c64, "bf16"), dev(q, "bf16"), dev(W_uk, "bf16"), dev(W_uv, "bf16")
+    ref = orc.decode_attn(host64(qd), [S - 1], host64(ked).reshape(1, S, n_heads, -1), host64(cd).reshape(1, S, -1),
+                          [S], host64(Wukd), host64(Wuvd), idx, 128, sh["rope_base"])
+    # the scores of the test really span far more than the rescale slack
+    q64, Wuk64, c_r = host64(qd)[0], host64(Wukd), host64(cd)
+    rise = []
+    for h in range(n_heads):
+        qt_h = Wuk64[:, h, :] @ q64[h, orc.nonelite_dims(idx[h], 128)]
+        s_h = (c_r @ qt_h) * np.log2(np.e) / np.sqrt(128.0)
+        rise.append(s_h[-1] - s_h[0])
+    assert max(rise) > 24.0 and min(rise) < -24.0          # in the log2 domain; the kernels' slack is 8
+    for ns in (1, 3):
+        out = host64(gpu_decode(dims, qd, i32([S - 1]), i32([S]), S, S, Wukd, Wuvd, i32(idx), ked, cd, n_splits=ns))
+        assert np.all(np.isfinite(out))
+        assert orc.max_abs_rel(out, ref) <= TOL["bf16"], "n_splits=%d" % ns
 
 
 def test_decode_is_bitwise_repeatable():
