@@ -69,7 +69,8 @@ static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_
     p->off_m = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_l = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_u = off;  off = align_up(off + np * 32 * dc * 2, 256);
-    p->up_cw = (d->d_c % 192 == 0) ? 192 : 64;
+    p->merge_batch = merge_batch_supported(*d, B, ns) ? 1 : 0;
+    p->up_cw = p->merge_batch ? 128 : (d->d_c % 192 == 0) ? 192 : 64;
     p->off_opart = off;
     off = align_up(off + Bz * nh * (size_t)(d->d_c / p->up_cw) * d->head_dim * sizeof(float), 256);
     p->off_cnt = off;

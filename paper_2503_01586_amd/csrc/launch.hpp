@@ -16,6 +16,7 @@ struct DecodePlan {
   int32_t mfma;         // 1: bf16 MFMA kernels, 0: generic VALU kernels
   int32_t head_groups;  // MFMA path: groups of up to 32 heads
   int32_t up_cw;        // MFMA path: latent columns per merge/up-projection work-group
+  int32_t merge_batch;  // MFMA path: 1 = the merge kernel that takes all batch rows per work-group
   size_t off_qe;        // rotated, scaled elite query      fp32 [B, n_h, 2r]
   size_t off_qt;        // absorbed, scaled latent query    fp32 [B, n_h, d_c] (generic) / bf16 (mfma)
   size_t off_m;         // split maxima (log2 domain)       fp32 [B, n_splits, n_h_pad]
@@ -82,6 +83,7 @@ bool decode_mfma_supported(const elitekv_dims& d);
 struct bf16_t;
 hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt,
                              hipStream_t stream);
+bool merge_batch_supported(const elitekv_dims& d, int64_t B, int64_t n_splits);
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);
