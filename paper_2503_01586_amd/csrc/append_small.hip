@@ -180,9 +180,15 @@ hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream) {
 #undef EKV_AS
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  return launch_append_finish(a, partial, ks, stream);
+}
+
+hipError_t launch_append_finish(const AppendArgs& a, const float* partial, int ksplit, hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  const int N = 2 * d.r * d.n_heads + d.d_c;
   append_finish_kernel<<<dim3((unsigned)a.T, (N + 255) / 256), 256, 0, stream>>>(
       partial, a.pos, a.slot, a.T, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
-      d.n_heads, d.head_dim, d.r, d.d_c, ks, make_rope_table(d.rope_base, d.head_dim));
+      d.n_heads, d.head_dim, d.r, d.d_c, ksplit, make_rope_table(d.rope_base, d.head_dim));
   return hipGetLastError();
 }
 

@@ -168,6 +168,7 @@ int elitekv_validate_elite_idx(const elitekv_dims* dims, const int32_t* idx_host
 
 size_t elitekv_append_workspace_bytes(const elitekv_dims* dims, int64_t T) {
   if (check_dims(dims) || T < 0) return 0;
+  if (T > 0 && append_skinny_supported(*dims, T)) return align_up(append_skinny_workspace(*dims, T), 256);
   if (T > 0 && append_small_supported(*dims, T)) return align_up(append_small_workspace(*dims, T), 256);
   return 0;
 }
@@ -193,8 +194,10 @@ int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, 
   a.dims = *dims; a.x = x; a.pos = pos; a.slot = slot; a.T = T; a.W_ke = W_ke; a.W_dkv = W_dkv;
   a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows;
   a.ws = (char*)ws;
-  const hipError_t e = append_small_supported(*dims, T) ? launch_append_small(a, (hipStream_t)hip_stream)
-                                                        : launch_append_generic(a, (hipStream_t)hip_stream);
+  const hipStream_t stream = (hipStream_t)hip_stream;
+  const hipError_t e = append_skinny_supported(*dims, T) ? launch_append_skinny(a, stream)
+                       : append_small_supported(*dims, T) ? launch_append_small(a, stream)
+                                                          : launch_append_generic(a, stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
 }
 

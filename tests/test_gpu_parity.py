@@ -34,6 +34,10 @@ APPEND_CASES = {
     "bf16_7b_decode_step": (shape(4096, 32, 128, 8, 1536, "bf16"), 8, 32767),
     "bf16_7b_64_tokens": (shape(4096, 32, 128, 8, 1536, "bf16"), 64, 4095),
     "bf16_odd_hidden": (shape(1000, 32, 128, 8, 1536, "bf16"), 5, 100),
+    "bf16_odd_hidden_batch": (shape(1000, 32, 128, 8, 1536, "bf16"), 24, 100),
+    "bf16_13b_batch_16": (shape(5120, 40, 128, 8, 1920, "bf16"), 16, 8191),
+    "bf16_7b_12pct_batch_64": (shape(4096, 32, 128, 4, 768, "bf16"), 64, 2047),
+    "bf16_7b_batch_40": (shape(4096, 32, 128, 8, 1536, "bf16"), 40, 4095),
 }
 
 
