@@ -189,4 +189,211 @@ hipError_t launch_append_skinny(const AppendArgs& a, hipStream_t stream) {
   return launch_append_finish(a, partial, ks, stream);
 }
 
+// ---------------------------------------------------------------------------------------------
+// append_gemm: prefill-sized appends (T > 64).  A dense contraction bounded by the matrix cores.
+// Work-group tile: 128 output columns x (64 * WN) tokens, 2 x 2 waves, each wave 64 columns x
+// (32 * WN) tokens = 2 x WN accumulator tiles of 32 x 32.  Both operands go through LDS in
+// double-buffered stages of 64 contraction rows (global -> registers -> LDS, the loads of stage
+// s+1 in flight while stage s is multiplied).  The epilogue rotates the elite pairs in registers
+// (a lane holds one token and four consecutive columns per group) and stores bf16 rows straight
+// into the cache planes.
+// ---------------------------------------------------------------------------------------------
+constexpr int kGmCols = 128;                   // output columns per work-group
+constexpr int kGmStage = 64;                   // contraction rows per stage
+constexpr int kGmARow = kGmCols * 2 + 32;      // bytes of a staged weight row [k][128 n] (+ bank spread)
+constexpr int kGmBRow = kGmStage * 2 + 16;     // bytes of a staged token row [t][64 k] (+ bank spread)
+
+template <int WN>
+struct GemmLayout {
+  static constexpr int BN = 64 * WN;                          // tokens per work-group
+  static constexpr int A_BYTES = kGmStage * kGmARow;
+  static constexpr int B_BYTES = BN * kGmBRow;
+  static constexpr int STAGE = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int NB = BN * 8 / 256;                     // 16-byte token pieces per thread per stage
+};
+
+template <int WN>
+__global__ __launch_bounds__(256) void append_gemm_kernel(
+    const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
+    const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const int32_t* __restrict__ elite_idx,
+    bf16_t* __restrict__ ke_plane, bf16_t* __restrict__ c_plane, int64_t plane_rows, int d, int n_h, int d_h,
+    int r, int d_c, RopeTable rope) {
+  using L = GemmLayout<WN>;
+  extern __shared__ __attribute__((aligned(16))) char gsm[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;                    // wave's 64-column half, token half
+  const int n32 = lane & 31, hi = lane >> 5, i16 = lane & 15, q16 = lane >> 4;
+  const int NE = 2 * r * n_h;
+  const int n0 = blockIdx.x * kGmCols;
+  const int64_t t0 = (int64_t)blockIdx.y * L::BN;
+  const int nstages = (d + kGmStage - 1) / kGmStage;
+
+  const bf16_t* wbase;
+  int64_t wstride;
+  if (n0 < NE) { wbase = W_ke + n0; wstride = NE; }
+  else { wbase = W_dkv + (n0 - NE); wstride = d_c; }
+
+  uint4 areg[4], breg[L::NB];
+  auto load_stage = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {               // weights: 64 rows x 16 pieces
+      const int e = i * 256 + tid, k = k0 + (e >> 4), ch = e & 15;
+      areg[i] = make_uint4(0, 0, 0, 0);
+      if (k < d) areg[i] = *reinterpret_cast<const uint4*>(wbase + (int64_t)k * wstride + ch * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < L::NB; ++i) {           // tokens: BN rows x 8 pieces
+      const int e = i * 256 + tid, ch = e & 7;
+      const int64_t t = t0 + (e >> 3);
+      const int k = k0 + ch * 8;
+      breg[i] = make_uint4(0, 0, 0, 0);
+      if (t < T && k < d) breg[i] = *reinterpret_cast<const uint4*>(x + t * d + k);
+    }
+  };
+  auto store_stage = [&](int buf) {
+    char* As = gsm + buf * L::STAGE;
+    char* Bs = As + L::A_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = i * 256 + tid;
+      *reinterpret_cast<uint4*>(As + (e >> 4) * kGmARow + (e & 15) * 16) = areg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < L::NB; ++i) {
+      const int e = i * 256 + tid;
+      *reinterpret_cast<uint4*>(Bs + (e >> 3) * kGmBRow + (e & 7) * 16) = breg[i];
+    }
+  };
+
+  am_f32x16 acc[2][WN];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j) acc[i][j] = (am_f32x16)(0.f);
+
+  // operand offsets inside a stage
+  const int a_off = (8 * (q16 >> 1) + (i16 >> 2)) * kGmARow + wm * 128 + 32 * (q16 & 1) + 8 * (i16 & 3);
+  const int b_off = (wn * 32 * WN + n32) * kGmBRow + hi * 16;
+
+  auto compute = [&](int buf) {
+    const char* As = gsm + buf * L::STAGE;
+    const char* Bs = As + L::A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < kGmStage / 16; ++ks) {
+      am_bf16x8 a[2], b[WN];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const char* base = As + a_off + ks * 16 * kGmARow + i * 64;
+        const am_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(base));
+        const am_s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(base + 4 * kGmARow));
+        a[i] = __builtin_bit_cast(am_bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+        b[j] = *reinterpret_cast<const am_bf16x8*>(Bs + b_off + j * 32 * kGmBRow + ks * 32);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  load_stage(0);
+  store_stage(0);
+  __syncthreads();
+  for (int s = 0; s < nstages; ++s) {
+    const bool more = s + 1 < nstages;
+    if (more) load_stage((s + 1) * kGmStage);
+    compute(s & 1);
+    if (more) store_stage((s + 1) & 1);
+    __syncthreads();
+  }
+
+  // epilogue: lane <-> token; registers 4*g4 .. 4*g4+3 of tile (i, j) are columns
+  //   n0 + wm*64 + i*32 + 8*g4 + 4*hi + {0, 1, 2, 3}
+  const bool elite_block = n0 < NE;
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int64_t t = t0 + wn * 32 * WN + j * 32 + n32;
+    if (t >= T) continue;
+    const int64_t row = slot[t];
+    if (row < 0 || row >= plane_rows) continue;
+    const int32_t p = pos[t];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int n = n0 + wm * 64 + i * 32 + 8 * g4 + 4 * hi;
+        float v0 = acc[i][j][4 * g4], v1 = acc[i][j][4 * g4 + 1], v2 = acc[i][j][4 * g4 + 2], v3 = acc[i][j][4 * g4 + 3];
+        bf16_t* dst;
+        if (elite_block) {
+          // two (even, odd) pairs: slots (n % 2r)/2 and the next one of the same head (2r is even and
+          // n is a multiple of 4, so a group of four never straddles a head when 2r % 4 == 0; with
+          // 2r % 4 == 2 the second pair may belong to the next head: both are looked up separately)
+          float sn, cs;
+          {
+            const int hh = n / (2 * r), jj = (n % (2 * r)) >> 1;
+            int ch = elite_idx[hh * r + jj];
+            ch = min(max(ch, 0), d_h / 2 - 1);
+            rope_sincos(p, rope.theta[ch], &sn, &cs);
+            const float a0 = v0 * cs - v1 * sn, a1 = v0 * sn + v1 * cs;
+            v0 = a0; v1 = a1;
+          }
+          {
+            const int n2 = n + 2;
+            const int hh = n2 / (2 * r), jj = (n2 % (2 * r)) >> 1;
+            int ch = elite_idx[hh * r + jj];
+            ch = min(max(ch, 0), d_h / 2 - 1);
+            rope_sincos(p, rope.theta[ch], &sn, &cs);
+            const float a2 = v2 * cs - v3 * sn, a3 = v2 * sn + v3 * cs;
+            v2 = a2; v3 = a3;
+          }
+          dst = ke_plane + row * NE + n;
+        } else {
+          dst = c_plane + row * d_c + (n - NE);
+        }
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+        pk.y = (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16);
+        *reinterpret_cast<uint2*>(dst) = pk;
+      }
+    }
+  }
+}
+
+bool append_gemm_supported(const elitekv_dims& d, int64_t T) {
+  if (d.dtype != ELITEKV_BF16 || T <= 64) return false;
+  const int NE = 2 * d.r * d.n_heads;
+  return NE % kGmCols == 0 && d.d_c % kGmCols == 0 && d.d_model % 8 == 0;
+}
+
+template <int WN>
+static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
+  using L = GemmLayout<WN>;
+  const elitekv_dims& d = a.dims;
+  const int N = 2 * d.r * d.n_heads + d.d_c;
+  static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
+  if (!attr_done && L::LDS_BYTES > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&append_gemm_kernel<WN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const dim3 grid(N / kGmCols, (unsigned)((a.T + L::BN - 1) / L::BN));
+  append_gemm_kernel<WN><<<grid, 256, L::LDS_BYTES, stream>>>(
+      (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv, a.elite_idx,
+      (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows, d.d_model, d.n_heads, d.head_dim, d.r, d.d_c,
+      make_rope_table(d.rope_base, d.head_dim));
+  return hipGetLastError();
+}
+
+hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  const int64_t col_blocks = (2 * d.r * d.n_heads + d.d_c) / kGmCols;
+  // wide token tiles once they still give every compute unit a few work-groups
+  if (col_blocks * ((a.T + 255) / 256) >= 1024) return launch_gemm_wn<4>(a, stream);
+  return launch_gemm_wn<1>(a, stream);
+}
+
 }  // namespace ekv

@@ -195,7 +195,8 @@ int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, 
   a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows;
   a.ws = (char*)ws;
   const hipStream_t stream = (hipStream_t)hip_stream;
-  const hipError_t e = append_skinny_supported(*dims, T) ? launch_append_skinny(a, stream)
+  const hipError_t e = append_gemm_supported(*dims, T)     ? launch_append_gemm(a, stream)
+                       : append_skinny_supported(*dims, T) ? launch_append_skinny(a, stream)
                        : append_small_supported(*dims, T) ? launch_append_small(a, stream)
                                                           : launch_append_generic(a, stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;

@@ -82,6 +82,8 @@ hipError_t launch_append_finish(const AppendArgs& a, const float* partial, int k
 bool append_skinny_supported(const elitekv_dims& d, int64_t T);
 size_t append_skinny_workspace(const elitekv_dims& d, int64_t T);
 hipError_t launch_append_skinny(const AppendArgs& a, hipStream_t stream);
+bool append_gemm_supported(const elitekv_dims& d, int64_t T);
+hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_generic(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 bool decode_mfma_supported(const elitekv_dims& d);
 struct bf16_t;

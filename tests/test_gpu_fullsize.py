@@ -79,3 +79,32 @@ def test_full_size_append_and_decode(name):
             gots.append(out[b, h])
     err = orc.max_abs_rel(np.stack(gots), np.stack(refs))
     assert err <= TOL[dt], "max-abs-rel %g" % err
+
+
+def test_prefill_append_with_wide_token_tiles():
+    """An append large enough for the widest token tiles of the GEMM path (7B shape at 12.5 % cache,
+    33 100 tokens, not a multiple of any tile): sampled rows against the oracle, and the rows
+    around the destination range stay untouched."""
+    cfg = synth.CONFIGS["7b_12_b64_s2048"]
+    n_h, d_h, r, d_c, d = cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c, cfg.d_model
+    dims = dims_of(cfg)
+    T, guard = 33100, 7
+    rng = synth.rng_for(cfg.index, stream=11)
+    idx = synth.draw_elite_idx(rng, n_h, d_h, r)
+    W_ke, W_dkv, _, _ = synth.draw_weights(rng, d, n_h, d_h, r, d_c)
+    Wked, Wdkvd = dev(W_ke, "bf16"), dev(W_dkv, "bf16")
+    xd = torch.from_numpy(rng.standard_normal((T, d), dtype=np.float32)).to(torch.bfloat16).to(DEV)
+    pos_h = rng.integers(0, 4096, size=T)
+    slot_h = np.arange(T) + guard
+    ke = torch.full((T + 2 * guard, n_h, 2 * r), 3.0, dtype=torch.bfloat16, device=DEV)
+    c = torch.full((T + 2 * guard, d_c), 3.0, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, T), 16), dtype=torch.uint8, device=DEV)
+    ekv.elitekv_append(dims, xd, i32(pos_h), i64(slot_h), Wked, Wdkvd, i32(idx), ke, c, ws=ws)
+    torch.cuda.synchronize()
+    assert bool((ke[:guard] == 3.0).all()) and bool((ke[T + guard:] == 3.0).all())
+    assert bool((c[:guard] == 3.0).all()) and bool((c[T + guard:] == 3.0).all())
+    Wke64, Wdkv64 = host64(Wked), host64(Wdkvd)
+    for t in (0, 1, 255, 256, 257, 12345, 32767, 32768, T - 2, T - 1):
+        ke_ref, c_ref = orc.append(host64(xd[t:t + 1]), pos_h[t:t + 1], Wke64, Wdkv64, idx, d_h, cfg.rope_base)
+        assert orc.max_abs_rel(host64(c[slot_h[t]]), c_ref[0]) <= TOL["bf16"]
+        assert orc.max_abs_rel(host64(ke[slot_h[t]]), ke_ref[0]) <= TOL["bf16"]

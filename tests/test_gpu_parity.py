@@ -38,6 +38,9 @@ APPEND_CASES = {
     "bf16_13b_batch_16": (shape(5120, 40, 128, 8, 1920, "bf16"), 16, 8191),
     "bf16_7b_12pct_batch_64": (shape(4096, 32, 128, 4, 768, "bf16"), 64, 2047),
     "bf16_7b_batch_40": (shape(4096, 32, 128, 8, 1536, "bf16"), 40, 4095),
+    "bf16_7b_300_tokens": (shape(4096, 32, 128, 8, 1536, "bf16"), 300, 32767),
+    "bf16_13b_200_tokens": (shape(5120, 40, 128, 8, 1920, "bf16"), 200, 8191),
+    "bf16_12pct_odd_hidden_130": (shape(1000, 32, 128, 4, 768, "bf16"), 130, 2047),
 }
 
 
