@@ -174,6 +174,7 @@ def main():
     if not args.no_comparators:
         result["comparators"] = comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream,
                                             cache_bytes, args)
+        result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, idx_d, dev, dt, stream)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0,
                                               cache_bytes)
@@ -238,6 +239,34 @@ def comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream, 
     out["mha_uncompressed_GBs"] = round(full_bytes / (ms * 1e-3) / 1e9, 1)
     out["mha_cache_bytes"] = full_bytes
     return out
+
+
+def append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, idx_d, dev, dt, stream, T=2048, iters=20):
+    """The prefill-sized append of the same shape (a dense contraction on the matrix cores):
+    T tokens through x [W_ke | W_dkv] + selective RoPE into fresh cache rows."""
+    import torch
+    d, n_h, r, d_c = cfg.d_model, cfg.n_heads, cfg.r, cfg.d_c
+    g = torch.Generator(device=dev)
+    g.manual_seed(15860)
+    x = torch.randn(T, d, device=dev, dtype=torch.float32, generator=g).to(dt)
+    pos = torch.arange(T, dtype=torch.int32, device=dev)
+    slot = torch.arange(T, dtype=torch.int64, device=dev)
+    ke = torch.zeros(T, n_h, 2 * r, dtype=dt, device=dev)
+    c = torch.zeros(T, d_c, dtype=dt, device=dev)
+    ws = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, T), 16), dtype=torch.uint8, device=dev)
+    for _ in range(3):
+        ekv.elitekv_append(dims, x, pos, slot, W_ke_d, W_dkv_d, idx_d, ke, c, ws=ws, stream=stream)
+    e0, e1 = ev.create(), ev.create()
+    ev.record(e0, stream)
+    for _ in range(iters):
+        ekv.elitekv_append(dims, x, pos, slot, W_ke_d, W_dkv_d, idx_d, ke, c, ws=ws, stream=stream)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms = ev.elapsed_ms(e0, e1) / iters
+    flops = 2.0 * T * d * (2 * r * n_h + d_c)
+    tf = flops / (ms * 1e-3) / 1e12
+    return {"tokens": T, "ms": round(ms, 5), "TFLOPs": round(tf, 1), "bound": "mfma", "peak_TFLOPs": 2500.0,
+            "frac": round(tf / 2500.0, 4), "tokens_per_s": round(T / (ms * 1e-3), 1)}
 
 
 def cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0, cache_bytes):

@@ -402,28 +402,40 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   // two tiles per trip so that buffer and register-set indices are compile-time
   char* ctile1 = ctile0 + L::TILE_BYTES;
   char* ketile1 = KE2 ? ketile0 + L::KE_BYTES : ketile0;
-  issue_c(t0, ctile0);
-  issue_ke(t0, ketile0);
+  // The i-th tile this work-group processes.  The second work-group of a head-group pair swaps
+  // neighbouring tiles: at any moment the two fetch DIFFERENT rows from HBM, and each finds the
+  // tile its partner fetched one step earlier in the XCD's L2 (twice as many independent streams
+  // as when both ask for the same rows at the same time).
+  const int n_my = (int)((t_end - t0 + t_step - 1) / t_step);
+  const int swp = (p.pair_map && hg) ? 1 : 0;
+  auto tile_at = [&](int i) -> int64_t {     // t_end stands for "no such tile"
+    if (i >= n_my) return t_end;
+    const int j = i ^ swp;
+    return t0 + (int64_t)(j < n_my ? j : i) * t_step;
+  };
+  const int64_t first = tile_at(0);
+  issue_c(first, ctile0);
+  issue_ke(first, ketile0);
   load_query();   // after the first tile's loads are in flight
-  for (int64_t tile = t0; tile < t_end; tile += 2 * t_step) {
-    const int64_t t1 = tile + t_step, t2 = tile + 2 * t_step;
-    if (t1 < t_end) {
+  for (int i = 0; i < n_my; i += 2) {
+    const int64_t ta = tile_at(i), tb = tile_at(i + 1), tc = tile_at(i + 2);
+    if (tb < t_end) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // buffer 1 was last read one tile ago
-      issue(t1, ctile1, ketile1);
+      issue(tb, ctile1, ketile1);
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IN_FLIGHT) : "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    compute(tile, ctile0, ketile0, t1);
-    if (t1 >= t_end) break;
-    if (t2 < t_end) {
+    compute(ta, ctile0, ketile0, tb);
+    if (tb >= t_end) break;
+    if (tc < t_end) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      issue(t2, ctile0, ketile0);
+      issue(tc, ctile0, ketile0);
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IN_FLIGHT) : "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    compute(t1, ctile1, ketile1, t2);
+    compute(tb, ctile1, ketile1, tc);
   }
 
   // ---- write this split's partial (m, l, U)

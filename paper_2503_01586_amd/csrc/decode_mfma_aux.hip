@@ -464,7 +464,7 @@ template <int CW, int DH>
 __global__ __launch_bounds__(256) void merge_up_batch_kernel(
     const float* __restrict__ part_m, const float* __restrict__ part_l,
     const bf16_t* __restrict__ part_u, const bf16_t* __restrict__ W_uv, float* __restrict__ opart,
-    int B, int n_h, int nhp, int d_c, int n_splits) {
+    int B, int n_h, int nhp, int d_c, int n_splits, int rows_per_wg) {
   using L = MergeBatchLayout<CW, DH>;
   constexpr int KPT = L::KPT, JPW = L::JPW, WROW = L::WROW, LPR = L::LPR, NG = L::NG, UROW = L::UROW;
   extern __shared__ __attribute__((aligned(16))) char bsm[];
@@ -473,9 +473,9 @@ __global__ __launch_bounds__(256) void merge_up_batch_kernel(
   float* invl = reinterpret_cast<float*>(bsm + L::BIG);        // [kMbRows]
   float* wsp = invl + kMbRows;                                 // [rows][n_splits] split maxima, then weights
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int chunk = blockIdx.x, head = blockIdx.y, b0 = blockIdx.z * kMbRows;
+  const int chunk = blockIdx.x, head = blockIdx.y, b0 = blockIdx.z * rows_per_wg;
   const int n_chunks = gridDim.x;
-  const int rows = min(kMbRows, B - b0);
+  const int rows = min(rows_per_wg, B - b0);
   float* lsp = wsp + rows * n_splits;                          // [rows][n_splits] split sums
   const int col0 = chunk * CW;
 
@@ -526,8 +526,10 @@ __global__ __launch_bounds__(256) void merge_up_batch_kernel(
   // (4) merged latent: group <-> (row, slice of the splits); lane <-> 8 columns
   const int SL = rows < NG ? NG / rows : 1;                    // slices per row
   const int cl = tid % LPR, g = tid / LPR;
-  if (g < NG) {
-    for (int rs = g; rs < rows * SL; rs += NG) {
+  if (g < NG && rows * SL <= NG) {
+    // at most one (row, slice) item per group: eight splits at a time
+    const int rs = g;
+    if (rs < rows * SL) {
       const int rl = rs % rows, sl = rs / rows;
       const bf16_t* ub = part_u + (((int64_t)(b0 + rl) * n_splits) * nhp + head) * (int64_t)d_c + col0 + cl * 8;
       const int64_t sstep = (int64_t)nhp * d_c;
@@ -556,6 +558,56 @@ __global__ __launch_bounds__(256) void merge_up_batch_kernel(
       float* ur = ubar + rs * UROW + cl * 8;
       *reinterpret_cast<float4*>(ur) = make_float4(acc[0], acc[1], acc[2], acc[3]);
       *reinterpret_cast<float4*>(ur + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
+  } else if (g < NG) {
+    // several items per group: two (row, slice) items at a time, four splits each (8 loads of 16 bytes in flight)
+    for (int rs = g; rs < rows * SL; rs += 2 * NG) {
+      const int rs2 = rs + NG;
+      const bool two = rs2 < rows * SL;
+      const int rl0 = rs % rows, sl0 = rs / rows;
+      const int rl1 = two ? rs2 % rows : rl0, sl1 = two ? rs2 / rows : sl0;
+      const int64_t sstep = (int64_t)nhp * d_c;
+      const bf16_t* ub0 = part_u + (((int64_t)(b0 + rl0) * n_splits) * nhp + head) * (int64_t)d_c + col0 + cl * 8;
+      const bf16_t* ub1 = part_u + (((int64_t)(b0 + rl1) * n_splits) * nhp + head) * (int64_t)d_c + col0 + cl * 8;
+      const float* wr0 = wsp + rl0 * n_splits;
+      const float* wr1 = wsp + rl1 * n_splits;
+      float acc0[8], acc1[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc0[i] = acc1[i] = 0.f;
+      for (int s0 = 0; s0 < n_splits; s0 += 4 * SL) {
+        uint4 u0[4], u1[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int sa = s0 + sl0 + q * SL, sb = s0 + sl1 + q * SL;
+          u0[q] = make_uint4(0, 0, 0, 0);
+          u1[q] = make_uint4(0, 0, 0, 0);
+          if (sa < n_splits) u0[q] = *reinterpret_cast<const uint4*>(ub0 + sa * sstep);
+          if (two && sb < n_splits) u1[q] = *reinterpret_cast<const uint4*>(ub1 + sb * sstep);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int sa = s0 + sl0 + q * SL, sb = s0 + sl1 + q * SL;
+          const float w0 = (sa < n_splits) ? wr0[sa] : 0.f;
+          const float w1 = (two && sb < n_splits) ? wr1[sb] : 0.f;
+          const uint32_t a4[4] = {u0[q].x, u0[q].y, u0[q].z, u0[q].w};
+          const uint32_t b4[4] = {u1[q].x, u1[q].y, u1[q].z, u1[q].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc0[2 * i] = fmaf(w0, __uint_as_float(a4[i] << 16), acc0[2 * i]);
+            acc0[2 * i + 1] = fmaf(w0, __uint_as_float(a4[i] & 0xffff0000u), acc0[2 * i + 1]);
+            acc1[2 * i] = fmaf(w1, __uint_as_float(b4[i] << 16), acc1[2 * i]);
+            acc1[2 * i + 1] = fmaf(w1, __uint_as_float(b4[i] & 0xffff0000u), acc1[2 * i + 1]);
+          }
+        }
+      }
+      float* ur = ubar + rs * UROW + cl * 8;
+      *reinterpret_cast<float4*>(ur) = make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
+      *reinterpret_cast<float4*>(ur + 4) = make_float4(acc0[4], acc0[5], acc0[6], acc0[7]);
+      if (two) {
+        float* ur2 = ubar + rs2 * UROW + cl * 8;
+        *reinterpret_cast<float4*>(ur2) = make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
+        *reinterpret_cast<float4*>(ur2 + 4) = make_float4(acc1[4], acc1[5], acc1[6], acc1[7]);
+      }
     }
   }
   __syncthreads();
@@ -611,14 +663,17 @@ __global__ __launch_bounds__(256) void out_reduce_kernel(const float* __restrict
 
 bool merge_batch_supported(const elitekv_dims& d, int64_t B, int64_t n_splits) {
   if (B < 2 || d.d_c % 128 || (d.head_dim != 128 && d.head_dim != 64)) return false;
-  return (B < kMbRows ? B : kMbRows) * n_splits <= kMbWeightFloats;
+  return (B < kMbRows ? B : kMbRows) * n_splits <= kMbWeightFloats;   // (any smaller row tile fits too)
 }
 
 template <int CW, int DH>
 static hipError_t launch_merge_batch(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
   using L = MergeBatchLayout<CW, DH>;
   const elitekv_dims& d = a.dims;
-  const int rows = (int)(a.B < kMbRows ? a.B : kMbRows);
+  // rows per work-group: all of them (up to kMbRows) unless that leaves compute units idle
+  int rows = (int)(a.B < kMbRows ? a.B : kMbRows);
+  const int64_t groups = (int64_t)(d.d_c / CW) * d.n_heads;
+  while (rows > 16 && groups * ((a.B + rows - 1) / rows) < 256) rows = (rows + 1) / 2;
   const size_t sm = L::lds_bytes(rows, p.n_splits);
   static size_t sm_set = 64 * 1024;   // raising the dynamic-LDS limit is idempotent
   if (sm > sm_set) {
@@ -627,11 +682,11 @@ static hipError_t launch_merge_batch(const DecodeArgs& a, const DecodePlan& p, h
     if (e != hipSuccess) return e;
     sm_set = sm;
   }
-  const dim3 grid(d.d_c / CW, d.n_heads, (unsigned)((a.B + kMbRows - 1) / kMbRows));
+  const dim3 grid(d.d_c / CW, d.n_heads, (unsigned)((a.B + rows - 1) / rows));
   merge_up_batch_kernel<CW, DH><<<grid, 256, sm, stream>>>(
       (const float*)(a.ws + p.off_m), (const float*)(a.ws + p.off_l), (const bf16_t*)(a.ws + p.off_u),
       (const bf16_t*)a.W_uv, (float*)(a.ws + p.off_opart), (int)a.B, d.n_heads, p.head_groups * 32, d.d_c,
-      p.n_splits);
+      p.n_splits, rows);
   return hipGetLastError();
 }
 
