@@ -154,17 +154,19 @@ int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* 
  * ------------------------------------------------------------------------------------------- */
 
 /*
- * elitekv_decode_attn with two HIP events (hipEvent_t, created by the caller with timing enabled)
- * recorded on hip_stream immediately before and after the split attention kernel, the kernel that
- * streams the cache planes.  Used by the benchmark to time that kernel alone inside the whole call.
- * Same arguments, results and errors as elitekv_decode_attn; ENULL if an event is NULL.
+ * Measurement only: elitekv_decode_attn restricted to the stages named in `stages`
+ * (bit 0: query preparation, bit 1: split attention over the cache planes, bit 2: merge of the
+ * splits + up-projection).  A stage that is left out reads what an earlier call with the same
+ * arguments left in the workspace, so a full call must come first; the benchmark uses it to time
+ * back-to-back launches of one stage with nothing else on the stream.  Same arguments and errors as
+ * elitekv_decode_attn; EINVAL if stages is outside 1..7.  `out` is written only by stage bit 2.
  */
-int elitekv_decode_attn_profiled(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
-                                 const int32_t* seq_len, int64_t B, int64_t max_seq_len,
-                                 int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
-                                 const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
-                                 int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
-                                 int32_t n_splits, void* hip_stream, void* ev_before, void* ev_after);
+int elitekv_decode_attn_stages(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                               const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                               int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                               const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                               int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
+                               int32_t n_splits, void* hip_stream, int32_t stages);
 
 /* Workspace bytes of elitekv_mha_decode.  n_splits == 0 means "auto". */
 size_t elitekv_mha_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,

@@ -50,8 +50,8 @@ def _load():
         "elitekv_decode_auto_splits": (I32, [DP, I64, I64]),
         "elitekv_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_decode_attn": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32, P]),
-        "elitekv_decode_attn_profiled": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32,
-                                                   P, P, P]),
+        "elitekv_decode_attn_stages": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32,
+                                                 P, I32]),
         "elitekv_mha_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_mha_decode": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, I64, P, P, SZ, I32, P]),
         "elitekv_stream_read": (C.c_int, [P, SZ, P, P]),
@@ -158,19 +158,18 @@ def elitekv_decode_attn(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows,
     _check(st, "elitekv_decode_attn")
 
 
-def elitekv_decode_attn_profiled(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
-                                 ke_plane, c_plane, out, ws, ev_before, ev_after, n_splits=0, stream=None,
-                                 B=None, plane_rows=None):
-    """ev_before / ev_after: hipEvent_t handles (ctypes.c_void_p or int)."""
+def elitekv_decode_attn_stages(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+                               ke_plane, c_plane, out, ws, stages, n_splits=0, stream=None, B=None,
+                               plane_rows=None):
+    """stages: bit 0 query preparation, bit 1 split attention, bit 2 merge + up-projection."""
     B = q.shape[0] if B is None else B
     plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
-    st = _lib.elitekv_decode_attn_profiled(C.byref(dims), _ptr(q), _ptr(q_pos), _ptr(seq_len), int(B),
-                                           int(max_seq_len), int(batch_stride_rows), _ptr(W_uk), _ptr(W_uv),
-                                           _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
-                                           _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream),
-                                           ev_before, ev_after)
-    _check(st, "elitekv_decode_attn_profiled")
+    st = _lib.elitekv_decode_attn_stages(C.byref(dims), _ptr(q), _ptr(q_pos), _ptr(seq_len), int(B),
+                                         int(max_seq_len), int(batch_stride_rows), _ptr(W_uk), _ptr(W_uv),
+                                         _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
+                                         _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream), int(stages))
+    _check(st, "elitekv_decode_attn_stages")
 
 
 def elitekv_mha_decode_workspace_bytes(dims, B, max_seq_len, n_splits=0) -> int:

@@ -224,9 +224,10 @@ static hipError_t launch_decode_generic_t(const DecodeArgs& a, const DecodePlan&
   float* pu = (float*)(a.ws + p.off_u);
   const float scale_log2e = kLog2e / sqrtf((float)d_h);
 
-  qprep_generic_kernel<T><<<dim3(n_h, (unsigned)a.B), kGenThreads, 0, stream>>>(
-      (const T*)a.q, a.q_pos, (const T*)a.W_uk, a.elite_idx, qe, qt, n_h, d_h, r, d_c, make_rope_table(d.rope_base, d.head_dim),
-      scale_log2e);
+  if (a.stages & 1)
+    qprep_generic_kernel<T><<<dim3(n_h, (unsigned)a.B), kGenThreads, 0, stream>>>(
+        (const T*)a.q, a.q_pos, (const T*)a.W_uk, a.elite_idx, qe, qt, n_h, d_h, r, d_c,
+        make_rope_table(d.rope_base, d.head_dim), scale_log2e);
 
   const dim3 grid(p.n_splits, n_h, (unsigned)a.B);
   const size_t sm = sizeof(float) * (size_t)(d_c + 2 * r + 2 * kGenTile);
@@ -235,15 +236,15 @@ static hipError_t launch_decode_generic_t(const DecodeArgs& a, const DecodePlan&
   attn_generic_kernel<T, C><<<grid, kGenThreads, sm, stream>>>(                                   \
       (const T*)a.ke_plane, (const T*)a.c_plane, qe, qt, a.seq_len, pm, pl, pu, n_h, 2 * r, d_c,  \
       a.max_seq_len, a.batch_stride_rows, a.plane_rows, p.n_splits, p.chunk)
-  if (a.ev_before) (void)hipEventRecord(a.ev_before, stream);
-  if (cpt <= 1) EKV_ATTN(1);
+  if (!(a.stages & 2)) {}
+  else if (cpt <= 1) EKV_ATTN(1);
   else if (cpt <= 2) EKV_ATTN(2);
   else if (cpt <= 4) EKV_ATTN(4);
   else if (cpt <= 8) EKV_ATTN(8);
   else EKV_ATTN(16);
 #undef EKV_ATTN
-  if (a.ev_after) (void)hipEventRecord(a.ev_after, stream);
 
+  if (!(a.stages & 4)) return hipGetLastError();
   const size_t sm2 = sizeof(float) * (size_t)(d_c + p.n_splits + kGenThreads);
   merge_upproj_generic_kernel<T><<<dim3(n_h, (unsigned)a.B), kGenThreads, sm2, stream>>>(
       pm, pl, pu, (const T*)a.W_uv, (T*)a.out, n_h, d_h, d_c, p.n_splits);

@@ -510,10 +510,11 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
   prm.batch = (int)a.B; prm.pair_map = p.head_groups == 2 ? 1 : 0;
 
-  hipError_t e = launch_qprep_rows(a, qe, qt, stream);
+  hipError_t e = hipSuccess;
+  if (a.stages & 1) e = launch_qprep_rows(a, qe, qt, stream);
   if (e != hipSuccess) return e;
+  if (!(a.stages & 2)) return (a.stages & 4) ? launch_merge_up(a, p, stream) : hipSuccess;
 
-  if (a.ev_before) (void)hipEventRecord(a.ev_before, stream);
   e = hipErrorInvalidValue;
   const int two_r = 2 * d.r;
 #define EKV_CASE(DC, NWV, DCW)                                                        \
@@ -527,9 +528,7 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   EKV_CASE(256, 4, 64)
 #undef EKV_CASE
   if (e != hipSuccess) return e;
-  if (a.ev_after) (void)hipEventRecord(a.ev_after, stream);
-
-  return launch_merge_up(a, p, stream);
+  return (a.stages & 4) ? launch_merge_up(a, p, stream) : hipSuccess;
 }
 
 }  // namespace ekv

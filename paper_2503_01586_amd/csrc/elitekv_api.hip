@@ -220,7 +220,7 @@ static int decode_impl(const elitekv_dims* dims, const void* q, const int32_t* q
                        int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
                        const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
                        int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
-                       void* hip_stream, void* ev_before, void* ev_after) {
+                       void* hip_stream, int32_t stages) {
   DecodePlan p;
   int st = plan_decode(dims, B, max_seq_len, n_splits, &p);
   if (st) return st;
@@ -239,7 +239,7 @@ static int decode_impl(const elitekv_dims* dims, const void* q, const int32_t* q
   a.dims = *dims; a.q = q; a.q_pos = q_pos; a.seq_len = seq_len; a.B = B; a.max_seq_len = max_seq_len;
   a.batch_stride_rows = batch_stride_rows; a.W_uk = W_uk; a.W_uv = W_uv; a.elite_idx = elite_idx;
   a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows; a.out = out; a.ws = (char*)ws;
-  a.ev_before = (hipEvent_t)ev_before; a.ev_after = (hipEvent_t)ev_after;
+  a.stages = stages;
   const hipError_t e = p.mfma ? launch_decode_mfma(a, p, (hipStream_t)hip_stream)
                              : launch_decode_generic(a, p, (hipStream_t)hip_stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
@@ -252,18 +252,18 @@ int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* 
                         int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
                         void* hip_stream) {
   return decode_impl(dims, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
-                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, nullptr, nullptr);
+                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, 7);
 }
 
-int elitekv_decode_attn_profiled(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
-                                 const int32_t* seq_len, int64_t B, int64_t max_seq_len,
-                                 int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
-                                 const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
-                                 int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
-                                 int32_t n_splits, void* hip_stream, void* ev_before, void* ev_after) {
-  if (!ev_before || !ev_after) return ELITEKV_ENULL;
+int elitekv_decode_attn_stages(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                               const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                               int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                               const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                               int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
+                               int32_t n_splits, void* hip_stream, int32_t stages) {
+  if (stages < 1 || stages > 7) return ELITEKV_EINVAL;
   return decode_impl(dims, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
-                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, ev_before, ev_after);
+                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, stages);
 }
 
 size_t elitekv_mha_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,

@@ -42,7 +42,7 @@ struct DecodeArgs {
   int64_t plane_rows;
   void* out;
   char* ws;
-  hipEvent_t ev_before, ev_after;   // optional: recorded around the split attention kernel
+  int32_t stages;                   // bit 0 q-prep, bit 1 split attention, bit 2 merge + up-projection
 };
 
 struct AppendArgs {
