@@ -40,6 +40,11 @@ evaluated in its relative form from full keys for any r; the r = 0 case;
 R(0) = identity; shift invariance; norm preservation; the closed forms for one
 cached token and for q = 0; permutation invariances; triple-loop brute force;
 hand-computed rotations; the cache-size and parameter-count formulas.
+
+The separated variant (S-LRD, two latents per token) has its own functions at the end of this
+file and its own pins (tests/test_oracle_slrd_pins.py): exact separate factors against the
+RoPElite score equation, brute force, the embedding into the joint variant with block-zero
+up-projections, closed forms, and the Section 3.2 size formulas.
 """
 from __future__ import annotations
 
@@ -163,6 +168,74 @@ def decode_attn(q, q_pos, ke, c, seq_len, W_uk, W_uv, elite_idx, head_dim: int,
             # reconstructed keys and values of every cached token
             K_full = np.concatenate([ke_b[:, h, :], c_b @ W_uk[:, h, :]], axis=1)
             V_full = c_b @ W_uv[:, h, :]
+            out[b, h] = softmax_attention(q_hat, K_full, V_full, d_h)
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
+# Separated low-rank decomposition (Section 3.2, "Separated Low-Rank Decomposition"): the
+# non-elite key block and the value block are factorised separately,
+#     W^k_{e^,0:n_h-1} ~ A^k B^k_S,   W^v_{0:n_h-1} ~ A^v B^v_S,
+# so a token caches two latents, c^k = x A^k (d_ck wide) and c^v = x A^v (d_cv wide), next to
+# its rotated elite keys.  Everything else is as in the joint variant.
+# ----------------------------------------------------------------------------------------------
+def slrd_cache_row_elems(n_heads: int, r: int, d_ck: int, d_cv: int) -> int:
+    """KV-cache elements per token per layer with S-LRD: 2 r n_h + d_ck + d_cv (Section 3.2)."""
+    return 2 * r * n_heads + d_ck + d_cv
+
+
+def slrd_param_count(d_model: int, n_heads: int, head_dim: int, r: int, d_ck: int, d_cv: int) -> int:
+    """Section 3.2, storage cost of RoPElite with S-LRD:
+    2 r n_h d + d_ck (d + d_h n_h - 2 r n_h) + d_cv (d + d_h n_h)."""
+    return (2 * r * n_heads * d_model + d_ck * (d_model + head_dim * n_heads - 2 * r * n_heads)
+            + d_cv * (d_model + head_dim * n_heads))
+
+
+def slrd_append(x, pos, W_ke, A_k, A_v, elite_idx, head_dim: int, rope_base: float):
+    """Cache rows for T tokens of an S-LRD model.
+
+    x [T, d]; W_ke [d, n_h, 2r]; A_k [d, d_ck]; A_v [d, d_cv]; elite_idx [n_h, r].
+    Returns (ke [T, n_h, 2r] rotated elite keys, c_k [T, d_ck], c_v [T, d_cv]), float64.
+    """
+    x = np.asarray(x, dtype=F64)
+    ke, c_k = append(x, pos, W_ke, A_k, elite_idx, head_dim, rope_base)   # elite keys do not depend on the latent
+    c_v = x @ np.asarray(A_v, dtype=F64)                                   # c^v_t = x_t A^v
+    return ke, c_k, c_v
+
+
+def slrd_decode_attn(q, q_pos, ke, c_k, c_v, seq_len, B_k, B_v, elite_idx, head_dim: int,
+                     rope_base: float, heads=None):
+    """Single-token decode attention of an S-LRD model: textbook attention (Section 2.1) over
+        k_j = [ rotated elite dims | c^k_j B^k_S,h ]   and   v_j = c^v_j B^v_S,h.
+
+    ke[b] [>=S_b, n_h, 2r]; c_k[b] [>=S_b, d_ck]; c_v[b] [>=S_b, d_cv];
+    B_k [d_ck, n_h, d_h-2r]; B_v [d_cv, n_h, d_h].  Other arguments as decode_attn.
+    """
+    q = np.asarray(q, dtype=F64)
+    B_k = np.asarray(B_k, dtype=F64)
+    B_v = np.asarray(B_v, dtype=F64)
+    elite_idx = np.asarray(elite_idx)
+    B, n_h, d_h = q.shape
+    assert d_h == head_dim
+    r = elite_idx.shape[1]
+    theta = rope_theta(head_dim, rope_base)
+    out = np.zeros((B, n_h, d_h), dtype=F64)
+    head_list = range(n_h) if heads is None else heads
+    for b in range(B):
+        S = int(seq_len[b])
+        if S == 0:
+            continue
+        ke_b = np.asarray(ke[b], dtype=F64)[:S]
+        ck_b = np.asarray(c_k[b], dtype=F64)[:S]
+        cv_b = np.asarray(c_v[b], dtype=F64)[:S]
+        for h in head_list:
+            idx_h = elite_idx[h]
+            q_e = q[b, h, elite_dims(idx_h)].reshape(r, 2)
+            alpha = F64(int(q_pos[b])) * theta[idx_h.astype(np.int64)] if r else np.zeros(0)
+            q_e = rotate_pairs(q_e, alpha).reshape(2 * r)
+            q_hat = np.concatenate([q_e, q[b, h, nonelite_dims(idx_h, d_h)]])
+            K_full = np.concatenate([ke_b[:, h, :], ck_b @ B_k[:, h, :]], axis=1)   # keys from c^k only
+            V_full = cv_b @ B_v[:, h, :]                                             # values from c^v only
             out[b, h] = softmax_attention(q_hat, K_full, V_full, d_h)
     return out
 
