@@ -150,6 +150,51 @@ int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* 
                         void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Separated low-rank decomposition (Section 3.2, "Separated Low-Rank Decomposition"):
+ *     W^k_{e^,0:n_h-1} ~ A^k B^k_S,   W^v_{0:n_h-1} ~ A^v B^v_S,
+ * a token caches two latents, c^k = x A^k (d_ck columns) and c^v = x A^v (d_cv columns), next to its
+ * rotated elite keys; 2 r n_h + d_ck + d_cv cache elements per token.  The two latents are stored
+ * SIDE BY SIDE in one row of the latent plane: c_plane [rows, d_ck + d_cv] = [c^k | c^v], so
+ * dims->d_c = d_ck + d_cv is the row width and d_ck says where c^v starts.  Everything else
+ * (planes, positions, slots, elite indices, workspace rules, streams, error codes) is as in the
+ * joint entry points above.  EINVAL unless 0 < d_ck < dims->d_c.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Section 3.2, storage cost with S-LRD: 2 r n_h d + d_ck (d + d_h n_h - 2 r n_h) + d_cv (d + d_h n_h). */
+int elitekv_slrd_param_count(const elitekv_dims* dims, int32_t d_ck, int64_t* n_params);
+
+/* Workspace bytes elitekv_slrd_append needs for T tokens (host only; may be 0). */
+size_t elitekv_slrd_append_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t T);
+
+/*
+ * Append T tokens: elite keys as in elitekv_append; latent row = [x A^k | x A^v].
+ * A_k [d_model, d_ck] and A_v [d_model, d_c - d_ck], row-major, device pointers.
+ */
+int elitekv_slrd_append(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                        const int64_t* slot, int64_t T, const void* W_ke, const void* A_k, const void* A_v,
+                        const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows, void* ws,
+                        size_t ws_bytes, void* hip_stream);
+
+/* Workspace bytes of elitekv_slrd_decode_attn (host only).  n_splits == 0 means "auto"
+ * (elitekv_decode_auto_splits gives the count). */
+size_t elitekv_slrd_decode_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B,
+                                           int64_t max_seq_len, int32_t n_splits);
+
+/*
+ * Single-token decode attention of an S-LRD model: keys are [rotated elite dims | c^k B^k_S,h],
+ * values are c^v B^v_S,h.  B_k [d_ck, n_h, d_h - 2r], B_v [d_c - d_ck, n_h, d_h], device pointers;
+ * the remaining arguments as in elitekv_decode_attn.  B^k_S is absorbed into the query and B^v_S is
+ * applied after the attention sum, so scores only touch the c^k columns of a cache row and the value
+ * accumulation only its c^v columns.
+ */
+int elitekv_slrd_decode_attn(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                             const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                             int64_t batch_stride_rows, const void* B_k, const void* B_v,
+                             const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                             int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                             void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement-only companions (not part of the method).
  * ------------------------------------------------------------------------------------------- */
 

@@ -50,6 +50,12 @@ def _load():
         "elitekv_decode_auto_splits": (I32, [DP, I64, I64]),
         "elitekv_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_decode_attn": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32, P]),
+        "elitekv_slrd_param_count": (C.c_int, [DP, I32, C.POINTER(I64)]),
+        "elitekv_slrd_append_workspace_bytes": (SZ, [DP, I32, I64]),
+        "elitekv_slrd_append": (C.c_int, [DP, I32, P, P, P, I64, P, P, P, P, P, P, I64, P, SZ, P]),
+        "elitekv_slrd_decode_workspace_bytes": (SZ, [DP, I32, I64, I64, I32]),
+        "elitekv_slrd_decode_attn": (C.c_int, [DP, I32, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32,
+                                               P]),
         "elitekv_decode_attn_stages": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32,
                                                  P, I32]),
         "elitekv_mha_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
@@ -156,6 +162,44 @@ def elitekv_decode_attn(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows,
                                   _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
                                   _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
     _check(st, "elitekv_decode_attn")
+
+
+def elitekv_slrd_param_count(dims, d_ck) -> int:
+    n = C.c_int64()
+    _check(_lib.elitekv_slrd_param_count(C.byref(dims), int(d_ck), C.byref(n)), "elitekv_slrd_param_count")
+    return n.value
+
+
+def elitekv_slrd_append_workspace_bytes(dims, d_ck, T) -> int:
+    return _lib.elitekv_slrd_append_workspace_bytes(C.byref(dims), int(d_ck), int(T))
+
+
+def elitekv_slrd_append(dims, d_ck, x, pos, slot, W_ke, A_k, A_v, elite_idx, ke_plane, c_plane, ws=None,
+                        stream=None, T=None, plane_rows=None):
+    T = x.shape[0] if T is None else T
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_slrd_append(C.byref(dims), int(d_ck), _ptr(x), _ptr(pos), _ptr(slot), int(T), _ptr(W_ke),
+                                  _ptr(A_k), _ptr(A_v), _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane),
+                                  int(plane_rows), _ptr(ws), ws_bytes, _stream(stream))
+    _check(st, "elitekv_slrd_append")
+
+
+def elitekv_slrd_decode_workspace_bytes(dims, d_ck, B, max_seq_len, n_splits=0) -> int:
+    return _lib.elitekv_slrd_decode_workspace_bytes(C.byref(dims), int(d_ck), int(B), int(max_seq_len),
+                                                    int(n_splits))
+
+
+def elitekv_slrd_decode_attn(dims, d_ck, q, q_pos, seq_len, max_seq_len, batch_stride_rows, B_k, B_v, elite_idx,
+                             ke_plane, c_plane, out, ws, n_splits=0, stream=None, B=None, plane_rows=None):
+    B = q.shape[0] if B is None else B
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_slrd_decode_attn(C.byref(dims), int(d_ck), _ptr(q), _ptr(q_pos), _ptr(seq_len), int(B),
+                                       int(max_seq_len), int(batch_stride_rows), _ptr(B_k), _ptr(B_v),
+                                       _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
+                                       _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
+    _check(st, "elitekv_slrd_decode_attn")
 
 
 def elitekv_decode_attn_stages(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,

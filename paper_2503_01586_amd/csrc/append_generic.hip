@@ -14,7 +14,7 @@ constexpr int kApK = 128;        // contraction chunk staged in LDS
 template <typename T>
 __global__ __launch_bounds__(kApThreads) void append_generic_kernel(
     const T* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot,
-    int64_t T_tokens, const T* __restrict__ W_ke, const T* __restrict__ W_dkv,
+    int64_t T_tokens, const T* __restrict__ W_ke, const T* __restrict__ W_dkv, const T* __restrict__ W_dkv2, int d_ck,
     const int32_t* __restrict__ elite_idx, T* __restrict__ ke_plane, T* __restrict__ c_plane,
     int64_t plane_rows, int d, int n_h, int d_h, int r, int d_c, RopeTable rope) {
   __shared__ float xs[kApTokens][kApK];
@@ -26,8 +26,7 @@ __global__ __launch_bounds__(kApThreads) void append_generic_kernel(
   const bool col_ok = n < N;
   const T* wcol;
   int64_t wstride;
-  if (n < NE) { wcol = W_ke + n; wstride = NE; }
-  else { wcol = W_dkv + (col_ok ? n - NE : 0); wstride = d_c; }
+  weight_column(col_ok ? n : 0, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wcol, &wstride);
 
   float acc[kApTokens];
 #pragma unroll
@@ -87,12 +86,12 @@ hipError_t launch_append_generic(const AppendArgs& a, hipStream_t stream) {
   if (d.dtype == ELITEKV_FP32) {
     append_generic_kernel<float><<<grid, kApThreads, 0, stream>>>(
         (const float*)a.x, a.pos, a.slot, a.T, (const float*)a.W_ke, (const float*)a.W_dkv,
-        a.elite_idx, (float*)a.ke_plane, (float*)a.c_plane, a.plane_rows, d.d_model, d.n_heads,
+        (const float*)a.W_dkv2, a.d_ck, a.elite_idx, (float*)a.ke_plane, (float*)a.c_plane, a.plane_rows, d.d_model, d.n_heads,
         d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
   } else {
     append_generic_kernel<bf16_t><<<grid, kApThreads, 0, stream>>>(
         (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
-        a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows, d.d_model, d.n_heads,
+        (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows, d.d_model, d.n_heads,
         d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
   }
   return hipGetLastError();

@@ -31,7 +31,7 @@ constexpr int kSkRow = kSkCols * 2 + 32;       // bytes of one staged weight row
 template <int TT>   // 32-token tiles (1 or 2)
 __global__ __launch_bounds__(256) void append_skinny_kernel(
     const bf16_t* __restrict__ x, int T, const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv,
-    float* __restrict__ partial, int d, int NE, int d_c, int kc) {
+    const bf16_t* __restrict__ W_dkv2, int d_ck, float* __restrict__ partial, int d, int NE, int d_c, int kc) {
   __shared__ __attribute__((aligned(16))) char wsm[2][kSkStage * kSkRow];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nt = wave & 1, kh = wave >> 1;
@@ -44,8 +44,7 @@ __global__ __launch_bounds__(256) void append_skinny_kernel(
 
   const bf16_t* wbase;
   int64_t wstride;
-  if (n0 < NE) { wbase = W_ke + n0; wstride = NE; }
-  else { wbase = W_dkv + (n0 - NE); wstride = d_c; }
+  weight_column(n0, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wbase, &wstride);   // a block lies in one matrix
 
   // weight loader: a stage is 128 rows x 8 pieces of 16 bytes; thread <-> 4 of them
   uint4 wreg[4];
@@ -146,10 +145,10 @@ __global__ __launch_bounds__(256) void append_skinny_kernel(
   }
 }
 
-bool append_skinny_supported(const elitekv_dims& d, int64_t T) {
+bool append_skinny_supported(const elitekv_dims& d, int64_t T, int d_ck) {
   if (d.dtype != ELITEKV_BF16 || T < 8 || T > 64) return false;
   const int NE = 2 * d.r * d.n_heads;
-  return NE % kSkCols == 0 && d.d_c % kSkCols == 0 && d.d_model % 8 == 0;
+  return NE % kSkCols == 0 && d.d_c % kSkCols == 0 && d_ck % kSkCols == 0 && d.d_model % 8 == 0;
 }
 
 // contraction splits: about one work-group per compute unit, whole stages per split
@@ -180,10 +179,12 @@ hipError_t launch_append_skinny(const AppendArgs& a, hipStream_t stream) {
   const dim3 grid(N / kSkCols, ks);
   if (a.T <= 32)
     append_skinny_kernel<1><<<grid, 256, 0, stream>>>((const bf16_t*)a.x, (int)a.T, (const bf16_t*)a.W_ke,
-                                                      (const bf16_t*)a.W_dkv, partial, d.d_model, NE, d.d_c, kc);
+                                                      (const bf16_t*)a.W_dkv, (const bf16_t*)a.W_dkv2, a.d_ck,
+                                                      partial, d.d_model, NE, d.d_c, kc);
   else
     append_skinny_kernel<2><<<grid, 256, 0, stream>>>((const bf16_t*)a.x, (int)a.T, (const bf16_t*)a.W_ke,
-                                                      (const bf16_t*)a.W_dkv, partial, d.d_model, NE, d.d_c, kc);
+                                                      (const bf16_t*)a.W_dkv, (const bf16_t*)a.W_dkv2, a.d_ck,
+                                                      partial, d.d_model, NE, d.d_c, kc);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_append_finish(a, partial, ks, stream);
@@ -216,8 +217,8 @@ struct GemmLayout {
 template <int WN>
 __global__ __launch_bounds__(256) void append_gemm_kernel(
     const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
-    const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const int32_t* __restrict__ elite_idx,
-    bf16_t* __restrict__ ke_plane, bf16_t* __restrict__ c_plane, int64_t plane_rows, int d, int n_h, int d_h,
+    const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const bf16_t* __restrict__ W_dkv2, int d_ck,
+    const int32_t* __restrict__ elite_idx, bf16_t* __restrict__ ke_plane, bf16_t* __restrict__ c_plane, int64_t plane_rows, int d, int n_h, int d_h,
     int r, int d_c, RopeTable rope) {
   using L = GemmLayout<WN>;
   extern __shared__ __attribute__((aligned(16))) char gsm[];
@@ -231,8 +232,7 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
 
   const bf16_t* wbase;
   int64_t wstride;
-  if (n0 < NE) { wbase = W_ke + n0; wstride = NE; }
-  else { wbase = W_dkv + (n0 - NE); wstride = d_c; }
+  weight_column(n0, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wbase, &wstride);   // a block lies in one matrix
 
   uint4 areg[4], breg[L::NB];
   auto load_stage = [&](int k0) {
@@ -362,10 +362,10 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
   }
 }
 
-bool append_gemm_supported(const elitekv_dims& d, int64_t T) {
+bool append_gemm_supported(const elitekv_dims& d, int64_t T, int d_ck) {
   if (d.dtype != ELITEKV_BF16 || T <= 64) return false;
   const int NE = 2 * d.r * d.n_heads;
-  return NE % kGmCols == 0 && d.d_c % kGmCols == 0 && d.d_model % 8 == 0;
+  return NE % kGmCols == 0 && d.d_c % kGmCols == 0 && d_ck % kGmCols == 0 && d.d_model % 8 == 0;
 }
 
 template <int WN>
@@ -382,8 +382,8 @@ static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
   }
   const dim3 grid(N / kGmCols, (unsigned)((a.T + L::BN - 1) / L::BN));
   append_gemm_kernel<WN><<<grid, 256, L::LDS_BYTES, stream>>>(
-      (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv, a.elite_idx,
-      (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows, d.d_model, d.n_heads, d.head_dim, d.r, d.d_c,
+      (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
+      (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows, d.d_model, d.n_heads, d.head_dim, d.r, d.d_c,
       make_rope_table(d.rope_base, d.head_dim));
   return hipGetLastError();
 }

@@ -16,7 +16,8 @@ constexpr int kAsTokens = 8;      // most tokens per work-group pass
 template <int TT>
 __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
     const bf16_t* __restrict__ x, int64_t T, const bf16_t* __restrict__ W_ke,
-    const bf16_t* __restrict__ W_dkv, float* __restrict__ partial, int d, int NE, int d_c, int kc) {
+    const bf16_t* __restrict__ W_dkv, const bf16_t* __restrict__ W_dkv2, int d_ck, float* __restrict__ partial,
+    int d, int NE, int d_c, int kc) {
   extern __shared__ __attribute__((aligned(16))) float xs[];   // [kc][TT]
   __shared__ float red[4][8][TT][8];                    // [wave][column chunk][token][8 cols]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -28,8 +29,8 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
 
   const bf16_t* wbase;
   int64_t wstride;
-  if (n0 < NE) { wbase = W_ke + n0 + cchunk * 8; wstride = NE; }
-  else { wbase = W_dkv + (n0 - NE) + cchunk * 8; wstride = d_c; }
+  weight_column(n0, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wbase, &wstride);   // a block lies in one matrix
+  wbase += cchunk * 8;
 
   // the weight rows of the first batch are requested before anything else: they are the long pole
   constexpr int kBatch = 8;
@@ -144,10 +145,10 @@ __global__ __launch_bounds__(256) void append_finish_kernel(
   }
 }
 
-bool append_small_supported(const elitekv_dims& d, int64_t T) {
+bool append_small_supported(const elitekv_dims& d, int64_t T, int d_ck) {
   if (d.dtype != ELITEKV_BF16 || T > 64) return false;
   const int NE = 2 * d.r * d.n_heads;
-  return NE % kAsCols == 0 && d.d_c % kAsCols == 0;
+  return NE % kAsCols == 0 && d.d_c % kAsCols == 0 && d_ck % kAsCols == 0;
 }
 
 // contraction splits so that (column blocks x splits) is about two work-groups per compute unit
@@ -172,7 +173,8 @@ hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream) {
 #define EKV_AS(TT)                                                                                   \
   append_small_kernel<TT><<<dim3(N / kAsCols, ks, (unsigned)((a.T + TT - 1) / TT)), kAsThreads,      \
                             (size_t)kc * TT * sizeof(float), stream>>>(                             \
-      (const bf16_t*)a.x, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv, partial, d.d_model, NE, d.d_c, kc)
+      (const bf16_t*)a.x, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv, (const bf16_t*)a.W_dkv2, a.d_ck,  \
+      partial, d.d_model, NE, d.d_c, kc)
   if (a.T == 1) EKV_AS(1);
   else if (a.T == 2) EKV_AS(2);
   else if (a.T <= 4) EKV_AS(4);

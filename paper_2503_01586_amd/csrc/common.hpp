@@ -35,6 +35,17 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Column n of the append's output Y = x [W_ke | W_dkv | W_dkv2]: which weight matrix holds it, at
+// which column, with which row stride.  NE = 2 r n_h elite columns, then d_ck columns of W_dkv,
+// then d_c - d_ck columns of W_dkv2 (separated latents; d_ck == d_c for the joint latent).
+template <typename T>
+__device__ __forceinline__ void weight_column(int n, int NE, int d_ck, int d_c, const T* W_ke, const T* W_dkv,
+                                              const T* W_dkv2, const T** base, int64_t* stride) {
+  if (n < NE) { *base = W_ke + n; *stride = NE; }
+  else if (n - NE < d_ck) { *base = W_dkv + (n - NE); *stride = d_ck; }
+  else { *base = W_dkv2 + (n - NE - d_ck); *stride = d_c - d_ck; }
+}
+
 // theta_i = base^(-2i/d_h) (Section 2.2; RoFormer's frequencies), computed once per call on the
 // host in double and handed to the kernels by value (head_dim <= 256: at most 128 chunks).
 struct RopeTable {

@@ -72,11 +72,13 @@ template <typename T, int CPT>
 __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
     const T* __restrict__ ke_plane, const T* __restrict__ c_plane, const float* __restrict__ qe,
     const float* __restrict__ qt, const int32_t* __restrict__ seq_len, float* __restrict__ part_m,
-    float* __restrict__ part_l, float* __restrict__ part_u, int n_h, int two_r, int d_c,
+    float* __restrict__ part_l, float* __restrict__ part_u, int n_h, int two_r, int d_c, int d_q, int d_u,
     int64_t max_seq_len, int64_t batch_stride_rows, int64_t plane_rows, int n_splits, int chunk) {
   extern __shared__ float smem[];
-  float* qt_s = smem;                 // [d_c]
-  float* qe_s = qt_s + d_c;           // [two_r]
+  // a cache row holds d_c latent columns: the first d_q of them enter the scores, the last d_u are
+  // accumulated as values (joint latent: d_q = d_u = d_c, the same columns serve both)
+  float* qt_s = smem;                 // [d_q]
+  float* qe_s = qt_s + d_q;           // [two_r]
   float* s_tile = qe_s + two_r;       // [kGenTile]
   float* p_tile = s_tile + kGenTile;  // [kGenTile]
 
@@ -91,7 +93,8 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
   const int64_t t0 = (int64_t)split * chunk;
   const int64_t t1 = min(t0 + chunk, len);
 
-  for (int k = tid; k < d_c; k += kGenThreads) qt_s[k] = qt[((int64_t)b * n_h + h) * d_c + k];
+  const int v0 = d_c - d_u;
+  for (int k = tid; k < d_q; k += kGenThreads) qt_s[k] = qt[((int64_t)b * n_h + h) * d_q + k];
   for (int e = tid; e < two_r; e += kGenThreads) qe_s[e] = qe[((int64_t)b * n_h + h) * two_r + e];
   __syncthreads();
 
@@ -109,7 +112,7 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
       if (ti < nt) {
         const int64_t row = row0 + tile + ti;
         const T* crow = c_plane + row * d_c;
-        for (int k = lane; k < d_c; k += 64) part = fmaf(qt_s[k], ld(crow, k), part);
+        for (int k = lane; k < d_q; k += 64) part = fmaf(qt_s[k], ld(crow, k), part);
         const T* krow = ke_plane + (row * n_h + h) * two_r;
         for (int e = lane; e < two_r; e += 64) part = fmaf(qe_s[e], ld(krow, e), part);
       }
@@ -127,9 +130,9 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
 #pragma unroll
     for (int cc = 0; cc < CPT; ++cc) {
       const int k = tid + cc * kGenThreads;
-      if (k < d_c) {
+      if (k < d_u) {
         float a = acc[cc] * alpha;
-        const T* col = c_plane + (row0 + tile) * d_c + k;
+        const T* col = c_plane + (row0 + tile) * d_c + v0 + k;
         for (int tt = 0; tt < nt; ++tt) a = fmaf(p_tile[tt], ld(col, (int64_t)tt * d_c), a);
         acc[cc] = a;
       }
@@ -146,7 +149,7 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
 #pragma unroll
   for (int cc = 0; cc < CPT; ++cc) {
     const int k = tid + cc * kGenThreads;
-    if (k < d_c) part_u[pi * d_c + k] = acc[cc];
+    if (k < d_u) part_u[pi * d_u + k] = acc[cc];
   }
 }
 
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(kGenThreads) void merge_upproj_generic_kernel(
 template <typename T>
 static hipError_t launch_decode_generic_t(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
-  const int n_h = d.n_heads, d_h = d.head_dim, r = d.r, d_c = d.d_c;
+  const int n_h = d.n_heads, d_h = d.head_dim, r = d.r, d_c = d.d_c, d_q = p.d_q, d_u = p.d_u;
   float* qe = (float*)(a.ws + p.off_qe);
   float* qt = (float*)(a.ws + p.off_qt);
   float* pm = (float*)(a.ws + p.off_m);
@@ -226,15 +229,15 @@ static hipError_t launch_decode_generic_t(const DecodeArgs& a, const DecodePlan&
 
   if (a.stages & 1)
     qprep_generic_kernel<T><<<dim3(n_h, (unsigned)a.B), kGenThreads, 0, stream>>>(
-        (const T*)a.q, a.q_pos, (const T*)a.W_uk, a.elite_idx, qe, qt, n_h, d_h, r, d_c,
+        (const T*)a.q, a.q_pos, (const T*)a.W_uk, a.elite_idx, qe, qt, n_h, d_h, r, d_q,
         make_rope_table(d.rope_base, d.head_dim), scale_log2e);
 
   const dim3 grid(p.n_splits, n_h, (unsigned)a.B);
-  const size_t sm = sizeof(float) * (size_t)(d_c + 2 * r + 2 * kGenTile);
-  const int cpt = (d_c + kGenThreads - 1) / kGenThreads;
+  const size_t sm = sizeof(float) * (size_t)(d_q + 2 * r + 2 * kGenTile);
+  const int cpt = (d_u + kGenThreads - 1) / kGenThreads;
 #define EKV_ATTN(C)                                                                               \
   attn_generic_kernel<T, C><<<grid, kGenThreads, sm, stream>>>(                                   \
-      (const T*)a.ke_plane, (const T*)a.c_plane, qe, qt, a.seq_len, pm, pl, pu, n_h, 2 * r, d_c,  \
+      (const T*)a.ke_plane, (const T*)a.c_plane, qe, qt, a.seq_len, pm, pl, pu, n_h, 2 * r, d_c, d_q, d_u, \
       a.max_seq_len, a.batch_stride_rows, a.plane_rows, p.n_splits, p.chunk)
   if (!(a.stages & 2)) {}
   else if (cpt <= 1) EKV_ATTN(1);
@@ -245,9 +248,9 @@ static hipError_t launch_decode_generic_t(const DecodeArgs& a, const DecodePlan&
 #undef EKV_ATTN
 
   if (!(a.stages & 4)) return hipGetLastError();
-  const size_t sm2 = sizeof(float) * (size_t)(d_c + p.n_splits + kGenThreads);
+  const size_t sm2 = sizeof(float) * (size_t)(d_u + p.n_splits + kGenThreads);
   merge_upproj_generic_kernel<T><<<dim3(n_h, (unsigned)a.B), kGenThreads, sm2, stream>>>(
-      pm, pl, pu, (const T*)a.W_uv, (T*)a.out, n_h, d_h, d_c, p.n_splits);
+      pm, pl, pu, (const T*)a.W_uv, (T*)a.out, n_h, d_h, d_u, p.n_splits);
   return hipGetLastError();
 }
 

@@ -43,6 +43,7 @@ struct AttnMfmaParams {
   bf16_t* part_u;         // [B, n_splits, HG*32, d_c]   split latent accumulators, head-major
   int n_h, d_c, n_splits, chunk, head_groups;
   int batch, pair_map;    // pair_map: 1-D grid, the two head groups of an item share an XCD
+  int d_q, d_u;           // widths of the absorbed query and of the latent accumulators (d_c when joint)
   int64_t max_seq_len, batch_stride_rows, plane_rows;
 };
 
@@ -120,7 +121,10 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 // log2-domain slack before the running maximum is raised: probabilities stay below 2^8
 constexpr float kRescaleSlack = 8.f;
 
-template <int NW, int DC_W, int TWO_R>
+// SEP = separated latents (Section 3.2, S-LRD): a cache row is [c^k (d_q columns) | c^v (d_u columns)];
+// the waves whose slice lies in c^k only compute scores, the waves whose slice lies in c^v only
+// accumulate values (d_q is a multiple of DC_W).  SEP = false is the joint latent: every wave does both.
+template <int NW, int DC_W, int TWO_R, bool SEP>
 __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams p) {
   using L = AttnMfmaLayout<NW, DC_W, TWO_R>;
   constexpr int KS = L::KS, CT = L::CT, NCB = L::NCB, EPL = L::EPL, TPW = L::TPW;
@@ -134,6 +138,10 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
+  const int nwk = SEP ? p.d_q / DC_W : NW;               // waves that compute scores
+  const bool do_s = !SEP || wave < nwk;                  // this wave's slice enters the scores
+  const bool do_v = !SEP || wave >= nwk;                 // this wave's slice is accumulated as values
+  const int vwave = SEP ? wave - nwk : wave;             // position of the slice among the value slices
   int split = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
   if (p.pair_map) {
     // Two head groups read the same latent rows.  Work-groups go to the eight XCDs round-robin by
@@ -170,8 +178,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
       p.part_m[pidx + n] = -INFINITY;
       p.part_l[pidx + n] = 0.f;
     }
-    uint4* z = reinterpret_cast<uint4*>(p.part_u + pidx * (int64_t)p.d_c);
-    for (int i = tid; i < 4 * p.d_c; i += NW * 64) z[i] = make_uint4(0, 0, 0, 0);
+    uint4* z = reinterpret_cast<uint4*>(p.part_u + pidx * (int64_t)p.d_u);
+    for (int i = tid; i < 4 * p.d_u; i += NW * 64) z[i] = make_uint4(0, 0, 0, 0);
     return;
   }
 
@@ -189,10 +197,11 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   for (int hh = 0; hh < 2; ++hh) {
     const int hq = hg * 32 + hh * 16 + i16;
     const bool ok = hq < p.n_h;
-    const bf16_t* qrow = p.qt + ((int64_t)b * p.n_h + (ok ? hq : p.n_h - 1)) * p.d_c + wave * DC_W + 8 * q16;
+    const bf16_t* qrow = p.qt + ((int64_t)b * p.n_h + (ok ? hq : p.n_h - 1)) * p.d_q + (do_s ? wave : 0) * DC_W + 8 * q16;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      s16x8 v = *reinterpret_cast<const s16x8*>(qrow + 32 * ks);
+      s16x8 v = (s16x8)(0);
+      if (do_s) v = *reinterpret_cast<const s16x8*>(qrow + 32 * ks);
       if (!ok) v = (s16x8)(0);
       Qb[ks][hh] = __builtin_bit_cast(bf16x8, v);
     }
@@ -286,6 +295,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   auto compute = [&](int64_t tile, const char* ctile, char* ketile, int64_t next_tile) {
     // ---- partial scores over this wave's latent slice, two head halves
     f32x4 sd[2] = {(f32x4)(0.f), (f32x4)(0.f)};
+    if (do_s) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       if (KS > 8 && ks % 4 == 0) asm volatile("" ::: "memory");   // wide slices: bound the operand look-ahead
@@ -294,8 +304,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
       sd[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Qb[ks][0], sd[0], 0, 0, 0);
       sd[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Qb[ks][1], sd[1], 0, 0, 0);
     }
+    }
     // ---- stage 1: publish them as x1[wave][token][head]; lane holds tokens 4*q16 + v, head hh*16 + i16
-    {
+    if (do_s) {
       float* xw = x1 + (wave * kTile + 4 * q16) * L::X1_ROW + i16;
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh)
@@ -331,7 +342,8 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
     for (int e = 0; e < EPL; ++e) {
       const int tok = own_t0 + 2 * e;
 #pragma unroll
-      for (int w2 = 0; w2 < NW; ++w2) fin[e] += x1[(w2 * kTile + tok) * L::X1_ROW + n];
+      for (int w2 = 0; w2 < NW; ++w2)
+        if (!SEP || w2 < nwk) fin[e] += x1[(w2 * kTile + tok) * L::X1_ROW + n];
       x2[n * L::X2_ROW + tok] = fin[e];
     }
     __syncthreads();
@@ -385,6 +397,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
       }
     }
     // ---- latent accumulation: U^T += C^T P^T, the tile read transposed from LDS
+    if (do_v) {
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
       if (CT > 8 && ct % 4 == 0) asm volatile("" ::: "memory");
@@ -396,6 +409,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
           (lds_s16x4_t*)(trp + (in_half ? trh_off[1] : tr_off[1][ct & 1])));
       const s16x8 a16 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       uacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a16), P, uacc[ct], 0, 0, 0);
+    }
     }
   };
 
@@ -461,39 +475,47 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
     }
   }
   constexpr int CPRW = DC_W * 2 / 16;                       // 16-byte chunks per head row
-  char* ubase = reinterpret_cast<char*>(p.part_u) + (pidx * (int64_t)p.d_c + (int64_t)wave * DC_W) * 2;
+  char* ubase = reinterpret_cast<char*>(p.part_u) + (pidx * (int64_t)p.d_u + (int64_t)(do_v ? vwave : 0) * DC_W) * 2;
 #pragma unroll
   for (int i = 0; i < 32 * CPRW / 64; ++i) {
     const int idx = i * 64 + lane;
     const int row = idx / CPRW, ch = idx % CPRW;
     const uint4 v = *reinterpret_cast<const uint4*>(tt + row * TSTR + ch * 16);
-    if (hg * 32 + row < p.n_h) *reinterpret_cast<uint4*>(ubase + (int64_t)row * p.d_c * 2 + ch * 16) = v;
+    if (do_v && hg * 32 + row < p.n_h) *reinterpret_cast<uint4*>(ubase + (int64_t)row * p.d_u * 2 + ch * 16) = v;
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int NW, int DC_W, int TWO_R>
+template <int NW, int DC_W, int TWO_R, bool SEP>
 static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t stream) {
   using L = AttnMfmaLayout<NW, DC_W, TWO_R>;
   static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<NW, DC_W, TWO_R>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<NW, DC_W, TWO_R, SEP>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const dim3 grid = prm.pair_map ? dim3((unsigned)((prm.n_splits * B + 7) / 8 * 16), 1, 1)
                                  : dim3(prm.n_splits, prm.head_groups, (unsigned)B);
-  attn_mfma_kernel<NW, DC_W, TWO_R><<<grid, NW * 64, L::LDS_BYTES, stream>>>(prm);
+  attn_mfma_kernel<NW, DC_W, TWO_R, SEP><<<grid, NW * 64, L::LDS_BYTES, stream>>>(prm);
   return hipGetLastError();
 }
 
-bool decode_mfma_supported(const elitekv_dims& d) {
+// wave slice of the compiled instantiation for a latent row of d_c columns; 0 = none
+static int slice_width(int d_c) { return d_c == 1920 ? 480 : d_c == 1536 || d_c == 768 ? 192 : d_c == 256 ? 64 : 0; }
+
+bool decode_mfma_supported(const elitekv_dims& d, int d_ck) {
   if (d.dtype != ELITEKV_BF16) return false;
   if ((d.head_dim != 128 && d.head_dim != 64) || (d.head_dim - 2 * d.r) % 8) return false;
   const int two_r = 2 * d.r;
   if (two_r != 8 && two_r != 16) return false;
-  return d.d_c == 1920 || d.d_c == 1536 || d.d_c == 768 || d.d_c == 256;
+  const int w = slice_width(d.d_c);
+  if (w == 0) return false;
+  if (d_ck > 0 && w == 480) return false;   // the one-wave-per-SIMD instantiation is compiled for the joint latent only
+  // separated latents: whole wave slices on either side of the boundary
+  // (and the value part a whole number of the merge kernels' 64-column chunks)
+  return d_ck == 0 || (d_ck > 0 && d_ck < d.d_c && d_ck % w == 0 && (d.d_c - d_ck) % 64 == 0);
 }
 
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
@@ -509,20 +531,25 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.head_groups = p.head_groups; prm.max_seq_len = a.max_seq_len;
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
   prm.batch = (int)a.B; prm.pair_map = p.head_groups == 2 ? 1 : 0;
+  prm.d_q = p.d_q; prm.d_u = p.d_u;
 
   hipError_t e = hipSuccess;
-  if (a.stages & 1) e = launch_qprep_rows(a, qe, qt, stream);
+  if (a.stages & 1) e = launch_qprep_rows(a, p, qe, qt, stream);
   if (e != hipSuccess) return e;
   if (!(a.stages & 2)) return (a.stages & 4) ? launch_merge_up(a, p, stream) : hipSuccess;
 
   e = hipErrorInvalidValue;
   const int two_r = 2 * d.r;
-#define EKV_CASE(DC, NWV, DCW)                                                        \
-  if (d.d_c == DC) {                                                                  \
-    e = two_r == 16 ? launch_attn<NWV, DCW, 16>(prm, a.B, stream)                     \
-                    : launch_attn<NWV, DCW, 8>(prm, a.B, stream);                     \
+  const bool sep = a.d_ck > 0;
+#define EKV_CASE(DC, NWV, DCW)                                                                         \
+  if (d.d_c == DC) {                                                                                   \
+    e = sep ? (two_r == 16 ? launch_attn<NWV, DCW, 16, true>(prm, a.B, stream)                         \
+                           : launch_attn<NWV, DCW, 8, true>(prm, a.B, stream))                         \
+            : (two_r == 16 ? launch_attn<NWV, DCW, 16, false>(prm, a.B, stream)                        \
+                           : launch_attn<NWV, DCW, 8, false>(prm, a.B, stream));                       \
   }
-  EKV_CASE(1920, 4, 480)
+  if (d.d_c == 1920)
+    e = two_r == 16 ? launch_attn<4, 480, 16, false>(prm, a.B, stream) : launch_attn<4, 480, 8, false>(prm, a.B, stream);
   EKV_CASE(1536, 8, 192)
   EKV_CASE(768, 4, 192)
   EKV_CASE(256, 4, 64)

@@ -136,11 +136,11 @@ __global__ __launch_bounds__(kQpThreads) void qprep_rows_kernel(
 }
 
 template <int BT>
-static hipError_t launch_qprep_bt(const DecodeArgs& a, float* qe, bf16_t* qt, hipStream_t stream) {
+static hipError_t launch_qprep_bt(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
   const int nd = d.head_dim - 2 * d.r;
   const size_t sm = (size_t)BT * d.n_heads * (nd + 8) * 2 + (size_t)d.n_heads * 8;   // < 64 KiB for n_h <= 32
-  const int64_t rows = (int64_t)d.d_c * d.n_heads;
+  const int64_t rows = (int64_t)p.d_q * d.n_heads;
   const dim3 grid((unsigned)((rows + kQpThreads - 1) / kQpThreads), (unsigned)((a.B + BT - 1) / BT));
   if (sm > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&qprep_rows_kernel<BT>),
@@ -149,7 +149,7 @@ static hipError_t launch_qprep_bt(const DecodeArgs& a, float* qe, bf16_t* qt, hi
   }
   qprep_rows_kernel<BT><<<grid, kQpThreads, sm, stream>>>(
       (const bf16_t*)a.q, a.q_pos, (const bf16_t*)a.W_uk, a.elite_idx, qe, qt, (int)a.B, d.n_heads, d.head_dim,
-      d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim), kLog2e / sqrtf((float)d.head_dim));
+      d.r, p.d_q, make_rope_table(d.rope_base, d.head_dim), kLog2e / sqrtf((float)d.head_dim));
   return hipGetLastError();
 }
 
@@ -255,21 +255,21 @@ __global__ __launch_bounds__(256) void qprep_mfma_kernel(
   }
 }
 
-bool qprep_mfma_supported(const elitekv_dims& d, int64_t B) {
+bool qprep_mfma_supported(const elitekv_dims& d, int d_q, int64_t B) {
   const int nd = d.head_dim - 2 * d.r;
-  return B >= 8 && d.d_c % 128 == 0 && nd % 8 == 0 && nd >= 16 && nd <= 128 && d.head_dim <= 128;
+  return B >= 8 && d_q % 128 == 0 && nd % 8 == 0 && nd >= 16 && nd <= 128 && d.head_dim <= 128;
 }
 
-static hipError_t launch_qprep_mfma(const DecodeArgs& a, float* qe, bf16_t* qt, hipStream_t stream) {
+static hipError_t launch_qprep_mfma(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
   const int nd = d.head_dim - 2 * d.r;
   const int ks = (nd + 15) / 16;
   const size_t sm = (size_t)kQmRows * (nd + 8) * 2 + 64 * sizeof(int);
-  const dim3 grid(d.d_c / 128, d.n_heads);
+  const dim3 grid(p.d_q / 128, d.n_heads);
 #define EKV_QM(KSV)                                                                                   \
   qprep_mfma_kernel<KSV><<<grid, 256, sm, stream>>>(                                                  \
       (const bf16_t*)a.q, a.q_pos, (const bf16_t*)a.W_uk, a.elite_idx, qe, qt, (int)a.B, d.n_heads,   \
-      d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim), kLog2e / sqrtf((float)d.head_dim))
+      d.head_dim, d.r, p.d_q, make_rope_table(d.rope_base, d.head_dim), kLog2e / sqrtf((float)d.head_dim))
   switch (ks) {
     case 1: EKV_QM(1); break;
     case 2: EKV_QM(2); break;
@@ -284,12 +284,12 @@ static hipError_t launch_qprep_mfma(const DecodeArgs& a, float* qe, bf16_t* qt, 
   return hipGetLastError();
 }
 
-hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt, hipStream_t stream) {
-  if (qprep_mfma_supported(a.dims, a.B)) return launch_qprep_mfma(a, qe, qt, stream);
-  if (a.B == 1) return launch_qprep_bt<1>(a, qe, qt, stream);
-  if (a.B == 2) return launch_qprep_bt<2>(a, qe, qt, stream);
-  if (a.B <= 4) return launch_qprep_bt<4>(a, qe, qt, stream);
-  return launch_qprep_bt<kQpBatchTile>(a, qe, qt, stream);
+hipError_t launch_qprep_rows(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt, hipStream_t stream) {
+  if (qprep_mfma_supported(a.dims, p.d_q, a.B)) return launch_qprep_mfma(a, p, qe, qt, stream);
+  if (a.B == 1) return launch_qprep_bt<1>(a, p, qe, qt, stream);
+  if (a.B == 2) return launch_qprep_bt<2>(a, p, qe, qt, stream);
+  if (a.B <= 4) return launch_qprep_bt<4>(a, p, qe, qt, stream);
+  return launch_qprep_bt<kQpBatchTile>(a, p, qe, qt, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -661,8 +661,8 @@ __global__ __launch_bounds__(256) void out_reduce_kernel(const float* __restrict
   st(out, e, a);
 }
 
-bool merge_batch_supported(const elitekv_dims& d, int64_t B, int64_t n_splits) {
-  if (B < 2 || d.d_c % 128 || (d.head_dim != 128 && d.head_dim != 64)) return false;
+bool merge_batch_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits) {
+  if (B < 2 || d_u % 128 || (d.head_dim != 128 && d.head_dim != 64)) return false;
   return (B < kMbRows ? B : kMbRows) * n_splits <= kMbWeightFloats;   // (any smaller row tile fits too)
 }
 
@@ -672,7 +672,7 @@ static hipError_t launch_merge_batch(const DecodeArgs& a, const DecodePlan& p, h
   const elitekv_dims& d = a.dims;
   // rows per work-group: all of them (up to kMbRows) unless that leaves compute units idle
   int rows = (int)(a.B < kMbRows ? a.B : kMbRows);
-  const int64_t groups = (int64_t)(d.d_c / CW) * d.n_heads;
+  const int64_t groups = (int64_t)(p.d_u / CW) * d.n_heads;
   while (rows > 16 && groups * ((a.B + rows - 1) / rows) < 256) rows = (rows + 1) / 2;
   const size_t sm = L::lds_bytes(rows, p.n_splits);
   static size_t sm_set = 64 * 1024;   // raising the dynamic-LDS limit is idempotent
@@ -682,10 +682,10 @@ static hipError_t launch_merge_batch(const DecodeArgs& a, const DecodePlan& p, h
     if (e != hipSuccess) return e;
     sm_set = sm;
   }
-  const dim3 grid(d.d_c / CW, d.n_heads, (unsigned)((a.B + rows - 1) / rows));
+  const dim3 grid(p.d_u / CW, d.n_heads, (unsigned)((a.B + rows - 1) / rows));
   merge_up_batch_kernel<CW, DH><<<grid, 256, sm, stream>>>(
       (const float*)(a.ws + p.off_m), (const float*)(a.ws + p.off_l), (const bf16_t*)(a.ws + p.off_u),
-      (const bf16_t*)a.W_uv, (float*)(a.ws + p.off_opart), (int)a.B, d.n_heads, p.head_groups * 32, d.d_c,
+      (const bf16_t*)a.W_uv, (float*)(a.ws + p.off_opart), (int)a.B, d.n_heads, p.head_groups * 32, p.d_u,
       p.n_splits, rows);
   return hipGetLastError();
 }
@@ -698,7 +698,7 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
     if (e != hipSuccess) return e;
     const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
     out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
-        (const float*)(a.ws + p.off_opart), (bf16_t*)a.out, d.head_dim, d.d_c / 128, total);
+        (const float*)(a.ws + p.off_opart), (bf16_t*)a.out, d.head_dim, p.d_u / 128, total);
     return hipGetLastError();
   }
   const float* pm = (const float*)(a.ws + p.off_m);
@@ -707,13 +707,13 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
   float* opart = (float*)(a.ws + p.off_opart);
   uint32_t* cnt = (uint32_t*)(a.ws + p.off_cnt);
   const int cw = p.up_cw;
-  const dim3 grid(d.d_c / cw, d.n_heads, (unsigned)a.B);
+  const dim3 grid(p.d_u / cw, d.n_heads, (unsigned)a.B);
   const int nhp = p.head_groups * 32;
 #define EKV_MU(CW, DH)                                                                              \
   do {                                                                                              \
     const size_t sm = sizeof(float) * ((size_t)p.n_splits + 256 + (size_t)(256 / (CW / 8)) * CW + CW); \
     merge_up_kernel<CW, DH><<<grid, 256, sm, stream>>>(pm, pl, pu, (const bf16_t*)a.W_uv, opart, cnt, \
-                                                       (bf16_t*)a.out, d.n_heads, nhp, d.d_c,        \
+                                                       (bf16_t*)a.out, d.n_heads, nhp, p.d_u,        \
                                                        p.n_splits);                                 \
   } while (0)
   if (cw == 192) { if (d.head_dim == 128) EKV_MU(192, 128); else EKV_MU(192, 64); }
@@ -723,7 +723,7 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
   if (e != hipSuccess) return e;
   const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
   out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(opart, (bf16_t*)a.out, d.head_dim,
-                                                                        d.d_c / cw, total);
+                                                                        p.d_u / cw, total);
   return hipGetLastError();
 }
 

@@ -36,19 +36,25 @@ static int32_t auto_splits_generic(const elitekv_dims* d, int64_t B, int64_t max
 }
 
 // Decide the path and lay the workspace out.  Returns a status.
-static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_t n_splits, DecodePlan* p) {
+// d_ck = 0: joint latent; d_ck > 0: separated latents, a cache row is [c^k (d_ck) | c^v (d_c - d_ck)]
+static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t max_seq, int32_t n_splits,
+                       DecodePlan* p) {
   int st = check_dims(d);
   if (st) return st;
   if (B < 0 || max_seq < 0 || n_splits < 0) return ELITEKV_EINVAL;
+  if (d_ck < 0 || d_ck >= d->d_c) return ELITEKV_EINVAL;
   if (d->d_c > 4096 || d->head_dim > 256 || n_splits > kMaxSplits) return ELITEKV_EUNSUPPORTED;
   if (B > 65535) return ELITEKV_EUNSUPPORTED;
   memset(p, 0, sizeof(*p));
   const int64_t Bq = B > 0 ? B : 1;
   const int64_t seq = max_seq > 0 ? max_seq : 1;
-  const size_t nh = d->n_heads, dc = d->d_c, Bz = (size_t)B;
+  const size_t nh = d->n_heads, Bz = (size_t)B;
+  p->d_q = d_ck > 0 ? d_ck : d->d_c;
+  p->d_u = d_ck > 0 ? d->d_c - d_ck : d->d_c;
+  const size_t dq = p->d_q, du = p->d_u;
   size_t off = 0;
   p->off_qe = off; off = align_up(off + Bz * nh * 2 * d->r * sizeof(float), 256);
-  if (decode_mfma_supported(*d)) {
+  if (decode_mfma_supported(*d, d_ck)) {
     // one work-group per (split, group of 32 heads, batch row); one group fills a compute unit
     p->mfma = 1;
     p->head_groups = (d->n_heads + 31) / 32;
@@ -65,14 +71,14 @@ static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_
     chunk = (chunk + 31) / 32 * 32;
     p->chunk = (int32_t)chunk;
     const size_t np = Bz * (size_t)ns * p->head_groups;
-    p->off_qt = off; off = align_up(off + Bz * nh * dc * 2, 256);
+    p->off_qt = off; off = align_up(off + Bz * nh * dq * 2, 256);
     p->off_m = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_l = off;  off = align_up(off + np * 32 * sizeof(float), 256);
-    p->off_u = off;  off = align_up(off + np * 32 * dc * 2, 256);
-    p->merge_batch = merge_batch_supported(*d, B, ns) ? 1 : 0;
-    p->up_cw = p->merge_batch ? 128 : (d->d_c % 192 == 0) ? 192 : 64;
+    p->off_u = off;  off = align_up(off + np * 32 * du * 2, 256);
+    p->merge_batch = merge_batch_supported(*d, p->d_u, B, ns) ? 1 : 0;
+    p->up_cw = p->merge_batch ? 128 : (p->d_u % 192 == 0) ? 192 : 64;
     p->off_opart = off;
-    off = align_up(off + Bz * nh * (size_t)(d->d_c / p->up_cw) * d->head_dim * sizeof(float), 256);
+    off = align_up(off + Bz * nh * (size_t)(p->d_u / p->up_cw) * d->head_dim * sizeof(float), 256);
     p->off_cnt = off;
     off = align_up(off + Bz * nh * sizeof(uint32_t), 256);
   } else {
@@ -83,10 +89,10 @@ static int plan_decode(const elitekv_dims* d, int64_t B, int64_t max_seq, int32_
     if (chunk < 1) chunk = 1;
     p->chunk = (int32_t)chunk;
     const size_t ns = p->n_splits;
-    p->off_qt = off; off = align_up(off + Bz * nh * dc * sizeof(float), 256);
+    p->off_qt = off; off = align_up(off + Bz * nh * dq * sizeof(float), 256);
     p->off_m = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
     p->off_l = off;  off = align_up(off + Bz * ns * nh * sizeof(float), 256);
-    p->off_u = off;  off = align_up(off + Bz * ns * nh * dc * sizeof(float), 256);
+    p->off_u = off;  off = align_up(off + Bz * ns * nh * du * sizeof(float), 256);
   }
   p->total = off;
   return ELITEKV_OK;
@@ -166,63 +172,79 @@ int elitekv_validate_elite_idx(const elitekv_dims* dims, const int32_t* idx_host
   return ELITEKV_OK;
 }
 
-size_t elitekv_append_workspace_bytes(const elitekv_dims* dims, int64_t T) {
+// d_ck = columns of the first latent weight matrix (d_c for the joint latent)
+static size_t append_ws_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t T) {
   if (check_dims(dims) || T < 0) return 0;
-  if (T > 0 && append_skinny_supported(*dims, T)) return align_up(append_skinny_workspace(*dims, T), 256);
-  if (T > 0 && append_small_supported(*dims, T)) return align_up(append_small_workspace(*dims, T), 256);
+  if (T > 0 && append_gemm_supported(*dims, T, d_ck)) return 0;
+  if (T > 0 && append_skinny_supported(*dims, T, d_ck)) return align_up(append_skinny_workspace(*dims, T), 256);
+  if (T > 0 && append_small_supported(*dims, T, d_ck)) return align_up(append_small_workspace(*dims, T), 256);
   return 0;
+}
+
+static int append_impl(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                       const int64_t* slot, int64_t T, const void* W_ke, const void* W_dkv, const void* W_dkv2,
+                       const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows, void* ws,
+                       size_t ws_bytes, void* hip_stream) {
+  int st = check_dims(dims);
+  if (st) return st;
+  if (T < 0 || plane_rows < 0 || d_ck <= 0 || d_ck > dims->d_c) return ELITEKV_EINVAL;
+  if (T == 0) return ELITEKV_OK;
+  if (!x || !pos || !slot || !W_dkv || !c_plane) return ELITEKV_ENULL;
+  if (d_ck < dims->d_c && !W_dkv2) return ELITEKV_ENULL;
+  if (dims->r > 0 && (!W_ke || !elite_idx || !ke_plane)) return ELITEKV_ENULL;
+  if (!aligned16(x) || !aligned16(W_dkv) || !aligned16(W_dkv2) || !aligned16(c_plane) || !aligned16(W_ke) ||
+      !aligned16(ke_plane) || !aligned16(ws))
+    return ELITEKV_EALIGN;
+  const size_t need = append_ws_bytes(dims, d_ck, T);
+  if (need > 0 && (!ws || ws_bytes < need)) return ws ? ELITEKV_EWORKSPACE : ELITEKV_ENULL;
+  if ((T + 7) / 8 > 2147483647LL) return ELITEKV_EUNSUPPORTED;
+
+  AppendArgs a;
+  a.dims = *dims; a.d_ck = d_ck; a.x = x; a.pos = pos; a.slot = slot; a.T = T; a.W_ke = W_ke; a.W_dkv = W_dkv;
+  a.W_dkv2 = W_dkv2; a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane;
+  a.plane_rows = plane_rows; a.ws = (char*)ws;
+  const hipStream_t stream = (hipStream_t)hip_stream;
+  const hipError_t e = append_gemm_supported(*dims, T, d_ck)     ? launch_append_gemm(a, stream)
+                       : append_skinny_supported(*dims, T, d_ck) ? launch_append_skinny(a, stream)
+                       : append_small_supported(*dims, T, d_ck)  ? launch_append_small(a, stream)
+                                                                 : launch_append_generic(a, stream);
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+size_t elitekv_append_workspace_bytes(const elitekv_dims* dims, int64_t T) {
+  return dims ? append_ws_bytes(dims, dims->d_c, T) : 0;
 }
 
 int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, const int64_t* slot,
                    int64_t T, const void* W_ke, const void* W_dkv, const int32_t* elite_idx,
                    void* ke_plane, void* c_plane, int64_t plane_rows, void* ws, size_t ws_bytes,
                    void* hip_stream) {
-  int st = check_dims(dims);
-  if (st) return st;
-  if (T < 0 || plane_rows < 0) return ELITEKV_EINVAL;
-  if (T == 0) return ELITEKV_OK;
-  if (!x || !pos || !slot || !W_dkv || !c_plane) return ELITEKV_ENULL;
-  if (dims->r > 0 && (!W_ke || !elite_idx || !ke_plane)) return ELITEKV_ENULL;
-  if (!aligned16(x) || !aligned16(W_dkv) || !aligned16(c_plane) || !aligned16(W_ke) ||
-      !aligned16(ke_plane) || !aligned16(ws))
-    return ELITEKV_EALIGN;
-  const size_t need = elitekv_append_workspace_bytes(dims, T);
-  if (need > 0 && (!ws || ws_bytes < need)) return ws ? ELITEKV_EWORKSPACE : ELITEKV_ENULL;
-  if ((T + 7) / 8 > 2147483647LL) return ELITEKV_EUNSUPPORTED;
-
-  AppendArgs a;
-  a.dims = *dims; a.x = x; a.pos = pos; a.slot = slot; a.T = T; a.W_ke = W_ke; a.W_dkv = W_dkv;
-  a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows;
-  a.ws = (char*)ws;
-  const hipStream_t stream = (hipStream_t)hip_stream;
-  const hipError_t e = append_gemm_supported(*dims, T)     ? launch_append_gemm(a, stream)
-                       : append_skinny_supported(*dims, T) ? launch_append_skinny(a, stream)
-                       : append_small_supported(*dims, T) ? launch_append_small(a, stream)
-                                                          : launch_append_generic(a, stream);
-  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+  if (!dims) return ELITEKV_ENULL;
+  return append_impl(dims, dims->d_c, x, pos, slot, T, W_ke, W_dkv, nullptr, elite_idx, ke_plane, c_plane,
+                     plane_rows, ws, ws_bytes, hip_stream);
 }
 
 int32_t elitekv_decode_auto_splits(const elitekv_dims* dims, int64_t B, int64_t max_seq_len) {
   DecodePlan p;
-  if (plan_decode(dims, B, max_seq_len, 0, &p)) return 0;
+  if (plan_decode(dims, 0, B, max_seq_len, 0, &p)) return 0;
   return p.n_splits;
 }
 
 size_t elitekv_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
                                       int32_t n_splits) {
   DecodePlan p;
-  if (plan_decode(dims, B, max_seq_len, n_splits, &p)) return 0;
+  if (plan_decode(dims, 0, B, max_seq_len, n_splits, &p)) return 0;
   return p.total;
 }
 
-static int decode_impl(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+static int decode_impl(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
                        const int32_t* seq_len, int64_t B, int64_t max_seq_len,
                        int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
                        const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
                        int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
                        void* hip_stream, int32_t stages) {
   DecodePlan p;
-  int st = plan_decode(dims, B, max_seq_len, n_splits, &p);
+  int st = plan_decode(dims, d_ck, B, max_seq_len, n_splits, &p);
   if (st) return st;
   if (batch_stride_rows < 0 || plane_rows < 0) return ELITEKV_EINVAL;
   if (B == 0) return ELITEKV_OK;
@@ -236,13 +258,59 @@ static int decode_impl(const elitekv_dims* dims, const void* q, const int32_t* q
   if (ws_bytes < p.total) return ELITEKV_EWORKSPACE;
 
   DecodeArgs a;
-  a.dims = *dims; a.q = q; a.q_pos = q_pos; a.seq_len = seq_len; a.B = B; a.max_seq_len = max_seq_len;
-  a.batch_stride_rows = batch_stride_rows; a.W_uk = W_uk; a.W_uv = W_uv; a.elite_idx = elite_idx;
-  a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows; a.out = out; a.ws = (char*)ws;
-  a.stages = stages;
+  a.dims = *dims; a.d_ck = d_ck; a.q = q; a.q_pos = q_pos; a.seq_len = seq_len; a.B = B;
+  a.max_seq_len = max_seq_len; a.batch_stride_rows = batch_stride_rows; a.W_uk = W_uk; a.W_uv = W_uv;
+  a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows; a.out = out;
+  a.ws = (char*)ws; a.stages = stages;
   const hipError_t e = p.mfma ? launch_decode_mfma(a, p, (hipStream_t)hip_stream)
                              : launch_decode_generic(a, p, (hipStream_t)hip_stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+/* ---- separated low-rank decomposition (two latents per token, stored side by side) ---- */
+
+int elitekv_slrd_param_count(const elitekv_dims* dims, int32_t d_ck, int64_t* n_params) {
+  int st = check_dims(dims);
+  if (st) return st;
+  if (d_ck <= 0 || d_ck >= dims->d_c) return ELITEKV_EINVAL;
+  if (!n_params) return ELITEKV_ENULL;
+  const int64_t d = dims->d_model, nh = dims->n_heads, dh = dims->head_dim, r = dims->r;
+  const int64_t dck = d_ck, dcv = dims->d_c - d_ck;
+  *n_params = 2 * r * nh * d + dck * (d + dh * nh - 2 * r * nh) + dcv * (d + dh * nh);
+  return ELITEKV_OK;
+}
+
+size_t elitekv_slrd_append_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t T) {
+  if (!dims || d_ck <= 0 || d_ck >= dims->d_c) return 0;
+  return append_ws_bytes(dims, d_ck, T);
+}
+
+int elitekv_slrd_append(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                        const int64_t* slot, int64_t T, const void* W_ke, const void* A_k, const void* A_v,
+                        const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows, void* ws,
+                        size_t ws_bytes, void* hip_stream) {
+  if (!dims) return ELITEKV_ENULL;
+  if (d_ck <= 0 || d_ck >= dims->d_c) return ELITEKV_EINVAL;
+  return append_impl(dims, d_ck, x, pos, slot, T, W_ke, A_k, A_v, elite_idx, ke_plane, c_plane, plane_rows, ws,
+                     ws_bytes, hip_stream);
+}
+
+size_t elitekv_slrd_decode_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B,
+                                           int64_t max_seq_len, int32_t n_splits) {
+  DecodePlan p;
+  if (d_ck <= 0 || plan_decode(dims, d_ck, B, max_seq_len, n_splits, &p)) return 0;
+  return p.total;
+}
+
+int elitekv_slrd_decode_attn(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                             const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                             int64_t batch_stride_rows, const void* B_k, const void* B_v,
+                             const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                             int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                             void* hip_stream) {
+  if (d_ck <= 0) return dims ? ELITEKV_EINVAL : ELITEKV_ENULL;
+  return decode_impl(dims, d_ck, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, B_k, B_v, elite_idx,
+                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, 7);
 }
 
 int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
@@ -251,7 +319,7 @@ int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* 
                         const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
                         int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
                         void* hip_stream) {
-  return decode_impl(dims, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+  return decode_impl(dims, 0, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
                      ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, 7);
 }
 
@@ -262,7 +330,7 @@ int elitekv_decode_attn_stages(const elitekv_dims* dims, const void* q, const in
                                int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
                                int32_t n_splits, void* hip_stream, int32_t stages) {
   if (stages < 1 || stages > 7) return ELITEKV_EINVAL;
-  return decode_impl(dims, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+  return decode_impl(dims, 0, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
                      ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, stages);
 }
 

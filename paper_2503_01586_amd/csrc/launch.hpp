@@ -17,6 +17,8 @@ struct DecodePlan {
   int32_t head_groups;  // MFMA path: groups of up to 32 heads
   int32_t up_cw;        // MFMA path: latent columns per merge/up-projection work-group
   int32_t merge_batch;  // MFMA path: 1 = the merge kernel that takes all batch rows per work-group
+  int32_t d_q;          // width of the absorbed query: d_c (joint latent) or d_ck (separated latents)
+  int32_t d_u;          // width of the latent accumulators: d_c (joint) or d_cv (separated)
   size_t off_qe;        // rotated, scaled elite query      fp32 [B, n_h, 2r]
   size_t off_qt;        // absorbed, scaled latent query    fp32 [B, n_h, d_c] (generic) / bf16 (mfma)
   size_t off_m;         // split maxima (log2 domain)       fp32 [B, n_splits, n_h_pad]
@@ -30,6 +32,7 @@ struct DecodePlan {
 
 struct DecodeArgs {
   elitekv_dims dims;
+  int32_t d_ck;         // separated latents: a cache row is [c^k (d_ck) | c^v (d_c - d_ck)]; 0 = joint latent
   const void* q;
   const int32_t* q_pos;
   const int32_t* seq_len;
@@ -47,6 +50,8 @@ struct DecodeArgs {
 
 struct AppendArgs {
   elitekv_dims dims;
+  int32_t d_ck;         // columns of W_dkv; the remaining d_c - d_ck latent columns come from W_dkv2
+  const void* W_dkv2;   // separated latents: A^v [d, d_c - d_ck]; unused when d_ck == d_c
   const void* x;
   const int32_t* pos;
   const int64_t* slot;
@@ -75,21 +80,21 @@ struct MhaArgs {
 };
 
 hipError_t launch_append_generic(const AppendArgs& a, hipStream_t stream);
-bool append_small_supported(const elitekv_dims& d, int64_t T);
+bool append_small_supported(const elitekv_dims& d, int64_t T, int d_ck);
 size_t append_small_workspace(const elitekv_dims& d, int64_t T);
 hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_append_finish(const AppendArgs& a, const float* partial, int ksplit, hipStream_t stream);
-bool append_skinny_supported(const elitekv_dims& d, int64_t T);
+bool append_skinny_supported(const elitekv_dims& d, int64_t T, int d_ck);
 size_t append_skinny_workspace(const elitekv_dims& d, int64_t T);
 hipError_t launch_append_skinny(const AppendArgs& a, hipStream_t stream);
-bool append_gemm_supported(const elitekv_dims& d, int64_t T);
+bool append_gemm_supported(const elitekv_dims& d, int64_t T, int d_ck);
 hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_generic(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
-bool decode_mfma_supported(const elitekv_dims& d);
+bool decode_mfma_supported(const elitekv_dims& d, int d_ck);
 struct bf16_t;
-hipError_t launch_qprep_rows(const DecodeArgs& a, float* qe, bf16_t* qt,
+hipError_t launch_qprep_rows(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt,
                              hipStream_t stream);
-bool merge_batch_supported(const elitekv_dims& d, int64_t B, int64_t n_splits);
+bool merge_batch_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits);
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);
