@@ -95,7 +95,14 @@ def main():
     rng = synth.rng_for(cfg.index)
     idx_h = synth.draw_elite_idx(rng, n_h, d_h, r)
     assert ekv.elitekv_validate_elite_idx(dims, idx_h) == 0
-    W_ke, W_dkv, W_uk, W_uv = synth.draw_weights(rng, d, n_h, d_h, r, d_c)
+    d_ck = cfg.d_ck                                   # > 0: separated latents, a cache row is [c^k | c^v]
+    if d_ck:
+        W_ke, W_dkv, W_uk, _ = synth.draw_weights(rng, d, n_h, d_h, r, d_ck)          # A^k, B^k_S
+        _, W_dkv2, _, W_uv = synth.draw_weights(rng, d, n_h, d_h, r, d_c - d_ck)      # A^v, B^v_S
+        W_dkv2_d = torch.from_numpy(np.ascontiguousarray(W_dkv2)).to(dt).to(dev)
+    else:
+        W_ke, W_dkv, W_uk, W_uv = synth.draw_weights(rng, d, n_h, d_h, r, d_c)
+        W_dkv2_d = None
     q_h = synth.draw_query(rng, B, n_h, d_h)
     x_h = synth.draw_hidden(rng, B, d)
     to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(dev)
@@ -116,17 +123,27 @@ def main():
     slot_d = (torch.arange(B, dtype=torch.int64, device=dev) * S + (S - 1))
     seq_d = torch.full((B,), S, dtype=torch.int32, device=dev)
     out_d = torch.empty(B, n_h, d_h, dtype=dt, device=dev)
-    ws_d = torch.empty(max(ekv.elitekv_decode_workspace_bytes(dims, B, S, args.splits), 16), dtype=torch.uint8,
-                       device=dev)
-    aws_d = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, B), 16), dtype=torch.uint8, device=dev)
+    if d_ck:
+        nws, naws = (ekv.elitekv_slrd_decode_workspace_bytes(dims, d_ck, B, S, args.splits),
+                     ekv.elitekv_slrd_append_workspace_bytes(dims, d_ck, B))
+    else:
+        nws, naws = ekv.elitekv_decode_workspace_bytes(dims, B, S, args.splits), ekv.elitekv_append_workspace_bytes(dims, B)
+    ws_d = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
+    aws_d = torch.empty(max(naws, 16), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     ev = HipEvents()
 
     def step(i):
         ke_p, c_p = planes[i % n_copies]
-        ekv.elitekv_append(dims, x_d, pos_d, slot_d, W_ke_d, W_dkv_d, idx_d, ke_p, c_p, ws=aws_d, stream=stream)
-        ekv.elitekv_decode_attn(dims, q_d, pos_d, seq_d, S, S, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out_d, ws_d,
-                                n_splits=args.splits, stream=stream)
+        if d_ck:
+            ekv.elitekv_slrd_append(dims, d_ck, x_d, pos_d, slot_d, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, ke_p, c_p,
+                                    ws=aws_d, stream=stream)
+            ekv.elitekv_slrd_decode_attn(dims, d_ck, q_d, pos_d, seq_d, S, S, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out_d,
+                                         ws_d, n_splits=args.splits, stream=stream)
+        else:
+            ekv.elitekv_append(dims, x_d, pos_d, slot_d, W_ke_d, W_dkv_d, idx_d, ke_p, c_p, ws=aws_d, stream=stream)
+            ekv.elitekv_decode_attn(dims, q_d, pos_d, seq_d, S, S, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out_d, ws_d,
+                                    n_splits=args.splits, stream=stream)
 
     for i in range(args.warmup):
         step(i)
@@ -146,7 +163,7 @@ def main():
     def attn_only(i):
         ke_p, c_p = planes[i % n_copies]
         ekv.elitekv_decode_attn_stages(dims, q_d, pos_d, seq_d, S, S, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out_d, ws_d,
-                                       2, n_splits=args.splits, stream=stream)
+                                       2, n_splits=args.splits, stream=stream, d_ck=d_ck)
     for i in range(args.warmup):
         attn_only(i)
     torch.cuda.synchronize()
@@ -173,7 +190,9 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "context": S, "d_model": d, "n_heads": n_h, "head_dim": d_h,
                    "r": r, "d_c": d_c, "cache_fraction": (2 * r * n_h + d_c) / (2 * n_h * d_h),
-                   "step": "elitekv_append(T=batch) + elitekv_decode_attn", "plane_copies": n_copies,
+                   "variant": "S-LRD (d_ck %d, d_cv %d)" % (d_ck, d_c - d_ck) if d_ck else "J-LRD",
+                   "step": ("elitekv_slrd_append(T=batch) + elitekv_slrd_decode_attn" if d_ck
+                            else "elitekv_append(T=batch) + elitekv_decode_attn"), "plane_copies": n_copies,
                    "n_splits": ekv.elitekv_decode_auto_splits(dims, B, S) if args.splits == 0 else args.splits},
         "pct_of_hbm_peak": round(100.0 * value_gbs / HBM_PEAK_GBS, 2),
         "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
@@ -188,9 +207,9 @@ def main():
     if not args.no_comparators:
         result["comparators"] = comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream,
                                             cache_bytes, args)
-        result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, idx_d, dev, dt, stream)
+        result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0,
+        result["cpu_baseline"] = cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_dkv2_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0,
                                               cache_bytes)
     print(json.dumps(result))
 
@@ -255,7 +274,7 @@ def comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream, 
     return out
 
 
-def append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, idx_d, dev, dt, stream, T=2048, iters=20):
+def append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream, T=2048, iters=20):
     """The prefill-sized append of the same shape (a dense contraction on the matrix cores):
     T tokens through x [W_ke | W_dkv] + selective RoPE into fresh cache rows."""
     import torch
@@ -267,13 +286,20 @@ def append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, idx_d, dev, dt, stream, 
     slot = torch.arange(T, dtype=torch.int64, device=dev)
     ke = torch.zeros(T, n_h, 2 * r, dtype=dt, device=dev)
     c = torch.zeros(T, d_c, dtype=dt, device=dev)
-    ws = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, T), 16), dtype=torch.uint8, device=dev)
+    ws = torch.empty(16, dtype=torch.uint8, device=dev)      # appends of more than 64 tokens need no workspace
+
+    def call():
+        if cfg.d_ck:
+            ekv.elitekv_slrd_append(dims, cfg.d_ck, x, pos, slot, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, ke, c, ws=ws,
+                                    stream=stream)
+        else:
+            ekv.elitekv_append(dims, x, pos, slot, W_ke_d, W_dkv_d, idx_d, ke, c, ws=ws, stream=stream)
     for _ in range(3):
-        ekv.elitekv_append(dims, x, pos, slot, W_ke_d, W_dkv_d, idx_d, ke, c, ws=ws, stream=stream)
+        call()
     e0, e1 = ev.create(), ev.create()
     ev.record(e0, stream)
     for _ in range(iters):
-        ekv.elitekv_append(dims, x, pos, slot, W_ke_d, W_dkv_d, idx_d, ke, c, ws=ws, stream=stream)
+        call()
     ev.record(e1, stream)
     torch.cuda.synchronize()
     ms = ev.elapsed_ms(e0, e1) / iters
@@ -283,7 +309,7 @@ def append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, idx_d, dev, dt, stream, 
             "frac": round(tf / 2500.0, 4), "tokens_per_s": round(T / (ms * 1e-3), 1)}
 
 
-def cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0, cache_bytes):
+def cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_dkv2_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0, cache_bytes):
     """The float64 oracle, as it stands, on the host's cores, over a bounded sample of the same
     workload: the append of the batch's tokens plus decode attention for a subset of heads of
     batch row 0, scaled linearly to all heads and rows."""
@@ -296,7 +322,11 @@ def cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d, host_pla
     ke0 = host_planes0[0][:S].to(torch.float64).numpy()
     c0 = host_planes0[1][:S].to(torch.float64).numpy()
     t0 = time.perf_counter()
-    orc.append(to64(x_d), np.full(B, S - 1), to64(W_ke_d), to64(W_dkv_d), idx_h, d_h, cfg.rope_base)
+    if cfg.d_ck:
+        orc.slrd_append(to64(x_d), np.full(B, S - 1), to64(W_ke_d), to64(W_dkv_d), to64(W_dkv2_d), idx_h, d_h,
+                        cfg.rope_base)
+    else:
+        orc.append(to64(x_d), np.full(B, S - 1), to64(W_ke_d), to64(W_dkv_d), idx_h, d_h, cfg.rope_base)
     t_app = time.perf_counter() - t0
     # decode: groups of 8 heads of batch row 0 (every batch row has the same shape and length),
     # one group after the other, round and round, until about 12 s of CPU time are spent
@@ -305,7 +335,11 @@ def cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, q_d, x_d, host_pla
     while spent < budget:
         heads = groups[gi % len(groups)]
         t0 = time.perf_counter()
-        orc.decode_attn(q[:1], [S - 1], [ke0], [c0], [S], Wuk, Wuv, idx_h, d_h, cfg.rope_base, heads=heads)
+        if cfg.d_ck:
+            orc.slrd_decode_attn(q[:1], [S - 1], [ke0], [c0[:, :cfg.d_ck]], [c0[:, cfg.d_ck:]], [S], Wuk, Wuv, idx_h,
+                                 d_h, cfg.rope_base, heads=heads)
+        else:
+            orc.decode_attn(q[:1], [S - 1], [ke0], [c0], [S], Wuk, Wuv, idx_h, d_h, cfg.rope_base, heads=heads)
         spent += time.perf_counter() - t0
         done_heads += len(heads)
         gi += 1

@@ -47,6 +47,7 @@ class Config:
     dtype: str          # "fp32" or "bf16"
     rope_base: float = 10000.0
     prefill: int = 0    # tokens of one prefill-append call (config 4)
+    d_ck: int = 0       # separated latents (S-LRD): d_c = d_ck + d_cv, the first d_ck columns are c^k; 0 = joint
 
     def as_dict(self):
         return asdict(self)
@@ -60,6 +61,10 @@ CONFIGS = {
     "13b_25_b16_s8192": Config("13b_25_b16_s8192", 3, 5120, 40, 128, 8, 1920, 16, 8192, "bf16"),
     "7b_12_b64_s2048": Config("7b_12_b64_s2048", 4, 4096, 32, 128, 4, 768, 64, 2048, "bf16",
                               prefill=2048),
+    # the separated low-rank variant at the same cache size as configs 2 and 1 (the paper prints no
+    # (d_ck, d_cv); these give the value side the larger share / an even split)
+    "7b_25_slrd_b1_s32768": Config("7b_25_slrd_b1_s32768", 5, 4096, 32, 128, 8, 1536, 1, 32768, "bf16", d_ck=576),
+    "7b_25_slrd_b8_s4096": Config("7b_25_slrd_b8_s4096", 6, 4096, 32, 128, 8, 1536, 8, 4096, "bf16", d_ck=768),
 }
 
 

@@ -205,13 +205,15 @@ int elitekv_slrd_decode_attn(const elitekv_dims* dims, int32_t d_ck, const void*
  * arguments left in the workspace, so a full call must come first; the benchmark uses it to time
  * back-to-back launches of one stage with nothing else on the stream.  Same arguments and errors as
  * elitekv_decode_attn; EINVAL if stages is outside 1..7.  `out` is written only by stage bit 2.
+ * d_ck = 0: the joint latent (elitekv_decode_attn); d_ck > 0: separated latents with W_uk = B^k_S and
+ * W_uv = B^v_S (elitekv_slrd_decode_attn).
  */
 int elitekv_decode_attn_stages(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
                                const int32_t* seq_len, int64_t B, int64_t max_seq_len,
                                int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
                                const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
                                int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
-                               int32_t n_splits, void* hip_stream, int32_t stages);
+                               int32_t n_splits, void* hip_stream, int32_t stages, int32_t d_ck);
 
 /* Workspace bytes of elitekv_mha_decode.  n_splits == 0 means "auto". */
 size_t elitekv_mha_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,

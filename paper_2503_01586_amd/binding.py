@@ -57,7 +57,7 @@ def _load():
         "elitekv_slrd_decode_attn": (C.c_int, [DP, I32, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32,
                                                P]),
         "elitekv_decode_attn_stages": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32,
-                                                 P, I32]),
+                                                 P, I32, I32]),
         "elitekv_mha_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_mha_decode": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, I64, P, P, SZ, I32, P]),
         "elitekv_stream_read": (C.c_int, [P, SZ, P, P]),
@@ -204,15 +204,17 @@ def elitekv_slrd_decode_attn(dims, d_ck, q, q_pos, seq_len, max_seq_len, batch_s
 
 def elitekv_decode_attn_stages(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
                                ke_plane, c_plane, out, ws, stages, n_splits=0, stream=None, B=None,
-                               plane_rows=None):
-    """stages: bit 0 query preparation, bit 1 split attention, bit 2 merge + up-projection."""
+                               plane_rows=None, d_ck=0):
+    """stages: bit 0 query preparation, bit 1 split attention, bit 2 merge + up-projection.
+    d_ck = 0: joint latent; d_ck > 0: separated latents (W_uk = B_k, W_uv = B_v)."""
     B = q.shape[0] if B is None else B
     plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     st = _lib.elitekv_decode_attn_stages(C.byref(dims), _ptr(q), _ptr(q_pos), _ptr(seq_len), int(B),
                                          int(max_seq_len), int(batch_stride_rows), _ptr(W_uk), _ptr(W_uv),
                                          _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
-                                         _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream), int(stages))
+                                         _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream), int(stages),
+                                         int(d_ck))
     _check(st, "elitekv_decode_attn_stages")
 
 

@@ -230,17 +230,20 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
   const int64_t t0 = (int64_t)blockIdx.y * L::BN;
   const int nstages = (d + kGmStage - 1) / kGmStage;
 
+  // this thread always loads the same 8-column piece (tid % 16) of a weight row; each 64-column
+  // half of the block lies in one of the weight matrices
   const bf16_t* wbase;
   int64_t wstride;
-  weight_column(n0, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wbase, &wstride);   // a block lies in one matrix
+  weight_column(n0 + ((tid & 8) ? 64 : 0), NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wbase, &wstride);
+  wbase += (tid & 7) * 8;
 
   uint4 areg[4], breg[L::NB];
   auto load_stage = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {               // weights: 64 rows x 16 pieces
-      const int e = i * 256 + tid, k = k0 + (e >> 4), ch = e & 15;
+      const int e = i * 256 + tid, k = k0 + (e >> 4);
       areg[i] = make_uint4(0, 0, 0, 0);
-      if (k < d) areg[i] = *reinterpret_cast<const uint4*>(wbase + (int64_t)k * wstride + ch * 8);
+      if (k < d) areg[i] = *reinterpret_cast<const uint4*>(wbase + (int64_t)k * wstride);
     }
 #pragma unroll
     for (int i = 0; i < L::NB; ++i) {           // tokens: BN rows x 8 pieces
@@ -312,7 +315,6 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
 
   // epilogue: lane <-> token; registers 4*g4 .. 4*g4+3 of tile (i, j) are columns
   //   n0 + wm*64 + i*32 + 8*g4 + 4*hi + {0, 1, 2, 3}
-  const bool elite_block = n0 < NE;
 #pragma unroll
   for (int j = 0; j < WN; ++j) {
     const int64_t t = t0 + wn * 32 * WN + j * 32 + n32;
@@ -325,6 +327,7 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         const int n = n0 + wm * 64 + i * 32 + 8 * g4 + 4 * hi;
+        const bool elite_block = n < NE;                       // uniform over the wave's 64-column half
         float v0 = acc[i][j][4 * g4], v1 = acc[i][j][4 * g4 + 1], v2 = acc[i][j][4 * g4 + 2], v3 = acc[i][j][4 * g4 + 3];
         bf16_t* dst;
         if (elite_block) {
@@ -365,7 +368,8 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
 bool append_gemm_supported(const elitekv_dims& d, int64_t T, int d_ck) {
   if (d.dtype != ELITEKV_BF16 || T <= 64) return false;
   const int NE = 2 * d.r * d.n_heads;
-  return NE % kGmCols == 0 && d.d_c % kGmCols == 0 && d_ck % kGmCols == 0 && d.d_model % 8 == 0;
+  // 128-column blocks in all, each 64-column half inside one weight matrix
+  return (NE + d.d_c) % kGmCols == 0 && NE % 64 == 0 && d.d_c % 64 == 0 && d_ck % 64 == 0 && d.d_model % 8 == 0;
 }
 
 template <int WN>

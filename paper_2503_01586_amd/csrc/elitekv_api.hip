@@ -328,9 +328,9 @@ int elitekv_decode_attn_stages(const elitekv_dims* dims, const void* q, const in
                                int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
                                const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
                                int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
-                               int32_t n_splits, void* hip_stream, int32_t stages) {
+                               int32_t n_splits, void* hip_stream, int32_t stages, int32_t d_ck) {
   if (stages < 1 || stages > 7) return ELITEKV_EINVAL;
-  return decode_impl(dims, 0, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+  return decode_impl(dims, d_ck, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
                      ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, stages);
 }
 

@@ -41,6 +41,7 @@ APPEND_CASES = {
     "bf16_7b_300_tokens": (shape(4096, 32, 128, 8, 1536, "bf16"), 300, 32767),
     "bf16_13b_200_tokens": (shape(5120, 40, 128, 8, 1920, "bf16"), 200, 8191),
     "bf16_12pct_odd_hidden_130": (shape(1000, 32, 128, 4, 768, "bf16"), 130, 2047),
+    "bf16_half_block_boundary_200": (shape(1024, 24, 64, 4, 320, "bf16"), 200, 999),   # 2 r n_h = 192
 }
 
 

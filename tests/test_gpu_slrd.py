@@ -59,6 +59,7 @@ APPEND_CASES = {
     "bf16_7b_one_token": (shape(4096, 32, 128, 8, 576, 960, "bf16"), 1),
     "bf16_7b_batch_16": (shape(4096, 32, 128, 8, 576, 960, "bf16"), 16),
     "bf16_7b_300_tokens": (shape(4096, 32, 128, 8, 640, 896, "bf16"), 300),
+    "bf16_7b_300_tokens_576": (shape(4096, 32, 128, 8, 576, 960, "bf16"), 300),      # boundary inside a 128-column block
     "bf16_unaligned_split": (shape(512, 8, 64, 4, 72, 56, "bf16"), 40),       # falls to the generic kernel
 }
 
