@@ -214,6 +214,67 @@ struct GemmLayout {
   static constexpr int NB = BN * 8 / 256;                     // 16-byte token pieces per thread per stage
 };
 
+// Epilogue of the GEMM kernels: lane <-> token; registers 4*g4 .. 4*g4+3 of accumulator tile (i, j)
+// are the output columns n0 + wm*64 + i*32 + 8*g4 + 4*hi + {0, 1, 2, 3} of token
+// t0 + wn*32*WN + j*32 + n32.  Elite pairs are rotated in registers; bf16 rows go to the planes.
+template <int WN>
+__device__ __forceinline__ void gemm_epilogue(am_f32x16 (&acc)[2][WN], int n0, int64_t t0, int wm, int wn, int n32,
+                                              int hi, int64_t T, const int32_t* __restrict__ pos,
+                                              const int64_t* __restrict__ slot, const int32_t* __restrict__ elite_idx,
+                                              bf16_t* __restrict__ ke_plane, bf16_t* __restrict__ c_plane,
+                                              int64_t plane_rows, int n_h, int d_h, int r, int d_c,
+                                              const RopeTable& rope) {
+  const int NE = 2 * r * n_h;
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int64_t t = t0 + wn * 32 * WN + j * 32 + n32;
+    if (t >= T) continue;
+    const int64_t row = slot[t];
+    if (row < 0 || row >= plane_rows) continue;
+    const int32_t p = pos[t];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int n = n0 + wm * 64 + i * 32 + 8 * g4 + 4 * hi;
+        const bool elite_block = n < NE;                       // uniform over the wave's 64-column half
+        float v0 = acc[i][j][4 * g4], v1 = acc[i][j][4 * g4 + 1], v2 = acc[i][j][4 * g4 + 2], v3 = acc[i][j][4 * g4 + 3];
+        bf16_t* dst;
+        if (elite_block) {
+          // two (even, odd) pairs: slots (n % 2r)/2 and the next one of the same head (2r is even and
+          // n is a multiple of 4, so a group of four never straddles a head when 2r % 4 == 0; with
+          // 2r % 4 == 2 the second pair may belong to the next head: both are looked up separately)
+          float sn, cs;
+          {
+            const int hh = n / (2 * r), jj = (n % (2 * r)) >> 1;
+            int ch = elite_idx[hh * r + jj];
+            ch = min(max(ch, 0), d_h / 2 - 1);
+            rope_sincos(p, rope.theta[ch], &sn, &cs);
+            const float a0 = v0 * cs - v1 * sn, a1 = v0 * sn + v1 * cs;
+            v0 = a0; v1 = a1;
+          }
+          {
+            const int n2 = n + 2;
+            const int hh = n2 / (2 * r), jj = (n2 % (2 * r)) >> 1;
+            int ch = elite_idx[hh * r + jj];
+            ch = min(max(ch, 0), d_h / 2 - 1);
+            rope_sincos(p, rope.theta[ch], &sn, &cs);
+            const float a2 = v2 * cs - v3 * sn, a3 = v2 * sn + v3 * cs;
+            v2 = a2; v3 = a3;
+          }
+          dst = ke_plane + row * NE + n;
+        } else {
+          dst = c_plane + row * d_c + (n - NE);
+        }
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
+        pk.y = (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16);
+        *reinterpret_cast<uint2*>(dst) = pk;
+      }
+    }
+  }
+}
+
 template <int WN>
 __global__ __launch_bounds__(256) void append_gemm_kernel(
     const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
@@ -313,56 +374,166 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
     __syncthreads();
   }
 
-  // epilogue: lane <-> token; registers 4*g4 .. 4*g4+3 of tile (i, j) are columns
-  //   n0 + wm*64 + i*32 + 8*g4 + 4*hi + {0, 1, 2, 3}
+  gemm_epilogue<WN>(acc, n0, t0, wm, wn, n32, hi, T, pos, slot, elite_idx, ke_plane, c_plane, plane_rows, n_h, d_h,
+                    r, d_c, rope);
+}
+
+// ---------------------------------------------------------------------------------------------
+// append_gemm_dma: the same GEMM with both operands brought in by direct global->LDS loads into a
+// ring of NS stages of 32 contraction rows (no register staging, one barrier per stage, the loads
+// of the next NS-1 stages in flight while a stage is multiplied).  A direct load writes 1 KiB
+// (64 lanes x 16 bytes) contiguously, so the LDS layouts are made of 1 KiB blocks:
+//   weights  [32 k][128 n]: blocks of 8 rows x 128 bytes, 16-byte pieces XOR-swizzled by row
+//            (conflict-free transposed reads), block (kb, nb) at (kb*2 + nb) KiB;
+//   tokens   [BN t][32 k]:  blocks of 16 rows x 64 bytes, pieces XOR-swizzled by row.
+// Needs d_model % 32 == 0 (whole stages); other shapes take append_gemm_kernel.
+// ---------------------------------------------------------------------------------------------
+constexpr int kGdStage = 32;                    // contraction rows per stage
+constexpr int kGdA = 8 * 1024;                  // bytes of a weight stage
+
+__device__ __forceinline__ int gd_swz8(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+__device__ __forceinline__ int gd_swz4(int row) { return (((row >> 1) & 1) << 1) | ((row >> 2) & 1); }
+
+__device__ __forceinline__ void gd_dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+
+template <int WN, int NS>
+struct GemmDmaLayout {
+  static constexpr int BN = 64 * WN;
+  static constexpr int B_BYTES = BN * 64;                     // token stage
+  static constexpr int STAGE = kGdA + B_BYTES;
+  static constexpr int LDS_BYTES = NS * STAGE;
+  static constexpr int LOADS = STAGE / 1024;                  // direct loads per stage per work-group
+  static constexpr int LPW = LOADS / 4;                       // ... per wave
+  static_assert(LOADS % 4 == 0, "the loads of a stage are divided evenly among the four waves");
+  static_assert(LDS_BYTES <= 160 * 1024, "exceeds the LDS of a compute unit");
+};
+
+template <int WN, int NS>
+__global__ __launch_bounds__(256) void append_gemm_dma_kernel(
+    const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
+    const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const bf16_t* __restrict__ W_dkv2, int d_ck,
+    const int32_t* __restrict__ elite_idx, bf16_t* __restrict__ ke_plane, bf16_t* __restrict__ c_plane,
+    int64_t plane_rows, int d, int n_h, int d_h, int r, int d_c, RopeTable rope) {
+  using L = GemmDmaLayout<WN, NS>;
+  extern __shared__ __attribute__((aligned(16))) char gsm[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int n32 = lane & 31, hi = lane >> 5, i16 = lane & 15, q16 = lane >> 4;
+  const int NE = 2 * r * n_h;
+  // Work-groups go to the eight XCDs round-robin by linear index.  All column blocks of one token
+  // block are given to the SAME XCD, one after the other, so the token tile is fetched into that
+  // XCD's L2 once and re-used by every column block instead of being fetched by eight L2s.
+  const int col_blocks = (NE + d_c) / kGmCols;
+  const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  const int64_t tblock = (int64_t)(seq / col_blocks) * 8 + xcd;
+  const int n0 = (seq % col_blocks) * kGmCols;
+  const int64_t t0 = tblock * L::BN;
+  if (t0 >= T) return;
+  const int nstages = d / kGdStage;
+
+  // ---- loader.  Wave w issues loads w*LPW .. w*LPW+LPW-1 of a stage; load index < 8 is weight block
+  // (kb = idx/2, nb = idx%2), the others are token blocks of 16 rows.
+  const char* gsrc[L::LPW];      // this lane's global address for the next stage to be requested
+  int64_t gstep[L::LPW];         // bytes to advance per stage
 #pragma unroll
-  for (int j = 0; j < WN; ++j) {
-    const int64_t t = t0 + wn * 32 * WN + j * 32 + n32;
-    if (t >= T) continue;
-    const int64_t row = slot[t];
-    if (row < 0 || row >= plane_rows) continue;
-    const int32_t p = pos[t];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int n = n0 + wm * 64 + i * 32 + 8 * g4 + 4 * hi;
-        const bool elite_block = n < NE;                       // uniform over the wave's 64-column half
-        float v0 = acc[i][j][4 * g4], v1 = acc[i][j][4 * g4 + 1], v2 = acc[i][j][4 * g4 + 2], v3 = acc[i][j][4 * g4 + 3];
-        bf16_t* dst;
-        if (elite_block) {
-          // two (even, odd) pairs: slots (n % 2r)/2 and the next one of the same head (2r is even and
-          // n is a multiple of 4, so a group of four never straddles a head when 2r % 4 == 0; with
-          // 2r % 4 == 2 the second pair may belong to the next head: both are looked up separately)
-          float sn, cs;
-          {
-            const int hh = n / (2 * r), jj = (n % (2 * r)) >> 1;
-            int ch = elite_idx[hh * r + jj];
-            ch = min(max(ch, 0), d_h / 2 - 1);
-            rope_sincos(p, rope.theta[ch], &sn, &cs);
-            const float a0 = v0 * cs - v1 * sn, a1 = v0 * sn + v1 * cs;
-            v0 = a0; v1 = a1;
-          }
-          {
-            const int n2 = n + 2;
-            const int hh = n2 / (2 * r), jj = (n2 % (2 * r)) >> 1;
-            int ch = elite_idx[hh * r + jj];
-            ch = min(max(ch, 0), d_h / 2 - 1);
-            rope_sincos(p, rope.theta[ch], &sn, &cs);
-            const float a2 = v2 * cs - v3 * sn, a3 = v2 * sn + v3 * cs;
-            v2 = a2; v3 = a3;
-          }
-          dst = ke_plane + row * NE + n;
-        } else {
-          dst = c_plane + row * d_c + (n - NE);
-        }
-        uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16_bits(v0) | ((uint32_t)f32_to_bf16_bits(v1) << 16);
-        pk.y = (uint32_t)f32_to_bf16_bits(v2) | ((uint32_t)f32_to_bf16_bits(v3) << 16);
-        *reinterpret_cast<uint2*>(dst) = pk;
-      }
+  for (int u = 0; u < L::LPW; ++u) {
+    const int idx = wave * L::LPW + u;
+    if (idx < 8) {
+      const int kb = idx >> 1, nb = idx & 1, row = lane >> 3, pc = (lane & 7) ^ gd_swz8(row);
+      const bf16_t* wb;
+      int64_t ws;
+      weight_column(n0 + nb * 64, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wb, &ws);
+      gsrc[u] = reinterpret_cast<const char*>(wb + (int64_t)(kb * 8 + row) * ws + pc * 8);
+      gstep[u] = (int64_t)kGdStage * ws * 2;
+    } else {
+      const int tb = idx - 8, row = lane >> 2, pc = (lane & 3) ^ gd_swz4(row);
+      const int64_t t = min(t0 + tb * 16 + row, T - 1);        // rows past the end repeat the last token
+      gsrc[u] = reinterpret_cast<const char*>(x + t * d + pc * 8);
+      gstep[u] = (int64_t)kGdStage * 2;
     }
   }
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)gsm);
+  int issue_slot = 0;            // ring slot of the next stage to be requested; stages are requested in order
+  auto issue = [&]() {
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds0 + issue_slot * L::STAGE + wave * L::LPW * 1024);
+#pragma unroll
+    for (int u = 0; u < L::LPW; ++u) {
+      gd_dma16(gsrc[u], base + u * 1024);
+      gsrc[u] += gstep[u];
+    }
+    issue_slot = (issue_slot + 1 == NS) ? 0 : issue_slot + 1;
+  };
+
+  am_f32x16 acc[2][WN];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j) acc[i][j] = (am_f32x16)(0.f);
+
+  // ---- operand read offsets inside a stage
+  // weights, transposed read: k rows 8*(q16/2) + 4e + i16/4 of a k-step (block kb = 2*ks + q16/2 ...)
+  int a_off[2][2];               // [i: 32-column tile of the wave's 64-column half][e: rows 0-3 | 4-7]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const int r8 = 4 * e + (i16 >> 2);
+      const int piece = (i << 2) | ((q16 & 1) << 1) | ((i16 & 3) >> 1);       // 16-byte piece inside the 128-byte row
+      a_off[i][e] = ((q16 >> 1) * 2 + wm) * 1024 + r8 * 128 + ((piece ^ gd_swz8(r8)) << 4) + ((i16 & 1) << 3);
+    }
+  // tokens: row n32 of tile j (block 2*(wn*WN + j) + n32/16), piece 2*ks + hi
+  int b_off[2];                  // [ks]
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int row = n32 & 15;
+    b_off[ks] = kGdA + (wn * WN * 2 + (n32 >> 4)) * 1024 + row * 64 + (((2 * ks + hi) ^ gd_swz4(row)) << 4);
+  }
+
+  int use_slot = 0;              // ring slot of the stage being multiplied
+  auto compute = [&]() {
+    const char* st = gsm + use_slot * L::STAGE;
+    use_slot = (use_slot + 1 == NS) ? 0 : use_slot + 1;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      am_bf16x8 a[2], b[WN];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const am_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 4096 + a_off[i][0]));
+        const am_s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 4096 + a_off[i][1]));
+        a[i] = __builtin_bit_cast(am_bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
+#pragma unroll
+      for (int j = 0; j < WN; ++j) b[j] = *reinterpret_cast<const am_bf16x8*>(st + b_off[ks] + j * 2048);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  // ---- ring pipeline: stages s+1 .. s+NS-2 stay in flight while stage s is consumed
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nstages) issue();
+  for (int s = 0; s < nstages; ++s) {
+    const int ahead = min(nstages - 1 - s, NS - 2);             // stages after s that have been issued
+    // wait until this wave's loads of stage s have landed (the loads of `ahead` later stages may remain)
+    switch (ahead) {
+      case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+      case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(1 * L::LPW) : "memory"); break;
+      case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * L::LPW) : "memory"); break;
+      case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * L::LPW) : "memory"); break;
+      default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * L::LPW) : "memory"); break;
+    }
+    __syncthreads();           // every wave's part of stage s is in LDS; everyone is done with stage s-1
+    if (s + NS - 1 < nstages) issue();                          // into the buffer stage s-1 occupied
+    compute();
+  }
+
+  gemm_epilogue<WN>(acc, n0, t0, wm, wn, n32, hi, T, pos, slot, elite_idx, ke_plane, c_plane, plane_rows, n_h, d_h,
+                    r, d_c, rope);
 }
 
 bool append_gemm_supported(const elitekv_dims& d, int64_t T, int d_ck) {
@@ -392,10 +563,36 @@ static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+template <int WN, int NS>
+static hipError_t launch_gemm_dma(const AppendArgs& a, hipStream_t stream) {
+  using L = GemmDmaLayout<WN, NS>;
+  const elitekv_dims& d = a.dims;
+  const int N = 2 * d.r * d.n_heads + d.d_c;
+  static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
+  if (!attr_done && L::LDS_BYTES > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int64_t tblocks = (a.T + L::BN - 1) / L::BN;
+  const dim3 grid((unsigned)((tblocks + 7) / 8 * 8 * (N / kGmCols)));   // token blocks padded to whole rounds of 8 XCDs
+  append_gemm_dma_kernel<WN, NS><<<grid, 256, L::LDS_BYTES, stream>>>(
+      (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
+      (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
+      d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
+  return hipGetLastError();
+}
+
 hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
   const int64_t col_blocks = (2 * d.r * d.n_heads + d.d_c) / kGmCols;
-  // wide token tiles once they still give every compute unit a few work-groups
+  // the widest token tile that still gives every compute unit work
+  if (d.d_model % kGdStage == 0) {
+    if (col_blocks * ((a.T + 255) / 256) >= 512) return launch_gemm_dma<4, 6>(a, stream);
+    if (col_blocks * ((a.T + 127) / 128) >= 256) return launch_gemm_dma<2, 4>(a, stream);
+    return launch_gemm_dma<1, 6>(a, stream);
+  }
   if (col_blocks * ((a.T + 255) / 256) >= 1024) return launch_gemm_wn<4>(a, stream);
   return launch_gemm_wn<1>(a, stream);
 }

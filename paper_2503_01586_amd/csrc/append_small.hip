@@ -126,8 +126,16 @@ __global__ __launch_bounds__(256) void append_finish_kernel(
   const int n = blockIdx.y * 256 + threadIdx.x;
   const bool col_ok = n < N;
   float mine = 0.f;
-  if (col_ok)
-    for (int s = 0; s < ksplit; ++s) mine += partial[((int64_t)s * T + t) * N + n];
+  if (col_ok) {
+    // eight independent loads in flight per round; the sum keeps the split order
+    for (int s0 = 0; s0 < ksplit; s0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = (s0 + u < ksplit) ? partial[((int64_t)(s0 + u) * T + t) * N + n] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) mine += v[u];
+    }
+  }
   const float other = __shfl_xor(mine, 1, kWave);
   if (!col_ok) return;
   const int64_t row = slot[t];
