@@ -240,6 +240,25 @@ def slrd_decode_attn(q, q_pos, ke, c_k, c_v, seq_len, B_k, B_v, elite_idx, head_
     return out
 
 
+# ----------------------------------------------------------------------------------------------
+# Several queries per sequence (a prefill chunk, or the verification of drafted tokens): every
+# query is one more instance of the decode attention above, over the rows of its own sequence that
+# it may see.  Section 2.1 builds K_t, V_t from the tokens up to t: a query at step t attends to the
+# cache rows of steps <= t, which the caller states as a visible-row count per query.
+# ----------------------------------------------------------------------------------------------
+def multiquery_attn(q, q_pos, ke, c, kv_len, W_uk, W_uv, elite_idx, head_dim: int, rope_base: float):
+    """q [B, T, n_h, d_h]; q_pos [B, T]; ke[b], c[b]: the planes of sequence b; kv_len [B, T] rows of
+    sequence b visible to query (b, t) (causal decoding: position + 1).  Returns o [B, T, n_h, d_h]."""
+    q = np.asarray(q, dtype=F64)
+    B, T = q.shape[:2]
+    out = np.zeros_like(q)
+    for b in range(B):
+        for t in range(T):
+            out[b, t] = decode_attn(q[b, t][None], [int(q_pos[b][t])], [ke[b]], [c[b]], [int(kv_len[b][t])],
+                                    W_uk, W_uv, elite_idx, head_dim, rope_base)[0]
+    return out
+
+
 def mha_decode(q, q_pos, K_rot, V, seq_len, rope_base: float):
     """Comparator: ordinary RoPE multi-head decode attention (Sections 2.1 and 2.2).
 

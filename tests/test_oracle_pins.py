@@ -409,6 +409,40 @@ def test_mha_decode_matches_complex_reference():
 # ----------------------------------------------------------------------------------------------
 # the pins bite: plant one mistake at a time in the oracle and require some pin to fail
 # ----------------------------------------------------------------------------------------------
+# ----------------------------------------------------------------------------------------------
+# Several queries per sequence: against causal attention written as one masked score matrix over
+# un-rotated full keys (relative form of Section 2.2 eq. 1b; Section 2.1 for the softmax)
+# ----------------------------------------------------------------------------------------------
+def test_multiquery_equals_masked_causal_attention():
+    d, n_h, d_h, r, S, T, base = 20, 2, 8, 2, 9, 4, 1000.0
+    rng, Wk, Wv, idx, x, _, _, _ = _full_model(71, d, n_h, d_h, r, S)
+    W_ke, A, W_uk, W_uv = exact_elitekv_weights(rng, Wk, Wv, idx)
+    pos = np.arange(S)
+    ke, c = orc.append(x, pos, W_ke, A, idx, d_h, base)
+    q = rng.standard_normal((1, T, n_h, d_h))
+    q_pos = np.arange(S - T, S)[None]                     # the last T tokens of the sequence are the queries
+    got = orc.multiquery_attn(q, q_pos, [ke], [c], q_pos + 1, W_uk, W_uv, idx, d_h, base)[0]
+    # reference: one [T, S] score matrix per head from full keys, relative rotations, causal mask
+    k_raw = np.einsum("sd,dhe->she", x, Wk)
+    v = np.einsum("sd,dhe->she", x, Wv)
+    th = _theta_plain(d_h, base)
+    for h in range(n_h):
+        elite = set(int(i) for i in idx[h])
+        s = np.full((T, S), -np.inf)
+        for t in range(T):
+            for j in range(S):
+                if j > q_pos[0, t]:
+                    continue                               # the mask: no later token is visible
+                acc = 0.0
+                for i in range(d_h // 2):
+                    qi, ki = q[0, t, h, 2 * i:2 * i + 2], k_raw[j, h, 2 * i:2 * i + 2]
+                    acc += float(qi @ _rot_matrix((int(q_pos[0, t]) - j) * th[i]) @ ki) if i in elite else float(qi @ ki)
+                s[t, j] = acc / math.sqrt(d_h)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        assert np.max(np.abs(got[:, h, :] - p @ v[:, h, :])) < TOL
+
+
 def _pins():
     return [lambda: test_p1_full_rope_equals_standard_attention(1),
             lambda: test_p2_matches_ropelite_equation_relative_form(2),
