@@ -150,6 +150,25 @@ int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* 
                         void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Several queries per sequence (a prefill chunk, the verification of drafted tokens): T query
+ * tokens of each of B sequences attend over the cache rows of their own sequence.  Section 2.1
+ * builds K_t, V_t from the tokens up to step t, so query (b, t) sees a prefix of sequence b's rows;
+ * the caller states its length in kv_len (causal decoding: the query's position + 1, after the
+ * chunk's own tokens have been appended).  Each query is computed exactly as by elitekv_decode_attn.
+ *   q      [B, T, n_h, d_h]   q_pos [B * T]   kv_len [B * T]   out [B, T, n_h, d_h]
+ * Sequence b owns plane rows [b * batch_stride_rows, ...); max_seq_len bounds every kv_len.
+ * Other arguments, workspace rules and errors as elitekv_decode_attn; EINVAL if T < 1,
+ * EUNSUPPORTED if B * T > 65535.
+ * ------------------------------------------------------------------------------------------- */
+size_t elitekv_multiquery_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t T, int64_t max_seq_len,
+                                          int32_t n_splits);
+int elitekv_multiquery_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos, const int32_t* kv_len,
+                            int64_t B, int64_t T, int64_t max_seq_len, int64_t batch_stride_rows,
+                            const void* W_uk, const void* W_uv, const int32_t* elite_idx, const void* ke_plane,
+                            const void* c_plane, int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
+                            int32_t n_splits, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Separated low-rank decomposition (Section 3.2, "Separated Low-Rank Decomposition"):
  *     W^k_{e^,0:n_h-1} ~ A^k B^k_S,   W^v_{0:n_h-1} ~ A^v B^v_S,
  * a token caches two latents, c^k = x A^k (d_ck columns) and c^v = x A^v (d_cv columns), next to its

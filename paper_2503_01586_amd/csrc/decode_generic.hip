@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
     const T* __restrict__ ke_plane, const T* __restrict__ c_plane, const float* __restrict__ qe,
     const float* __restrict__ qt, const int32_t* __restrict__ seq_len, float* __restrict__ part_m,
     float* __restrict__ part_l, float* __restrict__ part_u, int n_h, int two_r, int d_c, int d_q, int d_u,
-    int64_t max_seq_len, int64_t batch_stride_rows, int64_t plane_rows, int n_splits, int chunk) {
+    int64_t max_seq_len, int64_t batch_stride_rows, int64_t plane_rows, int n_splits, int chunk, int q_per_seq) {
   extern __shared__ float smem[];
   // a cache row holds d_c latent columns: the first d_q of them enter the scores, the last d_u are
   // accumulated as values (joint latent: d_q = d_u = d_c, the same columns serve both)
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_kernel(
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  const int64_t row0 = (int64_t)b * batch_stride_rows;
+  const int64_t row0 = (int64_t)(b / q_per_seq) * batch_stride_rows;
   int64_t len = seq_len[b];
   len = min(len, max_seq_len);
   len = min(len, plane_rows - row0);
@@ -238,7 +238,7 @@ static hipError_t launch_decode_generic_t(const DecodeArgs& a, const DecodePlan&
 #define EKV_ATTN(C)                                                                               \
   attn_generic_kernel<T, C><<<grid, kGenThreads, sm, stream>>>(                                   \
       (const T*)a.ke_plane, (const T*)a.c_plane, qe, qt, a.seq_len, pm, pl, pu, n_h, 2 * r, d_c, d_q, d_u, \
-      a.max_seq_len, a.batch_stride_rows, a.plane_rows, p.n_splits, p.chunk)
+      a.max_seq_len, a.batch_stride_rows, a.plane_rows, p.n_splits, p.chunk, a.q_per_seq)
   if (!(a.stages & 2)) {}
   else if (cpt <= 1) EKV_ATTN(1);
   else if (cpt <= 2) EKV_ATTN(2);

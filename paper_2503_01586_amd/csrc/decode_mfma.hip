@@ -43,6 +43,7 @@ struct AttnMfmaParams {
   bf16_t* part_u;         // [B, n_splits, HG*32, d_c]   split latent accumulators, head-major
   int n_h, d_c, n_splits, chunk, head_groups;
   int batch, pair_map;    // pair_map: 1-D grid, the two head groups of an item share an XCD
+  int q_per_seq;          // query rows per sequence (several queries share the cache rows of a sequence)
   int d_q, d_u;           // widths of the absorbed query and of the latent accumulators (d_c when joint)
   int64_t max_seq_len, batch_stride_rows, plane_rows;
 };
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
   float* x1 = reinterpret_cast<float*>(smem + L::X1_OFF);
   float* x2 = reinterpret_cast<float*>(smem + L::X2_OFF);
 
-  const int64_t row0 = (int64_t)b * p.batch_stride_rows;
+  const int64_t row0 = (int64_t)(b / p.q_per_seq) * p.batch_stride_rows;
   int64_t len = p.seq_len[b];
   len = min(len, p.max_seq_len);
   len = min(len, p.plane_rows - row0);
@@ -531,7 +532,7 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.head_groups = p.head_groups; prm.max_seq_len = a.max_seq_len;
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
   prm.batch = (int)a.B; prm.pair_map = p.head_groups == 2 ? 1 : 0;
-  prm.d_q = p.d_q; prm.d_u = p.d_u;
+  prm.d_q = p.d_q; prm.d_u = p.d_u; prm.q_per_seq = a.q_per_seq;
 
   hipError_t e = hipSuccess;
   if (a.stages & 1) e = launch_qprep_rows(a, p, qe, qt, stream);

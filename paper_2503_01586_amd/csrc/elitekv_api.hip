@@ -242,7 +242,7 @@ static int decode_impl(const elitekv_dims* dims, int32_t d_ck, const void* q, co
                        int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
                        const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
                        int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
-                       void* hip_stream, int32_t stages) {
+                       void* hip_stream, int32_t stages, int32_t q_per_seq = 1) {
   DecodePlan p;
   int st = plan_decode(dims, d_ck, B, max_seq_len, n_splits, &p);
   if (st) return st;
@@ -261,10 +261,30 @@ static int decode_impl(const elitekv_dims* dims, int32_t d_ck, const void* q, co
   a.dims = *dims; a.d_ck = d_ck; a.q = q; a.q_pos = q_pos; a.seq_len = seq_len; a.B = B;
   a.max_seq_len = max_seq_len; a.batch_stride_rows = batch_stride_rows; a.W_uk = W_uk; a.W_uv = W_uv;
   a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows; a.out = out;
-  a.ws = (char*)ws; a.stages = stages;
+  a.ws = (char*)ws; a.stages = stages; a.q_per_seq = q_per_seq;
   const hipError_t e = p.mfma ? launch_decode_mfma(a, p, (hipStream_t)hip_stream)
                              : launch_decode_generic(a, p, (hipStream_t)hip_stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+/* ---- several queries per sequence ---- */
+
+size_t elitekv_multiquery_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t T, int64_t max_seq_len,
+                                          int32_t n_splits) {
+  DecodePlan p;
+  if (B < 0 || T < 1 || B * T > 65535 || plan_decode(dims, 0, B * T, max_seq_len, n_splits, &p)) return 0;
+  return p.total;
+}
+
+int elitekv_multiquery_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos, const int32_t* kv_len,
+                            int64_t B, int64_t T, int64_t max_seq_len, int64_t batch_stride_rows,
+                            const void* W_uk, const void* W_uv, const int32_t* elite_idx, const void* ke_plane,
+                            const void* c_plane, int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
+                            int32_t n_splits, void* hip_stream) {
+  if (B < 0 || T < 1) return dims ? ELITEKV_EINVAL : ELITEKV_ENULL;
+  if (B * T > 65535) return ELITEKV_EUNSUPPORTED;
+  return decode_impl(dims, 0, q, q_pos, kv_len, B * T, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, 7, (int32_t)T);
 }
 
 /* ---- separated low-rank decomposition (two latents per token, stored side by side) ---- */

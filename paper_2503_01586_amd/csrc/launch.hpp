@@ -45,6 +45,7 @@ struct DecodeArgs {
   int64_t plane_rows;
   void* out;
   char* ws;
+  int32_t q_per_seq;                // queries per sequence: row b of q belongs to sequence b / q_per_seq
   int32_t stages;                   // bit 0 q-prep, bit 1 split attention, bit 2 merge + up-projection
 };
 
