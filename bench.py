@@ -207,6 +207,9 @@ def main():
     if not args.no_comparators:
         result["comparators"] = comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream,
                                             cache_bytes, args)
+        if not d_ck:
+            result["multiquery"] = multiquery(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
+                                              cache_bytes)
         result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_dkv2_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0,
@@ -272,6 +275,39 @@ def comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream, 
     out["mha_uncompressed_GBs"] = round(full_bytes / (ms * 1e-3) / 1e9, 1)
     out["mha_cache_bytes"] = full_bytes
     return out
+
+
+def multiquery(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream, cache_bytes, T=8, iters=20):
+    """A chunk of T queries per sequence (the last T positions, causal) over the same planes:
+    every query consumes the sequence's cache rows; the rows come from HBM once and are re-used
+    from the L2 of the XCD that the queries of a sequence share."""
+    import torch
+    B, S, n_h, d_h = cfg.batch, cfg.context, cfg.n_heads, cfg.head_dim
+    if B * T > 65535:
+        return None
+    g = torch.Generator(device=dev)
+    g.manual_seed(15861)
+    q = torch.randn(B, T, n_h, d_h, device=dev, dtype=torch.float32, generator=g).to(dt)
+    pos = (torch.arange(T, device=dev, dtype=torch.int32) + (S - T)).repeat(B)
+    kv = pos + 1
+    out = torch.empty(B, T, n_h, d_h, dtype=dt, device=dev)
+    ws = torch.empty(ekv.elitekv_multiquery_workspace_bytes(dims, B, T, S, 0), dtype=torch.uint8, device=dev)
+
+    def call(i):
+        ke_p, c_p = planes[i % len(planes)]
+        ekv.elitekv_multiquery_attn(dims, q, pos, kv, S, S, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out, ws, stream=stream)
+    for i in range(3):
+        call(i)
+    e0, e1 = ev.create(), ev.create()
+    ev.record(e0, stream)
+    for i in range(iters):
+        call(i)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms = ev.elapsed_ms(e0, e1) / iters
+    return {"queries_per_sequence": T, "ms_per_call": round(ms, 5), "us_per_query": round(ms * 1e3 / (B * T), 3),
+            "cache_bytes_consumed_GBs": round(cache_bytes * T / (ms * 1e-3) / 1e9, 1),
+            "query_tokens_per_s": round(B * T / (ms * 1e-3), 1)}
 
 
 def append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream, T=2048, iters=20):
