@@ -297,7 +297,7 @@ hipError_t launch_qprep_rows(const DecodeArgs& a, const DecodePlan& p, float* qe
 //   * exact log-sum-exp merge of the sequence splits for this head (weights from m, l),
 //   * the merged, normalised latent of the chunk's columns,
 //   * its contribution to the up-projection  o[h, :] = ubar[h, :] W_uv[:, h, :]   (B^v_J),
-//   * the last chunk of a head to finish adds the chunk partials in a fixed order and writes out.
+//   * written as a partial per chunk; out_reduce adds the chunk partials in a fixed order.
 // Partials: part_m / part_l [P, NHP], part_u [P, NHP, d_c] bf16 with P = b * n_splits + s.
 // All global loads that do not depend on earlier results (the W_uv rows, the first batch of
 // split accumulators) are requested at the top so that their latency overlaps the merge weights.
@@ -306,7 +306,7 @@ template <int CW, int DH>
 __global__ __launch_bounds__(256) void merge_up_kernel(
     const float* __restrict__ part_m, const float* __restrict__ part_l,
     const bf16_t* __restrict__ part_u, const bf16_t* __restrict__ W_uv, float* __restrict__ opart,
-    uint32_t* __restrict__ counters, bf16_t* __restrict__ out, int n_h, int nhp, int d_c, int n_splits) {
+    int n_h, int nhp, int d_c, int n_splits) {
   constexpr int LPR = CW / 8;              // lanes that cover one split's row chunk (16 bytes each)
   constexpr int NG = 256 / LPR;            // split groups working in parallel
   constexpr int LPW = DH / 8;              // lanes that cover one W_uv row
@@ -705,16 +705,14 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
   const float* pl = (const float*)(a.ws + p.off_l);
   const bf16_t* pu = (const bf16_t*)(a.ws + p.off_u);
   float* opart = (float*)(a.ws + p.off_opart);
-  uint32_t* cnt = (uint32_t*)(a.ws + p.off_cnt);
   const int cw = p.up_cw;
   const dim3 grid(p.d_u / cw, d.n_heads, (unsigned)a.B);
   const int nhp = p.head_groups * 32;
 #define EKV_MU(CW, DH)                                                                              \
   do {                                                                                              \
     const size_t sm = sizeof(float) * ((size_t)p.n_splits + 256 + (size_t)(256 / (CW / 8)) * CW + CW); \
-    merge_up_kernel<CW, DH><<<grid, 256, sm, stream>>>(pm, pl, pu, (const bf16_t*)a.W_uv, opart, cnt, \
-                                                       (bf16_t*)a.out, d.n_heads, nhp, p.d_u,        \
-                                                       p.n_splits);                                 \
+    merge_up_kernel<CW, DH><<<grid, 256, sm, stream>>>(pm, pl, pu, (const bf16_t*)a.W_uv, opart, d.n_heads, \
+                                                       nhp, p.d_u, p.n_splits);                          \
   } while (0)
   if (cw == 192) { if (d.head_dim == 128) EKV_MU(192, 128); else EKV_MU(192, 64); }
   else { if (d.head_dim == 128) EKV_MU(64, 128); else EKV_MU(64, 64); }

@@ -79,8 +79,6 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     p->up_cw = p->merge_batch ? 128 : (p->d_u % 192 == 0) ? 192 : 64;
     p->off_opart = off;
     off = align_up(off + Bz * nh * (size_t)(p->d_u / p->up_cw) * d->head_dim * sizeof(float), 256);
-    p->off_cnt = off;
-    off = align_up(off + Bz * nh * sizeof(uint32_t), 256);
   } else {
     p->mfma = 0;
     p->head_groups = 1;

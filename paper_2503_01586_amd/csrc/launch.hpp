@@ -24,9 +24,7 @@ struct DecodePlan {
   size_t off_m;         // split maxima (log2 domain)       fp32 [B, n_splits, n_h_pad]
   size_t off_l;         // split sums                       fp32 [B, n_splits, n_h_pad]
   size_t off_u;         // split latent accumulators        fp32 [B, n_splits, ...]
-  size_t off_ubar;      // merged, normalised latent        fp32 [B, n_h, d_c]
   size_t off_opart;     // up-projection partials           fp32
-  size_t off_cnt;       // arrival counters                 uint32
   size_t total;
 };
 

@@ -149,3 +149,42 @@ def test_mha_and_stream_argument_errors():
     assert lib.elitekv_stream_read(None, 16, FAKE, None) == ekv.ENULL
     assert lib.elitekv_stream_read(FAKE, 24, FAKE, None) == ekv.EALIGN
     assert lib.elitekv_stream_read(FAKE, 0, FAKE, None) == ekv.OK
+
+
+def test_slrd_argument_errors():
+    d = _dims()
+    dc = d.d_c
+    slrd = lambda d_ck, **kw: lib.elitekv_slrd_decode_attn(
+        C.byref(d), d_ck, kw.get("q", FAKE), FAKE, FAKE, kw.get("B", 1), 128, 128, FAKE, kw.get("B_v", FAKE), FAKE,
+        FAKE, FAKE, 128, FAKE, FAKE, kw.get("wsb", 1 << 30), 0, None)
+    assert slrd(0) == ekv.EINVAL and slrd(dc) == ekv.EINVAL and slrd(-3) == ekv.EINVAL    # 0 < d_ck < d_c
+    assert slrd(dc // 2, B=0) == ekv.OK
+    assert slrd(dc // 2, q=None) == ekv.ENULL
+    assert slrd(dc // 2, B_v=FAKE + 4) == ekv.EALIGN
+    need = ekv.elitekv_slrd_decode_workspace_bytes(d, dc // 2, 1, 128)
+    assert need > 0 and slrd(dc // 2, wsb=need - 1) == ekv.EWORKSPACE
+    assert ekv.elitekv_slrd_decode_workspace_bytes(d, 0, 1, 128) == 0
+    app = lambda d_ck, **kw: lib.elitekv_slrd_append(C.byref(d), d_ck, FAKE, FAKE, FAKE, kw.get("T", 1), FAKE, FAKE,
+                                                     kw.get("A_v", FAKE), FAKE, FAKE, FAKE, 16, FAKE, 1 << 30, None)
+    assert app(0) == ekv.EINVAL and app(dc) == ekv.EINVAL
+    assert app(dc // 2, T=0) == ekv.OK
+    assert app(dc // 2, A_v=None) == ekv.ENULL
+    # Section 3.2, S-LRD storage cost, against the oracle's statement of the same formula
+    big = ekv.make_dims(4096, 32, 128, 8, 1536, "bf16")
+    assert ekv.elitekv_slrd_param_count(big, 576) == orc.slrd_param_count(4096, 32, 128, 8, 576, 960)
+    # the separated latents at the 7B shape take the matrix-core path only for whole wave slices
+    assert ekv.elitekv_slrd_decode_workspace_bytes(big, 576, 1, 4096) < ekv.elitekv_decode_workspace_bytes(big, 1, 4096)
+
+
+def test_multiquery_argument_errors():
+    d = _dims()
+    mq = lambda **kw: lib.elitekv_multiquery_attn(C.byref(d), kw.get("q", FAKE), FAKE, FAKE, kw.get("B", 2),
+                                                  kw.get("T", 3), 128, 128, FAKE, FAKE, FAKE, FAKE, FAKE, 256, FAKE,
+                                                  FAKE, kw.get("wsb", 1 << 30), 0, None)
+    assert mq(T=0) == ekv.EINVAL and mq(B=-1) == ekv.EINVAL
+    assert mq(B=0) == ekv.OK
+    assert mq(B=300, T=300) == ekv.EUNSUPPORTED
+    assert mq(q=None) == ekv.ENULL
+    need = ekv.elitekv_multiquery_workspace_bytes(d, 2, 3, 128)
+    assert need == ekv.elitekv_decode_workspace_bytes(d, 6, 128)       # B*T query rows
+    assert mq(wsb=need - 1) == ekv.EWORKSPACE
