@@ -1,0 +1,56 @@
+"""The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+memset), so a decode step can be captured into a HIP graph and replayed.  The graph is replayed
+several times with eager work and synchronisations in between, and every replay is checked
+against the eager result."""
+import numpy as np
+import pytest
+import torch
+
+import elitekv_synth as synth
+import paper_2503_01586_amd as ekv
+
+from gpu_util import DEV, dev, dims_of, i32, i64
+from test_gpu_parity import _draw, shape
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("B", [1, 8])
+def test_append_and_decode_replay_from_a_graph(B):
+    sh, S = shape(512, 32, 128, 8, 1536, "bf16"), 700
+    rng, idx, W_ke, W_dkv, W_uk, W_uv, x, q = _draw(sh, B, B, 123 + B)
+    dims = dims_of(sh)
+    ke64, c64 = synth.draw_cache_planes(rng, B * S, 32, 8, 1536)
+    ke, c = dev(ke64, "bf16"), dev(c64, "bf16")
+    xd, qd, Wked, Wdkvd, Wukd, Wuvd = (dev(a, "bf16") for a in (x, q, W_ke, W_dkv, W_uk, W_uv))
+    idxd = i32(idx)
+    pos = torch.full((B,), S - 1, dtype=torch.int32, device=DEV)
+    slot = torch.arange(B, dtype=torch.int64, device=DEV) * S + (S - 1)
+    seq = torch.full((B,), S, dtype=torch.int32, device=DEV)
+    out = torch.zeros(B, 32, 128, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(ekv.elitekv_decode_workspace_bytes(dims, B, S), dtype=torch.uint8, device=DEV)
+    aws = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, B), 16), dtype=torch.uint8, device=DEV)
+
+    def step(stream):
+        ekv.elitekv_append(dims, xd, pos, slot, Wked, Wdkvd, idxd, ke, c, ws=aws, stream=stream)
+        ekv.elitekv_decode_attn(dims, qd, pos, seq, S, S, Wukd, Wuvd, idxd, ke, c, out, ws, stream=stream)
+
+    step(torch.cuda.current_stream().cuda_stream)          # eager (also the first-launch set-up of the kernels)
+    torch.cuda.synchronize()
+    want = out.clone()
+
+    side = torch.cuda.Stream()                             # default priority
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(side.cuda_stream)                             # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        out.fill_(float("nan"))                            # eager work between the replays
+        ws.fill_(0xFF)
+        c[slot] = 0
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), "replay %d differs from the eager step" % rep
