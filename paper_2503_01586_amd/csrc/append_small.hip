@@ -44,14 +44,25 @@ __global__ __launch_bounds__(kAsThreads) void append_small_kernel(
       if (s0 + u < steps && k < d) wq[u] = *reinterpret_cast<const uint4*>(wbase + (int64_t)k * wstride);
     }
   };
-  load_batch(0);
-
-  // stage x[t0 .. t0+8, k0 .. k0+kc) as xs[k][token]: per pass a thread takes one k for all tokens
-  for (int kk = tid; kk < kc; kk += kAsThreads) {
-    float xv[TT];
+  // stage x[t0 .. t0+TT, k0 .. k0+kc) as xs[k][token]: per pass a thread takes one k for all tokens.
+  // The first pass of these small loads is requested ahead of the weight rows (behind 16 MB of
+  // queued weight traffic they would return late); the weight rows follow at once.
+  auto load_x = [&](int kk, float (&xv)[TT]) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
-      xv[tt] = (t0 + tt < T && k0 + kk < d) ? ld(x, (t0 + tt) * d + k0 + kk) : 0.f;
+      xv[tt] = (kk < kc && t0 + tt < T && k0 + kk < d) ? ld(x, (t0 + tt) * d + k0 + kk) : 0.f;
+  };
+  float xfirst[TT];
+  load_x(tid, xfirst);
+  load_batch(0);
+  for (int kk = tid; kk < kc; kk += kAsThreads) {
+    float xv[TT];
+    if (kk == tid) {
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) xv[tt] = xfirst[tt];
+    } else {
+      load_x(kk, xv);
+    }
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) xs[kk * TT + tt] = xv[tt];
   }

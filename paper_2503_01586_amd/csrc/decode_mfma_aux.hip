@@ -364,6 +364,12 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   const int64_t p0 = (int64_t)b * n_splits;
   const int col0 = chunk * CW;
 
+  // (0) the split maxima and sums this thread will need first (split tid of the first 256): requested
+  //     before the bulk loads, behind which they would return late
+  const bool first_ok = tid < n_splits;
+  const float m_first = first_ok ? part_m[(p0 + tid) * nhp + head] : -INFINITY;
+  const float l_first = first_ok ? part_l[(p0 + tid) * nhp + head] : 0.f;
+
   // (1) this thread's W_uv rows: k = col0 + wave*RPI + rr + i*4*RPI
   const int jl = lane % LPW, rr = lane / LPW;
   uint4 wreg[NWI];
@@ -390,8 +396,8 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   load_batch(0);
 
   // (3) merge weights  w_s = exp2(m_s - max m),  L = sum w_s l_s   (an empty split has l = 0)
-  float m = -INFINITY;
-  for (int s = tid; s < n_splits; s += 256) m = fmaxf(m, part_m[(p0 + s) * nhp + head]);
+  float m = m_first;
+  for (int s = tid + 256; s < n_splits; s += 256) m = fmaxf(m, part_m[(p0 + s) * nhp + head]);
   m = wave_max(m);
   if (lane == 0) red[wave] = m;
   __syncthreads();
@@ -399,8 +405,9 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   __syncthreads();
   float lsum = 0.f;
   for (int s = tid; s < n_splits; s += 256) {
-    const float ls = part_l[(p0 + s) * nhp + head];
-    const float w = (ls > 0.f) ? exp2f(part_m[(p0 + s) * nhp + head] - m) : 0.f;
+    const float ls = (s == tid) ? l_first : part_l[(p0 + s) * nhp + head];
+    const float ms = (s == tid) ? m_first : part_m[(p0 + s) * nhp + head];
+    const float w = (ls > 0.f) ? exp2f(ms - m) : 0.f;
     wsp[s] = w;
     lsum += w * ls;
   }
