@@ -429,9 +429,9 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams
     return t0 + (int64_t)(j < n_my ? j : i) * t_step;
   };
   const int64_t first = tile_at(0);
+  load_query();   // requested ahead of the tiles: behind a tile's worth of queued traffic it would return late
   issue_c(first, ctile0);
   issue_ke(first, ketile0);
-  load_query();   // after the first tile's loads are in flight
   for (int i = 0; i < n_my; i += 2) {
     const int64_t ta = tile_at(i), tb = tile_at(i + 1), tc = tile_at(i + 2);
     if (tb < t_end) {
