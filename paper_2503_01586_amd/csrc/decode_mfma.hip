@@ -125,8 +125,10 @@ constexpr float kRescaleSlack = 8.f;
 // SEP = separated latents (Section 3.2, S-LRD): a cache row is [c^k (d_q columns) | c^v (d_u columns)];
 // the waves whose slice lies in c^k only compute scores, the waves whose slice lies in c^v only
 // accumulate values (d_q is a multiple of DC_W).  SEP = false is the joint latent: every wave does both.
+// (Four-wave instantiations with slices of up to 192 columns use at most 75 KB of LDS: they are
+// compiled for two work-groups per compute unit, i.e. at most 256 registers per lane.)
 template <int NW, int DC_W, int TWO_R, bool SEP>
-__global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(const AttnMfmaParams p) {
+__global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void attn_mfma_kernel(const AttnMfmaParams p) {
   using L = AttnMfmaLayout<NW, DC_W, TWO_R>;
   constexpr int KS = L::KS, CT = L::CT, NCB = L::NCB, EPL = L::EPL, TPW = L::TPW;
   constexpr int KCH = TWO_R / 8;                 // 16-byte chunks of one head's elite key
@@ -505,6 +507,9 @@ static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t 
 
 // wave slice of the compiled instantiation for a latent row of d_c columns; 0 = none
 static int slice_width(int d_c) { return d_c == 1920 ? 480 : d_c == 1536 || d_c == 768 ? 192 : d_c == 256 ? 64 : 0; }
+
+// work-groups of the attention kernel that fit one compute unit (see the launch bounds of the kernel)
+int decode_mfma_groups_per_cu(const elitekv_dims& d) { return (d.d_c == 768 || d.d_c == 256) ? 2 : 1; }
 
 bool decode_mfma_supported(const elitekv_dims& d, int d_ck) {
   if (d.dtype != ELITEKV_BF16) return false;

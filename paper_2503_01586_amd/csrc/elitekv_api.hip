@@ -60,7 +60,11 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     p->head_groups = (d->n_heads + 31) / 32;
     int64_t ns = n_splits;
     if (ns == 0) {
-      ns = (kComputeUnits + Bq * p->head_groups - 1) / (Bq * p->head_groups);
+      // the narrow-latent instantiations run two work-groups per compute unit; with many batch rows
+      // it pays to give every compute unit two (more splits also mean more partials to merge)
+      const int64_t want = (decode_mfma_groups_per_cu(*d) == 2 && Bq * p->head_groups >= 16) ? 2 * kComputeUnits
+                                                                                            : kComputeUnits;
+      ns = (want + Bq * p->head_groups - 1) / (Bq * p->head_groups);
       const int64_t cap = (seq + 15) / 16;
       if (ns > cap) ns = cap;
       if (ns > kMaxSplits) ns = kMaxSplits;

@@ -90,6 +90,7 @@ bool append_gemm_supported(const elitekv_dims& d, int64_t T, int d_ck);
 hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_generic(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 bool decode_mfma_supported(const elitekv_dims& d, int d_ck);
+int decode_mfma_groups_per_cu(const elitekv_dims& d);
 struct bf16_t;
 hipError_t launch_qprep_rows(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt,
                              hipStream_t stream);
