@@ -506,10 +506,29 @@ static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t 
 }
 
 // wave slice of the compiled instantiation for a latent row of d_c columns; 0 = none
-static int slice_width(int d_c) { return d_c == 1920 ? 480 : d_c == 1536 || d_c == 768 ? 192 : d_c == 256 ? 64 : 0; }
+// The compiled instantiations: every latent width that is a multiple of 128 up to 2048 (the
+// hardware-friendly widths of Appendix C) and 1920 (the 13B benchmark shape), as
+// X(d_c, waves, columns per wave).  Eight waves x <= 192 columns run two waves per SIMD; four waves
+// with wider slices run one wave per SIMD with the accumulators in AGPRs.
+#define EKV_ATTN_SHAPES(X)                                                                            \
+  X(2048, 4, 512) X(1920, 4, 480) X(1792, 4, 448) X(1664, 4, 416) X(1536, 8, 192) X(1408, 4, 352)     \
+  X(1280, 8, 160) X(1152, 4, 288) X(1024, 8, 128) X(896, 4, 224) X(768, 4, 192) X(640, 4, 160)        \
+  X(512, 4, 128) X(384, 4, 96) X(256, 4, 64) X(128, 2, 64)
+
+static void shape_of(int d_c, int* nw, int* dcw) {
+  *nw = 0; *dcw = 0;
+#define X(DC, NWV, DCW) if (d_c == DC) { *nw = NWV; *dcw = DCW; }
+  EKV_ATTN_SHAPES(X)
+#undef X
+}
+static int slice_width(int d_c) { int nw, w; shape_of(d_c, &nw, &w); return w; }
 
 // work-groups of the attention kernel that fit one compute unit (see the launch bounds of the kernel)
-int decode_mfma_groups_per_cu(const elitekv_dims& d) { return (d.d_c == 768 || d.d_c == 256) ? 2 : 1; }
+int decode_mfma_groups_per_cu(const elitekv_dims& d) {
+  int nw, w;
+  shape_of(d.d_c, &nw, &w);
+  return (nw == 4 && w <= 192) ? 2 : 1;
+}
 
 bool decode_mfma_supported(const elitekv_dims& d, int d_ck) {
   if (d.dtype != ELITEKV_BF16) return false;
@@ -518,7 +537,7 @@ bool decode_mfma_supported(const elitekv_dims& d, int d_ck) {
   if (two_r != 8 && two_r != 16) return false;
   const int w = slice_width(d.d_c);
   if (w == 0) return false;
-  if (d_ck > 0 && w == 480) return false;   // the one-wave-per-SIMD instantiation is compiled for the joint latent only
+  if (d_ck > 0 && w > 256) return false;    // the one-wave-per-SIMD instantiations are compiled for the joint latent only
   // separated latents: whole wave slices on either side of the boundary
   // (and the value part a whole number of the merge kernels' 64-column chunks)
   return d_ck == 0 || (d_ck > 0 && d_ck < d.d_c && d_ck % w == 0 && (d.d_c - d_ck) % 64 == 0);
@@ -547,19 +566,17 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   e = hipErrorInvalidValue;
   const int two_r = 2 * d.r;
   const bool sep = a.d_ck > 0;
-#define EKV_CASE(DC, NWV, DCW)                                                                         \
+#define X(DC, NWV, DCW)                                                                                \
   if (d.d_c == DC) {                                                                                   \
-    e = sep ? (two_r == 16 ? launch_attn<NWV, DCW, 16, true>(prm, a.B, stream)                         \
-                           : launch_attn<NWV, DCW, 8, true>(prm, a.B, stream))                         \
-            : (two_r == 16 ? launch_attn<NWV, DCW, 16, false>(prm, a.B, stream)                        \
-                           : launch_attn<NWV, DCW, 8, false>(prm, a.B, stream));                       \
+    if constexpr (DCW <= 256) {                                                                        \
+      if (sep) e = two_r == 16 ? launch_attn<NWV, DCW, 16, true>(prm, a.B, stream)                     \
+                               : launch_attn<NWV, DCW, 8, true>(prm, a.B, stream);                     \
+    }                                                                                                  \
+    if (!sep) e = two_r == 16 ? launch_attn<NWV, DCW, 16, false>(prm, a.B, stream)                     \
+                              : launch_attn<NWV, DCW, 8, false>(prm, a.B, stream);                     \
   }
-  if (d.d_c == 1920)
-    e = two_r == 16 ? launch_attn<4, 480, 16, false>(prm, a.B, stream) : launch_attn<4, 480, 8, false>(prm, a.B, stream);
-  EKV_CASE(1536, 8, 192)
-  EKV_CASE(768, 4, 192)
-  EKV_CASE(256, 4, 64)
-#undef EKV_CASE
+  EKV_ATTN_SHAPES(X)
+#undef X
   if (e != hipSuccess) return e;
   return (a.stages & 4) ? launch_merge_up(a, p, stream) : hipSuccess;
 }

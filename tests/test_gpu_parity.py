@@ -116,6 +116,15 @@ DECODE_CASES = {
 }
 
 
+# every latent width the matrix-core attention kernel is compiled for (multiples of 128 up to 2048)
+for _dc in (128, 384, 512, 640, 896, 1024, 1152, 1280, 1408, 1664, 1792, 2048):
+    DECODE_CASES["bf16_latent_%d" % _dc] = (shape(64, 32, 128, 8 if _dc % 256 else 4, _dc, "bf16"), [150, 33, 16],
+                                            [0, 3])
+DECODE_CASES["bf16_latent_2048_40_heads"] = (shape(64, 40, 128, 8, 2048, "bf16"), [97, 160], [0, 2])
+DECODE_CASES["bf16_latent_1024_batch_9"] = (shape(64, 32, 128, 8, 1024, "bf16"), [0, 1, 15, 16, 17, 250, 33, 48, 100],
+                                            [0, 3])
+
+
 @pytest.mark.parametrize("name", list(DECODE_CASES))
 def test_decode_matches_oracle_on_same_planes(name):
     sh, seqs, splits = DECODE_CASES[name]
