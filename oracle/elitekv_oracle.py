@@ -259,6 +259,79 @@ def multiquery_attn(q, q_pos, ke, c, kv_len, W_uk, W_uv, elite_idx, head_dim: in
     return out
 
 
+# ----------------------------------------------------------------------------------------------
+# RoPElite search (Section 3.1, Algorithm 1): the greedy choice of each head's elite chunks.
+# Round after round, every chunk that is not yet elite is tried as the one additional rotated chunk;
+# the chunk whose scores come closest (L1) to the scores of full RoPE is appended.
+# Readings: "attn_score" is the pre-softmax score s of Section 2.1 (the quantity the Section 3.1 score
+# equation rewrites), over the causal pairs (a query sees the keys up to its own step); ties go to
+# the lowest chunk index.
+# ----------------------------------------------------------------------------------------------
+def rope_on_chunks(x, pos, chunks, head_dim: int, rope_base: float):
+    """x [T, d_h] with only the listed chunks rotated by R(pos * theta_i) (Section 2.2, eq. 1a)."""
+    x = np.array(x, dtype=F64, copy=True)
+    theta = rope_theta(head_dim, rope_base)
+    for i in chunks:
+        i = int(i)
+        x[:, 2 * i:2 * i + 2] = rotate_pairs(x[:, 2 * i:2 * i + 2], np.asarray(pos, dtype=F64) * theta[i])
+    return x
+
+
+def causal_scores(q_h, k_h, head_dim: int):
+    """s[t, j] = q_t . k_j / sqrt(d_h) for j <= t, 0 elsewhere (Section 2.1, before the softmax)."""
+    s = (q_h @ k_h.T) / np.sqrt(F64(head_dim))
+    return np.tril(s)
+
+
+def ropelite_search(q, k, pos, r: int, head_dim: int, rope_base: float):
+    """q, k [T, n_h, d_h] un-rotated queries and keys of one layer; pos [T].
+    Returns (elite [n_h, r] int32 in selection order, dist [n_h, r] the winning L1 distances)."""
+    q = np.asarray(q, dtype=F64)
+    k = np.asarray(k, dtype=F64)
+    T, n_h, d_h = q.shape
+    all_chunks = list(range(d_h // 2))
+    elite = np.zeros((n_h, r), dtype=np.int32)
+    dist_out = np.zeros((n_h, r), dtype=F64)
+    for h in range(n_h):
+        s_full = causal_scores(rope_on_chunks(q[:, h], pos, all_chunks, d_h, rope_base),
+                               rope_on_chunks(k[:, h], pos, all_chunks, d_h, rope_base), d_h)
+        e = []
+        for i in range(r):
+            best, best_d = -1, np.inf
+            for j in all_chunks:
+                if j in e:
+                    continue
+                s_try = causal_scores(rope_on_chunks(q[:, h], pos, e + [j], d_h, rope_base),
+                                      rope_on_chunks(k[:, h], pos, e + [j], d_h, rope_base), d_h)
+                dj = float(np.sum(np.abs(s_full - s_try)))
+                if dj < best_d:                       # strict: the lowest index wins a tie
+                    best, best_d = j, dj
+            e.append(best)
+            elite[h, i] = best
+            dist_out[h, i] = best_d
+    return elite, dist_out
+
+
+def ropelite_distances(q, k, pos, elite_h, head, head_dim: int, rope_base: float):
+    """L1 distance to the full-RoPE scores of head `head` for every chunk tried as the one addition
+    to the elite list `elite_h` (np.inf for chunks already in it): one round of Algorithm 1."""
+    q = np.asarray(q, dtype=F64)
+    k = np.asarray(k, dtype=F64)
+    d_h = q.shape[2]
+    all_chunks = list(range(d_h // 2))
+    e = [int(i) for i in elite_h]
+    s_full = causal_scores(rope_on_chunks(q[:, head], pos, all_chunks, d_h, rope_base),
+                           rope_on_chunks(k[:, head], pos, all_chunks, d_h, rope_base), d_h)
+    out = np.full(d_h // 2, np.inf)
+    for j in all_chunks:
+        if j in e:
+            continue
+        s_try = causal_scores(rope_on_chunks(q[:, head], pos, e + [j], d_h, rope_base),
+                              rope_on_chunks(k[:, head], pos, e + [j], d_h, rope_base), d_h)
+        out[j] = float(np.sum(np.abs(s_full - s_try)))
+    return out
+
+
 def mha_decode(q, q_pos, K_rot, V, seq_len, rope_base: float):
     """Comparator: ordinary RoPE multi-head decode attention (Sections 2.1 and 2.2).
 
