@@ -150,6 +150,24 @@ int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* 
                         void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * RoPElite search (Section 3.1, Algorithm 1): the greedy choice of every head's r elite chunks from
+ * a sample of UN-ROTATED queries and keys of one layer.  In each of r rounds every chunk that is
+ * not yet elite is tried as the one additional rotated chunk; the chunk whose pre-softmax scores
+ * (Section 2.1's s, over the causal pairs key step <= query step, scaled by 1/sqrt(d_h)) have the
+ * smallest L1 distance to the scores of full RoPE is appended; the lowest index wins a tie.
+ *   q, k      [T, n_heads, head_dim] float32, device      pos [T] int32, device
+ *   elite_out [n_heads, r] int32, device: chunk indices in selection order (usable as elite_idx)
+ *   dist_out  [n_heads, r] float32, device, or NULL: the winning distance of every round
+ * Arithmetic is fp32 (angles reduced in double); a near-tie between two chunks may resolve
+ * differently from exact arithmetic.  head_dim <= 128.  Workspace: the _workspace_bytes function.
+ * Enqueues 2 r + 2 kernels on hip_stream; no host synchronisation.
+ * ------------------------------------------------------------------------------------------- */
+size_t elitekv_ropelite_search_workspace_bytes(int64_t T, int32_t n_heads, int32_t head_dim, int32_t r);
+int elitekv_ropelite_search(const float* q, const float* k, const int32_t* pos, int64_t T, int32_t n_heads,
+                            int32_t head_dim, int32_t r, double rope_base, int32_t* elite_out, float* dist_out,
+                            void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Several queries per sequence (a prefill chunk, the verification of drafted tokens): T query
  * tokens of each of B sequences attend over the cache rows of their own sequence.  Section 2.1
  * builds K_t, V_t from the tokens up to step t, so query (b, t) sees a prefix of sequence b's rows;

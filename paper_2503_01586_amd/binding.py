@@ -50,6 +50,8 @@ def _load():
         "elitekv_decode_auto_splits": (I32, [DP, I64, I64]),
         "elitekv_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_decode_attn": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32, P]),
+        "elitekv_ropelite_search_workspace_bytes": (SZ, [I64, I32, I32, I32]),
+        "elitekv_ropelite_search": (C.c_int, [P, P, P, I64, I32, I32, I32, C.c_double, P, P, P, SZ, P]),
         "elitekv_multiquery_workspace_bytes": (SZ, [DP, I64, I64, I64, I32]),
         "elitekv_multiquery_attn": (C.c_int, [DP, P, P, P, I64, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32, P]),
         "elitekv_slrd_param_count": (C.c_int, [DP, I32, C.POINTER(I64)]),
@@ -164,6 +166,20 @@ def elitekv_decode_attn(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows,
                                   _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
                                   _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
     _check(st, "elitekv_decode_attn")
+
+
+def elitekv_ropelite_search_workspace_bytes(T, n_heads, head_dim, r) -> int:
+    return _lib.elitekv_ropelite_search_workspace_bytes(int(T), int(n_heads), int(head_dim), int(r))
+
+
+def elitekv_ropelite_search(q, k, pos, r, rope_base, elite_out, dist_out, ws, stream=None):
+    """q, k [T, n_h, d_h] float32; pos [T] int32; elite_out [n_h, r] int32; dist_out [n_h, r] float32 or None."""
+    T, n_h, d_h = q.shape
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_ropelite_search(_ptr(q), _ptr(k), _ptr(pos), int(T), int(n_h), int(d_h), int(r),
+                                      float(rope_base), _ptr(elite_out), _ptr(dist_out), _ptr(ws), ws_bytes,
+                                      _stream(stream))
+    _check(st, "elitekv_ropelite_search")
 
 
 def elitekv_multiquery_workspace_bytes(dims, B, T, max_seq_len, n_splits=0) -> int:

@@ -269,6 +269,33 @@ static int decode_impl(const elitekv_dims* dims, int32_t d_ck, const void* q, co
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
 }
 
+/* ---- RoPElite search ---- */
+
+static int check_search(int64_t T, int32_t n_h, int32_t head_dim, int32_t r, double rope_base) {
+  if (T < 1 || n_h < 1 || head_dim < 2 || (head_dim & 1) || r < 1 || 2 * r > head_dim) return ELITEKV_EINVAL;
+  if (!(rope_base > 0.0) || !isfinite(rope_base)) return ELITEKV_EINVAL;
+  if (head_dim > 128 || n_h > 65535 || T > (1 << 20)) return ELITEKV_EUNSUPPORTED;
+  return ELITEKV_OK;
+}
+
+size_t elitekv_ropelite_search_workspace_bytes(int64_t T, int32_t n_heads, int32_t head_dim, int32_t r) {
+  if (check_search(T, n_heads, head_dim, r, 10000.0)) return 0;
+  return search_workspace_bytes(T, n_heads, head_dim);
+}
+
+int elitekv_ropelite_search(const float* q, const float* k, const int32_t* pos, int64_t T, int32_t n_heads,
+                            int32_t head_dim, int32_t r, double rope_base, int32_t* elite_out, float* dist_out,
+                            void* ws, size_t ws_bytes, void* hip_stream) {
+  int st = check_search(T, n_heads, head_dim, r, rope_base);
+  if (st) return st;
+  if (!q || !k || !pos || !elite_out || !ws) return ELITEKV_ENULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(ws)) return ELITEKV_EALIGN;
+  if (ws_bytes < search_workspace_bytes(T, n_heads, head_dim)) return ELITEKV_EWORKSPACE;
+  const hipError_t e = launch_ropelite_search(q, k, pos, T, n_heads, head_dim, r, rope_base, elite_out, dist_out,
+                                              (char*)ws, (hipStream_t)hip_stream);
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
 /* ---- several queries per sequence ---- */
 
 size_t elitekv_multiquery_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t T, int64_t max_seq_len,

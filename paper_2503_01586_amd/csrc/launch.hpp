@@ -98,6 +98,10 @@ bool merge_batch_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);
+size_t search_workspace_bytes(int64_t T, int n_h, int d_h);
+hipError_t launch_ropelite_search(const float* q, const float* k, const int32_t* pos, int64_t T, int n_h, int d_h,
+                                  int r, double rope_base, int32_t* elite_out, float* dist_out, char* ws,
+                                  hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
 
 }  // namespace ekv
