@@ -210,6 +210,7 @@ def main():
         if not d_ck:
             result["multiquery"] = multiquery(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
                                               cache_bytes)
+        result["ropelite_search"] = ropelite_search(ekv, ev, cfg, dev, stream)
         result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_dkv2_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0,
@@ -308,6 +309,29 @@ def multiquery(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, strea
     return {"queries_per_sequence": T, "ms_per_call": round(ms, 5), "us_per_query": round(ms * 1e3 / (B * T), 3),
             "cache_bytes_consumed_GBs": round(cache_bytes * T / (ms * 1e-3) / 1e9, 1),
             "query_tokens_per_s": round(B * T / (ms * 1e-3), 1)}
+
+
+def ropelite_search(ekv, ev, cfg, dev, stream, T=512, iters=3):
+    """The greedy elite-chunk search of one layer (all heads, r rounds) on T sampled tokens."""
+    import torch
+    n_h, d_h, r = cfg.n_heads, cfg.head_dim, cfg.r
+    g = torch.Generator(device=dev)
+    g.manual_seed(15862)
+    q = torch.randn(T, n_h, d_h, device=dev, dtype=torch.float32, generator=g)
+    k = torch.randn(T, n_h, d_h, device=dev, dtype=torch.float32, generator=g)
+    pos = torch.arange(T, dtype=torch.int32, device=dev)
+    elite = torch.zeros(n_h, r, dtype=torch.int32, device=dev)
+    ws = torch.empty(ekv.elitekv_ropelite_search_workspace_bytes(T, n_h, d_h, r), dtype=torch.uint8, device=dev)
+    ekv.elitekv_ropelite_search(q, k, pos, r, cfg.rope_base, elite, None, ws, stream=stream)
+    e0, e1 = ev.create(), ev.create()
+    ev.record(e0, stream)
+    for _ in range(iters):
+        ekv.elitekv_ropelite_search(q, k, pos, r, cfg.rope_base, elite, None, ws, stream=stream)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms = ev.elapsed_ms(e0, e1) / iters
+    evals = T * (T + 1) / 2 * n_h * r * (d_h // 2)      # (causal pair, chunk) evaluations over all rounds
+    return {"tokens": T, "rounds": r, "ms_per_layer": round(ms, 4), "G_pair_chunk_evals_per_s": round(evals / ms / 1e6, 1)}
 
 
 def append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream, T=2048, iters=20):
