@@ -128,12 +128,24 @@ def main():
                      ekv.elitekv_slrd_append_workspace_bytes(dims, d_ck, B))
     else:
         nws, naws = ekv.elitekv_decode_workspace_bytes(dims, B, S, args.splits), ekv.elitekv_append_workspace_bytes(dims, B)
-    ws_d = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
+    nsws = (ekv.elitekv_slrd_decode_step_workspace_bytes(dims, d_ck, B, S, args.splits) if d_ck
+            else ekv.elitekv_decode_step_workspace_bytes(dims, B, S, args.splits))
+    ws_d = torch.empty(max(nws, nsws, 16), dtype=torch.uint8, device=dev)   # the step's workspace starts with the decode's
     aws_d = torch.empty(max(naws, 16), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     ev = HipEvents()
 
     def step(i):
+        ke_p, c_p = planes[i % n_copies]
+        if d_ck:
+            ekv.elitekv_slrd_decode_step(dims, d_ck, x_d, q_d, pos_d, slot_d, seq_d, S, S, W_ke_d, W_dkv_d, W_dkv2_d,
+                                         W_uk_d, W_uv_d, idx_d, ke_p, c_p, out_d, ws_d, n_splits=args.splits,
+                                         stream=stream)
+        else:
+            ekv.elitekv_decode_step(dims, x_d, q_d, pos_d, slot_d, seq_d, S, S, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, idx_d,
+                                    ke_p, c_p, out_d, ws_d, n_splits=args.splits, stream=stream)
+
+    def step_two_calls(i):
         ke_p, c_p = planes[i % n_copies]
         if d_ck:
             ekv.elitekv_slrd_append(dims, d_ck, x_d, pos_d, slot_d, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, ke_p, c_p,
@@ -155,6 +167,16 @@ def main():
     ev.record(e1, stream)
     torch.cuda.synchronize()
     ms_per_step = ev.elapsed_ms(e0, e1) / args.steps
+    # the same work through the two separate entry points (append, then attention), for reference
+    for i in range(args.warmup):
+        step_two_calls(i)
+    torch.cuda.synchronize()
+    ev.record(e0, stream)
+    for i in range(args.steps):
+        step_two_calls(i)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms_two_calls = ev.elapsed_ms(e0, e1) / args.steps
 
     # dominant kernel (the split attention kernel): K launches of that stage alone, back to back on
     # the stream over the same rotating plane copies, between ONE pair of HIP events (an event pair
@@ -164,6 +186,7 @@ def main():
         ke_p, c_p = planes[i % n_copies]
         ekv.elitekv_decode_attn_stages(dims, q_d, pos_d, seq_d, S, S, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out_d, ws_d,
                                        2, n_splits=args.splits, stream=stream, d_ck=d_ck)
+    step_two_calls(0)          # a full elitekv_decode_attn with these arguments leaves the prepared query behind
     for i in range(args.warmup):
         attn_only(i)
     torch.cuda.synchronize()
@@ -191,11 +214,13 @@ def main():
         "config": {"workload": cfg.name, "batch": B, "context": S, "d_model": d, "n_heads": n_h, "head_dim": d_h,
                    "r": r, "d_c": d_c, "cache_fraction": (2 * r * n_h + d_c) / (2 * n_h * d_h),
                    "variant": "S-LRD (d_ck %d, d_cv %d)" % (d_ck, d_c - d_ck) if d_ck else "J-LRD",
-                   "step": ("elitekv_slrd_append(T=batch) + elitekv_slrd_decode_attn" if d_ck
-                            else "elitekv_append(T=batch) + elitekv_decode_attn"), "plane_copies": n_copies,
+                   "step": ("elitekv_slrd_decode_step (= elitekv_slrd_append(T=batch) + elitekv_slrd_decode_attn)" if d_ck
+                            else "elitekv_decode_step (= elitekv_append(T=batch) + elitekv_decode_attn)"),
+                   "plane_copies": n_copies,
                    "n_splits": ekv.elitekv_decode_auto_splits(dims, B, S) if args.splits == 0 else args.splits},
         "pct_of_hbm_peak": round(100.0 * value_gbs / HBM_PEAK_GBS, 2),
         "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
+        "ms_per_step_two_calls": round(ms_two_calls, 5),
         "roofline": {"bound": "hbm", "kernel": "split attention kernel of elitekv_decode_attn",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES.get(cfg.name),

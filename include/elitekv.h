@@ -232,6 +232,46 @@ int elitekv_slrd_decode_attn(const elitekv_dims* dims, int32_t d_ck, const void*
                              void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * One decode step in one call: the B new tokens (one per sequence) are appended to the cache and
+ * each sequence's query attends to its cached tokens and to its new token.  With
+ * slot[b] = b * batch_stride_rows + seq_len[b] - 1 the result is that of elitekv_append (T = B; x,
+ * pos, slot) followed by elitekv_decode_attn (q, q_pos = pos, seq_len) on the same stream
+ * (Sections 3.1, 3.2 and 5 as cited there); sums may be taken in a different order, so results agree
+ * to rounding, not bit for bit.
+ *   seq_len[b] counts the tokens the query of sequence b attends to, the new one included: rows
+ *   b * batch_stride_rows + [0, seq_len[b] - 1) of the planes, then the new token, whose row is
+ *   slot[b] = b * batch_stride_rows + seq_len[b] - 1.  For a sequence whose slot[b] is anything
+ *   else (out of range: the token is not stored; another row) the row is stored as elitekv_append
+ *   stores it but out[b] is unspecified: depending on the shape the new token is attended to from
+ *   its fresh row or from whatever row seq_len[b] - 1 of the plane holds.
+ *   For fewer than eight sequences (bf16 shapes of the matrix-core path) the step is four launches:
+ *   the first pass of the append together with the query preparation; the attention, whose extra
+ *   work-groups add up the append's partial sums, rotate and store the new rows and pass the new
+ *   token on as one more split; the merge with the up-projection; the final reduction.  Other
+ *   shapes run the two entry points' kernels one after the other.
+ *   All other arguments, layouts, ownership and errors as in elitekv_append and
+ *   elitekv_decode_attn.  ws: elitekv_decode_step_workspace_bytes bytes (EWORKSPACE if smaller).
+ * ------------------------------------------------------------------------------------------- */
+size_t elitekv_decode_step_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
+                                           int32_t n_splits);
+int elitekv_decode_step(const elitekv_dims* dims, const void* x, const void* q, const int32_t* pos,
+                        const int64_t* slot, const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                        int64_t batch_stride_rows, const void* W_ke, const void* W_dkv, const void* W_uk,
+                        const void* W_uv, const int32_t* elite_idx, void* ke_plane, void* c_plane,
+                        int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                        void* hip_stream);
+
+/* The same step for separated latents: elitekv_slrd_append followed by elitekv_slrd_decode_attn. */
+size_t elitekv_slrd_decode_step_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B,
+                                                int64_t max_seq_len, int32_t n_splits);
+int elitekv_slrd_decode_step(const elitekv_dims* dims, int32_t d_ck, const void* x, const void* q,
+                             const int32_t* pos, const int64_t* slot, const int32_t* seq_len, int64_t B,
+                             int64_t max_seq_len, int64_t batch_stride_rows, const void* W_ke, const void* A_k,
+                             const void* A_v, const void* B_k, const void* B_v, const int32_t* elite_idx,
+                             void* ke_plane, void* c_plane, int64_t plane_rows, void* out, void* ws,
+                             size_t ws_bytes, int32_t n_splits, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement-only companions (not part of the method).
  * ------------------------------------------------------------------------------------------- */
 

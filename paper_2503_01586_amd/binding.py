@@ -60,6 +60,12 @@ def _load():
         "elitekv_slrd_decode_workspace_bytes": (SZ, [DP, I32, I64, I64, I32]),
         "elitekv_slrd_decode_attn": (C.c_int, [DP, I32, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32,
                                                P]),
+        "elitekv_decode_step_workspace_bytes": (SZ, [DP, I64, I64, I32]),
+        "elitekv_decode_step": (C.c_int, [DP, P, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, I64, P, P, SZ, I32,
+                                          P]),
+        "elitekv_slrd_decode_step_workspace_bytes": (SZ, [DP, I32, I64, I64, I32]),
+        "elitekv_slrd_decode_step": (C.c_int, [DP, I32, P, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, P, I64, P,
+                                               P, SZ, I32, P]),
         "elitekv_decode_attn_stages": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32,
                                                  P, I32, I32]),
         "elitekv_mha_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
@@ -235,6 +241,41 @@ def elitekv_slrd_decode_attn(dims, d_ck, q, q_pos, seq_len, max_seq_len, batch_s
                                        _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
                                        _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
     _check(st, "elitekv_slrd_decode_attn")
+
+
+def elitekv_decode_step_workspace_bytes(dims, B, max_seq_len, n_splits=0) -> int:
+    return _lib.elitekv_decode_step_workspace_bytes(C.byref(dims), int(B), int(max_seq_len), int(n_splits))
+
+
+def elitekv_decode_step(dims, x, q, pos, slot, seq_len, max_seq_len, batch_stride_rows, W_ke, W_dkv, W_uk, W_uv,
+                        elite_idx, ke_plane, c_plane, out, ws, n_splits=0, stream=None, B=None, plane_rows=None):
+    B = q.shape[0] if B is None else B
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_decode_step(C.byref(dims), _ptr(x), _ptr(q), _ptr(pos), _ptr(slot), _ptr(seq_len), int(B),
+                                  int(max_seq_len), int(batch_stride_rows), _ptr(W_ke), _ptr(W_dkv), _ptr(W_uk),
+                                  _ptr(W_uv), _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
+                                  _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
+    _check(st, "elitekv_decode_step")
+
+
+def elitekv_slrd_decode_step_workspace_bytes(dims, d_ck, B, max_seq_len, n_splits=0) -> int:
+    return _lib.elitekv_slrd_decode_step_workspace_bytes(C.byref(dims), int(d_ck), int(B), int(max_seq_len),
+                                                         int(n_splits))
+
+
+def elitekv_slrd_decode_step(dims, d_ck, x, q, pos, slot, seq_len, max_seq_len, batch_stride_rows, W_ke, A_k, A_v,
+                             B_k, B_v, elite_idx, ke_plane, c_plane, out, ws, n_splits=0, stream=None, B=None,
+                             plane_rows=None):
+    B = q.shape[0] if B is None else B
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_slrd_decode_step(C.byref(dims), int(d_ck), _ptr(x), _ptr(q), _ptr(pos), _ptr(slot),
+                                       _ptr(seq_len), int(B), int(max_seq_len), int(batch_stride_rows), _ptr(W_ke),
+                                       _ptr(A_k), _ptr(A_v), _ptr(B_k), _ptr(B_v), _ptr(elite_idx), _ptr(ke_plane),
+                                       _ptr(c_plane), int(plane_rows), _ptr(out), _ptr(ws), ws_bytes, int(n_splits),
+                                       _stream(stream))
+    _check(st, "elitekv_slrd_decode_step")
 
 
 def elitekv_decode_attn_stages(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,

@@ -46,6 +46,18 @@ struct AttnMfmaParams {
   int q_per_seq;          // query rows per sequence (several queries share the cache rows of a sequence)
   int d_q, d_u;           // widths of the absorbed query and of the latent accumulators (d_c when joint)
   int64_t max_seq_len, batch_stride_rows, plane_rows;
+  // Fused decode step: the newest token of every sequence (position seq_len - 1) is not read from the
+  // planes.  Its cache row is still a set of partial sums (the append's contraction splits); the
+  // extra work-groups with split index n_splits add them up, store the row and hand the token to
+  // the merge as one more split.  n_part = partials per batch row (n_splits, or n_splits + 1 here).
+  int n_part;
+  int fresh;              // 1: fused decode step
+  const float* fr_partial;   // [fr_ks][batch][N] sums of the append's contraction splits
+  const float2* fr_sincos;   // [batch][n_h * r]  (sin, cos) of the new token's elite chunks
+  const int64_t* fr_slot;    // [batch] destination rows
+  int fr_ks;
+  bf16_t* fr_ke_out;         // the planes, writable
+  bf16_t* fr_c_out;
 };
 
 // LDS layout of one wave's tile slice (16 tokens x DC_W latent columns, bf16): blocks of
@@ -122,6 +134,87 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 // log2-domain slack before the running maximum is raised: probabilities stay below 2^8
 constexpr float kRescaleSlack = 8.f;
 
+// The newest token of sequence b in a fused decode step, for head group hg (NT threads).
+//   1. its cache row = the sum of the append's contraction splits (in split order, as append_finish
+//      adds them), the elite pairs rotated with the (sin, cos) the query preparation left behind
+//      (same position, same chunks), rounded to bf16; head group 0 stores it at slot[b];
+//   2. its score against every head of the group, from the row AS STORED (what a later step reads):
+//      s_h = qe[h] . ke_row[h] + qt[h] . c_row[0 : d_q]           (log2 domain, query pre-scaled)
+//   3. one more split for the merge: m = s_h, l = 1, U = c_row[d_c - d_u : d_c].
+// A sequence with no attended token at all (seq_len <= 0) gets an empty split (l = 0).
+template <int NT, int TWO_R>
+__device__ __forceinline__ void new_token_role(const AttnMfmaParams& p, int hg, int b, char* smem) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int NE = p.n_h * TWO_R, N = NE + p.d_c;
+  float* row = reinterpret_cast<float*>(smem);             // [N] the row as stored
+  const int64_t slot = p.fr_slot[b];
+  const bool store = hg == 0 && slot >= 0 && slot < p.plane_rows;
+  for (int pr = tid; pr < N / 2; pr += NT) {
+    const int n = 2 * pr;
+    float a0 = 0.f, a1 = 0.f;
+    for (int s0 = 0; s0 < p.fr_ks; s0 += 8) {              // eight independent loads in flight; split order kept
+      float2 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        v[u] = (s0 + u < p.fr_ks)
+                   ? *reinterpret_cast<const float2*>(p.fr_partial + ((int64_t)(s0 + u) * p.batch + b) * N + n)
+                   : make_float2(0.f, 0.f);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { a0 += v[u].x; a1 += v[u].y; }
+    }
+    if (n < NE) {                                          // pair index pr = h * r + j
+      const float2 sc = p.fr_sincos[(int64_t)b * (NE / 2) + pr];
+      const float o0 = a0 * sc.y - a1 * sc.x, o1 = a1 * sc.y + a0 * sc.x;
+      a0 = o0; a1 = o1;
+    }
+    const uint32_t pk = pack_bf16x2(a0, a1);
+    row[n] = __uint_as_float(pk << 16);
+    row[n + 1] = __uint_as_float(pk & 0xffff0000u);
+    if (store) {
+      if (n < NE) *reinterpret_cast<uint32_t*>(p.fr_ke_out + slot * NE + n) = pk;
+      else *reinterpret_cast<uint32_t*>(p.fr_c_out + slot * (int64_t)p.d_c + (n - NE)) = pk;
+    }
+  }
+  __syncthreads();
+  int64_t len = p.seq_len[b];                              // clamped as the tile work-groups clamp it
+  len = min(len, p.max_seq_len);
+  len = min(len, p.plane_rows - (int64_t)(b / p.q_per_seq) * p.batch_stride_rows);
+  const bool attended = len > 0;
+  const int64_t pbase = ((int64_t)b * p.n_part + p.n_splits) * (p.head_groups * 32) + hg * 32;
+  const float* crow = row + NE;
+  for (int hh = wave; hh < 32; hh += NT / 64) {
+    const int head = hg * 32 + hh;
+    if (head >= p.n_h) continue;                           // uniform over the wave
+    float acc = 0.f;
+    const bf16_t* qrow = p.qt + ((int64_t)b * p.n_h + head) * p.d_q;
+    for (int k = lane * 8; k < p.d_q; k += 512) {
+      const uint4 qv = *reinterpret_cast<const uint4*>(qrow + k);
+      const uint32_t qq[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc = fmaf(__uint_as_float(qq[i] << 16), crow[k + 2 * i], acc);
+        acc = fmaf(__uint_as_float(qq[i] & 0xffff0000u), crow[k + 2 * i + 1], acc);
+      }
+    }
+    if (lane < TWO_R) acc = fmaf(p.qe[((int64_t)b * p.n_h + head) * TWO_R + lane], row[head * TWO_R + lane], acc);
+    acc = wave_sum(acc);
+    if (lane == 0) {
+      p.part_m[pbase + hh] = attended ? acc : -INFINITY;
+      p.part_l[pbase + hh] = attended ? 1.f : 0.f;
+    }
+    bf16_t* urow = p.part_u + (pbase + hh) * (int64_t)p.d_u;
+    const float* vrow = crow + (p.d_c - p.d_u);
+    for (int k = lane * 8; k < p.d_u; k += 512) {
+      uint4 o = make_uint4(0, 0, 0, 0);
+      if (attended) {
+        o.x = pack_bf16x2(vrow[k], vrow[k + 1]);     o.y = pack_bf16x2(vrow[k + 2], vrow[k + 3]);
+        o.z = pack_bf16x2(vrow[k + 4], vrow[k + 5]); o.w = pack_bf16x2(vrow[k + 6], vrow[k + 7]);
+      }
+      *reinterpret_cast<uint4*>(urow + k) = o;
+    }
+  }
+}
+
 // SEP = separated latents (Section 3.2, S-LRD): a cache row is [c^k (d_q columns) | c^v (d_u columns)];
 // the waves whose slice lies in c^k only compute scores, the waves whose slice lies in c^v only
 // accumulate values (d_q is a multiple of DC_W).  SEP = false is the joint latent: every wave does both.
@@ -153,10 +246,15 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
     // that XCD's L2 instead of fetching it from HBM again.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int item = (slot >> 1) * 8 + xcd;
-    if (item >= p.n_splits * p.batch) return;
+    const int per_row = p.n_splits + p.fresh;            // the new-token work-groups are items too
+    if (item >= per_row * p.batch) return;
     hg = slot & 1;
-    split = item % p.n_splits;
-    b = item / p.n_splits;
+    split = item % per_row;
+    b = item / per_row;
+  }
+  if (split >= p.n_splits) {                             // only in a fused decode step
+    new_token_role<NW * 64, TWO_R>(p, hg, b, smem);
+    return;
   }
   char* ctile0 = smem + wave * L::WTILE;                 // buffer 0; buffer 1 is TILE_BYTES further
   char* ketile0 = smem + L::KE_OFF + wave * L::KE_W;     // buffer 0; buffer 1 (if any) is KE_BYTES further
@@ -168,13 +266,14 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   len = min(len, p.max_seq_len);
   len = min(len, p.plane_rows - row0);
   len = max(len, (int64_t)0);
+  if (p.fresh) len = max(len - 1, (int64_t)0);           // the newest token comes from the new-token role
   // Split s takes the 16-token tiles s, s + n_splits, s + 2 n_splits, ...: at any moment the
   // work-groups of a batch row read one contiguous window of the planes that moves through the
   // sequence (DRAM-page friendly); the softmax does not care about token order.
   const int64_t t0 = (int64_t)split * kTile;
   const int64_t t_end = len;
   const int64_t t_step = (int64_t)p.n_splits * kTile;
-  const int64_t pidx = ((int64_t)b * p.n_splits + split) * (p.head_groups * 32) + hg * 32;
+  const int64_t pidx = ((int64_t)b * p.n_part + split) * (p.head_groups * 32) + hg * 32;
 
   if (t0 >= t_end) {   // empty split: weight 0 in the merge (l == 0), accumulator rows zeroed
     if (wave == 0 && g == 0) {
@@ -499,8 +598,9 @@ static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t 
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  const dim3 grid = prm.pair_map ? dim3((unsigned)((prm.n_splits * B + 7) / 8 * 16), 1, 1)
-                                 : dim3(prm.n_splits, prm.head_groups, (unsigned)B);
+  const int per_row = prm.n_splits + prm.fresh;     // + the new-token work-group of a fused decode step
+  const dim3 grid = prm.pair_map ? dim3((unsigned)((per_row * B + 7) / 8 * 16), 1, 1)
+                                 : dim3(per_row, prm.head_groups, (unsigned)B);
   attn_mfma_kernel<NW, DC_W, TWO_R, SEP><<<grid, NW * 64, L::LDS_BYTES, stream>>>(prm);
   return hipGetLastError();
 }
@@ -557,6 +657,14 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
   prm.batch = (int)a.B; prm.pair_map = p.head_groups == 2 ? 1 : 0;
   prm.d_q = p.d_q; prm.d_u = p.d_u; prm.q_per_seq = a.q_per_seq;
+  prm.n_part = p.n_part; prm.fresh = p.fresh;
+  prm.fr_partial = nullptr; prm.fr_sincos = nullptr; prm.fr_slot = nullptr; prm.fr_ks = 0;
+  prm.fr_ke_out = nullptr; prm.fr_c_out = nullptr;
+  if (p.fresh) {
+    prm.fr_partial = (const float*)(a.ws + p.off_apart); prm.fr_sincos = (const float2*)(a.ws + p.off_sincos);
+    prm.fr_slot = a.fr_slot; prm.fr_ks = p.fr_ks;
+    prm.fr_ke_out = (bf16_t*)a.fr_ke_out; prm.fr_c_out = (bf16_t*)a.fr_c_out;
+  }
 
   hipError_t e = hipSuccess;
   if (a.stages & 1) e = launch_qprep_rows(a, p, qe, qt, stream);

@@ -1,0 +1,89 @@
+// Front kernel of the fused decode step.  The step's two first pieces of work do not depend on each
+// other: the cache append of the step's tokens (x [W_ke | W_dkv]; Sections 3.1 and 3.2) and the
+// query preparation (rotated elite query, W_uk absorbed into the rest; Section 3.1 score equation,
+// Section 5).  Both are a single pass over a weight matrix of a few megabytes, far too short to
+// amortise a launch each, so one launch runs both: the first work-groups take the rows of W_uk, the
+// others the (column block, contraction split) pieces of the append.  The append's split sums are
+// added up, rotated and stored by the new-token work-groups of the attention kernel that follows in
+// the stream (they need the prepared query anyway), so the step has no separate finishing launch.
+#include "common.hpp"
+#include "launch.hpp"
+#include "append_small.hpp"
+#include "qprep_rows.hpp"
+
+namespace ekv {
+
+QprepRowsParams make_qprep_rows_params(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt);
+
+constexpr int kFrontBatch = 16;   // weight rows per thread in flight in the append role
+
+// token / batch-row tile (template parameter) that covers B rows
+static int front_tile(int64_t B) { return B == 1 ? 1 : B == 2 ? 2 : B <= 4 ? 4 : 8; }
+
+// BT = token / batch-row tile of both roles (the step appends one token per batch row)
+template <int BT>
+__global__ __launch_bounds__(256) void decode_front_kernel(const AppendSmallParams A, const QprepRowsParams Q,
+                                                           const RopeTable rope, int n_qprep, int n_blocks) {
+  extern __shared__ __attribute__((aligned(16))) char fsm[];
+  static_assert(kAsThreads == 256 && kQpThreads == 256, "both roles use 256 threads");
+  const int wg = blockIdx.x;
+  if (wg < n_qprep) {
+    qprep_rows_body<BT>(Q, rope, wg, n_qprep, 0, fsm);
+  } else {
+    const int e = wg - n_qprep;
+    append_small_body<BT, kFrontBatch>(A, e % n_blocks, e / n_blocks, 0, reinterpret_cast<float*>(fsm));
+  }
+}
+
+bool decode_front_plan(const elitekv_dims& d, int d_ck, int d_q, int64_t B, int* ks_out, int* kc_out) {
+  if (d.dtype != ELITEKV_BF16 || B < 1 || B > kAsTokens) return false;
+  if (qprep_mfma_supported(d, d_q, B)) return false;                 // eight rows and up: matrix-core kernels
+  const int nd = d.head_dim - 2 * d.r;
+  if (d.r < 1 || nd < 8 || nd % 8 || d.head_dim > 128) return false;
+  if (!append_small_supported(d, B, d_ck > 0 ? d_ck : d.d_c)) return false;
+  const size_t lds = qprep_rows_lds(d.n_heads, d.head_dim, d.r, front_tile(B));
+  if (lds > 150 * 1024) return false;
+  // contraction splits: as many as keep every work-group of the launch resident at once
+  const int resident = 256 * (lds + 2048 <= 80 * 1024 ? 2 : 1);
+  const int n_qprep = (int)(((int64_t)d_q * d.n_heads + kQpThreads - 1) / kQpThreads) + 1;
+  const int n_blocks = (2 * d.r * d.n_heads + d.d_c) / kAsCols;
+  int ks = 16;
+  while (ks > 2 && (n_qprep + n_blocks * ks > resident || (d.d_model + ks - 1) / ks < 64)) ks >>= 1;
+  int kc = (d.d_model + ks - 1) / ks;
+  kc = (kc + 31) / 32 * 32;
+  *ks_out = ks; *kc_out = kc;
+  return true;
+}
+
+template <int BT>
+static hipError_t launch_front_bt(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  const size_t sm_a = (size_t)p.fr_kc * BT * sizeof(float), sm_q = qprep_rows_lds(d.n_heads, d.head_dim, d.r, BT);
+  const size_t sm = sm_a > sm_q ? sm_a : sm_q;
+  static size_t sm_set = 60 * 1024;   // raising the dynamic-LDS limit is idempotent; done once per size
+  if (sm > sm_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_front_kernel<BT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    if (e != hipSuccess) return e;
+    sm_set = sm;
+  }
+  const int NE = 2 * d.r * d.n_heads;
+  AppendSmallParams A;
+  A.x = (const bf16_t*)ap.x; A.T = ap.T; A.W_ke = (const bf16_t*)ap.W_ke; A.W_dkv = (const bf16_t*)ap.W_dkv;
+  A.W_dkv2 = (const bf16_t*)ap.W_dkv2; A.partial = (float*)(a.ws + p.off_apart); A.d_ck = ap.d_ck; A.d = d.d_model;
+  A.NE = NE; A.d_c = d.d_c; A.kc = p.fr_kc;
+  const int n_blocks = (NE + d.d_c) / kAsCols;
+  const int n_qprep = (int)(((int64_t)p.d_q * d.n_heads + kQpThreads - 1) / kQpThreads) + 1;   // + the rotation group
+  decode_front_kernel<BT><<<n_qprep + n_blocks * p.fr_ks, 256, sm, stream>>>(
+      A, make_qprep_rows_params(a, p, (float*)(a.ws + p.off_qe), (bf16_t*)(a.ws + p.off_qt)),
+      make_rope_table(d.rope_base, d.head_dim), n_qprep, n_blocks);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_front(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
+  const int bt = front_tile(a.B);
+  return bt == 1 ? launch_front_bt<1>(ap, a, p, stream) : bt == 2 ? launch_front_bt<2>(ap, a, p, stream)
+       : bt == 4 ? launch_front_bt<4>(ap, a, p, stream) : launch_front_bt<8>(ap, a, p, stream);
+}
+
+}  // namespace ekv

@@ -37,8 +37,9 @@ static int32_t auto_splits_generic(const elitekv_dims* d, int64_t B, int64_t max
 
 // Decide the path and lay the workspace out.  Returns a status.
 // d_ck = 0: joint latent; d_ck > 0: separated latents, a cache row is [c^k (d_ck) | c^v (d_c - d_ck)]
+// want_fresh: plan the fused decode step (the newest token enters as one more split) if the kernels cover it
 static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t max_seq, int32_t n_splits,
-                       DecodePlan* p) {
+                       DecodePlan* p, bool want_fresh = false) {
   int st = check_dims(d);
   if (st) return st;
   if (B < 0 || max_seq < 0 || n_splits < 0) return ELITEKV_EINVAL;
@@ -58,6 +59,10 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     // one work-group per (split, group of 32 heads, batch row); one group fills a compute unit
     p->mfma = 1;
     p->head_groups = (d->n_heads + 31) / 32;
+    int ks = 0, kc = 0;
+    if (want_fresh && B > 0 && decode_front_plan(*d, d_ck, p->d_q, B, &ks, &kc)) {
+      p->fresh = 1; p->fr_ks = ks; p->fr_kc = kc;
+    }
     int64_t ns = n_splits;
     if (ns == 0) {
       // the narrow-latent instantiations run two work-groups per compute unit; with many batch rows
@@ -68,25 +73,35 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
       const int64_t cap = (seq + 15) / 16;
       if (ns > cap) ns = cap;
       if (ns > kMaxSplits) ns = kMaxSplits;
+      if (p->fresh && ns > 1) --ns;            // the new-token work-group takes a compute unit of its own
       if (ns < 1) ns = 1;
     }
+    if (p->fresh && ns + 1 > kMaxSplits) return ELITEKV_EUNSUPPORTED;
     p->n_splits = (int32_t)ns;
+    p->n_part = (int32_t)ns + p->fresh;
     int64_t chunk = (seq + ns - 1) / ns;
     chunk = (chunk + 31) / 32 * 32;
     p->chunk = (int32_t)chunk;
-    const size_t np = Bz * (size_t)ns * p->head_groups;
+    const size_t np = Bz * (size_t)p->n_part * p->head_groups;
     p->off_qt = off; off = align_up(off + Bz * nh * dq * 2, 256);
     p->off_m = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_l = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_u = off;  off = align_up(off + np * 32 * du * 2, 256);
-    p->merge_batch = merge_batch_supported(*d, p->d_u, B, ns) ? 1 : 0;
+    p->merge_batch = merge_batch_supported(*d, p->d_u, B, p->n_part) ? 1 : 0;
     p->up_cw = p->merge_batch ? 128 : (p->d_u % 192 == 0) ? 192 : 64;
     p->off_opart = off;
     off = align_up(off + Bz * nh * (size_t)(p->d_u / p->up_cw) * d->head_dim * sizeof(float), 256);
+    if (p->fresh) {
+      p->off_apart = off;
+      off = align_up(off + (size_t)p->fr_ks * Bz * (size_t)(2 * d->r * d->n_heads + d->d_c) * sizeof(float), 256);
+      p->off_sincos = off;
+      off = align_up(off + Bz * nh * (size_t)d->r * 2 * sizeof(float), 256);
+    }
   } else {
     p->mfma = 0;
     p->head_groups = 1;
     p->n_splits = n_splits > 0 ? n_splits : auto_splits_generic(d, Bq, seq);
+    p->n_part = p->n_splits;
     int64_t chunk = (seq + p->n_splits - 1) / p->n_splits;
     if (chunk < 1) chunk = 1;
     p->chunk = (int32_t)chunk;
@@ -183,10 +198,11 @@ static size_t append_ws_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t T)
   return 0;
 }
 
-static int append_impl(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
-                       const int64_t* slot, int64_t T, const void* W_ke, const void* W_dkv, const void* W_dkv2,
-                       const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows, void* ws,
-                       size_t ws_bytes, void* hip_stream) {
+// argument checks of an append; ws_needed = 0 skips the workspace check
+static int append_check(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                        const int64_t* slot, int64_t T, const void* W_ke, const void* W_dkv, const void* W_dkv2,
+                        const int32_t* elite_idx, const void* ke_plane, const void* c_plane, int64_t plane_rows,
+                        const void* ws, size_t ws_bytes, size_t ws_needed) {
   int st = check_dims(dims);
   if (st) return st;
   if (T < 0 || plane_rows < 0 || d_ck <= 0 || d_ck > dims->d_c) return ELITEKV_EINVAL;
@@ -197,20 +213,40 @@ static int append_impl(const elitekv_dims* dims, int32_t d_ck, const void* x, co
   if (!aligned16(x) || !aligned16(W_dkv) || !aligned16(W_dkv2) || !aligned16(c_plane) || !aligned16(W_ke) ||
       !aligned16(ke_plane) || !aligned16(ws))
     return ELITEKV_EALIGN;
-  const size_t need = append_ws_bytes(dims, d_ck, T);
-  if (need > 0 && (!ws || ws_bytes < need)) return ws ? ELITEKV_EWORKSPACE : ELITEKV_ENULL;
+  if (ws_needed > 0 && (!ws || ws_bytes < ws_needed)) return ws ? ELITEKV_EWORKSPACE : ELITEKV_ENULL;
   if ((T + 7) / 8 > 2147483647LL) return ELITEKV_EUNSUPPORTED;
+  return ELITEKV_OK;
+}
 
+static AppendArgs append_args(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                              const int64_t* slot, int64_t T, const void* W_ke, const void* W_dkv,
+                              const void* W_dkv2, const int32_t* elite_idx, void* ke_plane, void* c_plane,
+                              int64_t plane_rows, void* ws) {
   AppendArgs a;
   a.dims = *dims; a.d_ck = d_ck; a.x = x; a.pos = pos; a.slot = slot; a.T = T; a.W_ke = W_ke; a.W_dkv = W_dkv;
   a.W_dkv2 = W_dkv2; a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane;
   a.plane_rows = plane_rows; a.ws = (char*)ws;
-  const hipStream_t stream = (hipStream_t)hip_stream;
-  const hipError_t e = append_gemm_supported(*dims, T, d_ck)     ? launch_append_gemm(a, stream)
-                       : append_skinny_supported(*dims, T, d_ck) ? launch_append_skinny(a, stream)
-                       : append_small_supported(*dims, T, d_ck)  ? launch_append_small(a, stream)
-                                                                 : launch_append_generic(a, stream);
-  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+  return a;
+}
+
+static hipError_t append_dispatch(const AppendArgs& a, hipStream_t stream) {
+  const elitekv_dims* dims = &a.dims;
+  return append_gemm_supported(*dims, a.T, a.d_ck)     ? launch_append_gemm(a, stream)
+         : append_skinny_supported(*dims, a.T, a.d_ck) ? launch_append_skinny(a, stream)
+         : append_small_supported(*dims, a.T, a.d_ck)  ? launch_append_small(a, stream)
+                                                       : launch_append_generic(a, stream);
+}
+
+static int append_impl(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                       const int64_t* slot, int64_t T, const void* W_ke, const void* W_dkv, const void* W_dkv2,
+                       const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows, void* ws,
+                       size_t ws_bytes, void* hip_stream) {
+  const int st = append_check(dims, d_ck, x, pos, slot, T, W_ke, W_dkv, W_dkv2, elite_idx, ke_plane, c_plane,
+                              plane_rows, ws, ws_bytes, dims ? append_ws_bytes(dims, d_ck, T) : 0);
+  if (st || T == 0) return st;
+  const AppendArgs a = append_args(dims, d_ck, x, pos, slot, T, W_ke, W_dkv, W_dkv2, elite_idx, ke_plane,
+                                   c_plane, plane_rows, ws);
+  return append_dispatch(a, (hipStream_t)hip_stream) == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
 }
 
 size_t elitekv_append_workspace_bytes(const elitekv_dims* dims, int64_t T) {
@@ -239,15 +275,10 @@ size_t elitekv_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64
   return p.total;
 }
 
-static int decode_impl(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
-                       const int32_t* seq_len, int64_t B, int64_t max_seq_len,
-                       int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
-                       const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
-                       int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
-                       void* hip_stream, int32_t stages, int32_t q_per_seq = 1) {
-  DecodePlan p;
-  int st = plan_decode(dims, d_ck, B, max_seq_len, n_splits, &p);
-  if (st) return st;
+static int decode_check(const elitekv_dims* dims, const DecodePlan& p, const void* q, const int32_t* q_pos,
+                        const int32_t* seq_len, int64_t B, int64_t batch_stride_rows, const void* W_uk,
+                        const void* W_uv, const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                        int64_t plane_rows, const void* out, const void* ws, size_t ws_bytes) {
   if (batch_stride_rows < 0 || plane_rows < 0) return ELITEKV_EINVAL;
   if (B == 0) return ELITEKV_OK;
   if (B > 65535) return ELITEKV_EUNSUPPORTED;
@@ -258,15 +289,120 @@ static int decode_impl(const elitekv_dims* dims, int32_t d_ck, const void* q, co
       !aligned16(c_plane) || !aligned16(out) || !aligned16(ws))
     return ELITEKV_EALIGN;
   if (ws_bytes < p.total) return ELITEKV_EWORKSPACE;
+  return ELITEKV_OK;
+}
 
+static DecodeArgs decode_args(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                              const int32_t* seq_len, int64_t B, int64_t max_seq_len, int64_t batch_stride_rows,
+                              const void* W_uk, const void* W_uv, const int32_t* elite_idx, const void* ke_plane,
+                              const void* c_plane, int64_t plane_rows, void* out, void* ws, int32_t stages,
+                              int32_t q_per_seq) {
   DecodeArgs a;
   a.dims = *dims; a.d_ck = d_ck; a.q = q; a.q_pos = q_pos; a.seq_len = seq_len; a.B = B;
   a.max_seq_len = max_seq_len; a.batch_stride_rows = batch_stride_rows; a.W_uk = W_uk; a.W_uv = W_uv;
   a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows; a.out = out;
   a.ws = (char*)ws; a.stages = stages; a.q_per_seq = q_per_seq;
+  a.fr_slot = nullptr; a.fr_ke_out = nullptr; a.fr_c_out = nullptr;
+  return a;
+}
+
+static int decode_impl(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                       const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                       int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                       const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                       int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                       void* hip_stream, int32_t stages, int32_t q_per_seq = 1) {
+  DecodePlan p;
+  int st = plan_decode(dims, d_ck, B, max_seq_len, n_splits, &p);
+  if (st) return st;
+  st = decode_check(dims, p, q, q_pos, seq_len, B, batch_stride_rows, W_uk, W_uv, elite_idx, ke_plane, c_plane,
+                    plane_rows, out, ws, ws_bytes);
+  if (st || B == 0) return st;
+  const DecodeArgs a = decode_args(dims, d_ck, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv,
+                                   elite_idx, ke_plane, c_plane, plane_rows, out, ws, stages, q_per_seq);
   const hipError_t e = p.mfma ? launch_decode_mfma(a, p, (hipStream_t)hip_stream)
                              : launch_decode_generic(a, p, (hipStream_t)hip_stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+/* ---- fused decode step: append of the step's tokens + attention ---- */
+
+// workspace = [decode workspace (with the fused step's extra pieces) | append workspace of B tokens]
+static size_t step_ws_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t max_seq_len, int32_t n_splits) {
+  DecodePlan p;
+  if (plan_decode(dims, d_ck, B, max_seq_len, n_splits, &p, true)) return 0;
+  return p.total + (p.fresh ? 0 : append_ws_bytes(dims, d_ck > 0 ? d_ck : dims->d_c, B));
+}
+
+static int step_impl(const elitekv_dims* dims, int32_t d_ck, const void* x, const void* q, const int32_t* pos,
+                     const int64_t* slot, const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                     int64_t batch_stride_rows, const void* W_ke, const void* W_dkv, const void* W_dkv2,
+                     const void* W_uk, const void* W_uv, const int32_t* elite_idx, void* ke_plane, void* c_plane,
+                     int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits, void* hip_stream) {
+  DecodePlan p;
+  int st = plan_decode(dims, d_ck, B, max_seq_len, n_splits, &p, true);
+  if (st) return st;
+  const int32_t a_ck = d_ck > 0 ? d_ck : dims->d_c;          // columns of the first latent weight matrix
+  st = append_check(dims, a_ck, x, pos, slot, B, W_ke, W_dkv, W_dkv2, elite_idx, ke_plane, c_plane, plane_rows, ws,
+                    ws_bytes, 0);
+  if (st) return st;
+  st = decode_check(dims, p, q, pos, seq_len, B, batch_stride_rows, W_uk, W_uv, elite_idx, ke_plane, c_plane,
+                    plane_rows, out, ws, ws_bytes);
+  if (st || B == 0) return st;
+  const size_t need = p.total + (p.fresh ? 0 : append_ws_bytes(dims, a_ck, B));
+  if (ws_bytes < need) return ELITEKV_EWORKSPACE;
+  const hipStream_t stream = (hipStream_t)hip_stream;
+  const AppendArgs ap = append_args(dims, a_ck, x, pos, slot, B, W_ke, W_dkv, W_dkv2, elite_idx, ke_plane, c_plane,
+                                    plane_rows, (char*)ws + p.total);
+  DecodeArgs a = decode_args(dims, d_ck, q, pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+                             ke_plane, c_plane, plane_rows, out, ws, 7, 1);
+  hipError_t e;
+  if (p.fresh) {
+    // front kernel (first pass of the append + query preparation), then attention (whose new-token
+    // work-groups finish the append), merge and up-projection
+    a.fr_slot = slot; a.fr_ke_out = ke_plane; a.fr_c_out = c_plane;
+    e = launch_decode_front(ap, a, p, stream);
+    a.stages = 6;
+    if (e == hipSuccess) e = launch_decode_mfma(a, p, stream);
+  } else {
+    e = append_dispatch(ap, stream);
+    if (e == hipSuccess) e = p.mfma ? launch_decode_mfma(a, p, stream) : launch_decode_generic(a, p, stream);
+  }
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+size_t elitekv_decode_step_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
+                                           int32_t n_splits) {
+  return step_ws_bytes(dims, 0, B, max_seq_len, n_splits);
+}
+
+int elitekv_decode_step(const elitekv_dims* dims, const void* x, const void* q, const int32_t* pos,
+                        const int64_t* slot, const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                        int64_t batch_stride_rows, const void* W_ke, const void* W_dkv, const void* W_uk,
+                        const void* W_uv, const int32_t* elite_idx, void* ke_plane, void* c_plane,
+                        int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                        void* hip_stream) {
+  if (!dims) return ELITEKV_ENULL;
+  return step_impl(dims, 0, x, q, pos, slot, seq_len, B, max_seq_len, batch_stride_rows, W_ke, W_dkv, nullptr, W_uk,
+                   W_uv, elite_idx, ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream);
+}
+
+size_t elitekv_slrd_decode_step_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B,
+                                                int64_t max_seq_len, int32_t n_splits) {
+  if (!dims || d_ck <= 0 || d_ck >= dims->d_c) return 0;
+  return step_ws_bytes(dims, d_ck, B, max_seq_len, n_splits);
+}
+
+int elitekv_slrd_decode_step(const elitekv_dims* dims, int32_t d_ck, const void* x, const void* q,
+                             const int32_t* pos, const int64_t* slot, const int32_t* seq_len, int64_t B,
+                             int64_t max_seq_len, int64_t batch_stride_rows, const void* W_ke, const void* A_k,
+                             const void* A_v, const void* B_k, const void* B_v, const int32_t* elite_idx,
+                             void* ke_plane, void* c_plane, int64_t plane_rows, void* out, void* ws,
+                             size_t ws_bytes, int32_t n_splits, void* hip_stream) {
+  if (!dims) return ELITEKV_ENULL;
+  if (d_ck <= 0 || d_ck >= dims->d_c) return ELITEKV_EINVAL;
+  return step_impl(dims, d_ck, x, q, pos, slot, seq_len, B, max_seq_len, batch_stride_rows, W_ke, A_k, A_v, B_k,
+                   B_v, elite_idx, ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream);
 }
 
 /* ---- RoPElite search ---- */

@@ -25,6 +25,14 @@ struct DecodePlan {
   size_t off_l;         // split sums                       fp32 [B, n_splits, n_h_pad]
   size_t off_u;         // split latent accumulators        fp32 [B, n_splits, ...]
   size_t off_opart;     // up-projection partials           fp32
+  // fused decode step (fresh = 1): the newest token of every sequence reaches the attention as one more
+  // split, built from the append's contraction-split sums inside the attention kernel
+  int32_t fresh;
+  int32_t n_part;       // partials per batch row: n_splits + fresh
+  int32_t fr_ks;        // contraction splits of the step's append
+  int32_t fr_kc;        // ... rows of the weight matrices per split (a multiple of 32)
+  size_t off_apart;     // the append's split sums           fp32 [fr_ks, B, 2 r n_h + d_c]
+  size_t off_sincos;    // (sin, cos) of the rotated chunks  fp32 [B, n_h r, 2]
   size_t total;
 };
 
@@ -45,6 +53,10 @@ struct DecodeArgs {
   char* ws;
   int32_t q_per_seq;                // queries per sequence: row b of q belongs to sequence b / q_per_seq
   int32_t stages;                   // bit 0 q-prep, bit 1 split attention, bit 2 merge + up-projection
+  // fused decode step only: destination rows of the new tokens and the planes, writable
+  const int64_t* fr_slot;
+  void* fr_ke_out;
+  void* fr_c_out;
 };
 
 struct AppendArgs {
@@ -94,6 +106,12 @@ int decode_mfma_groups_per_cu(const elitekv_dims& d);
 struct bf16_t;
 hipError_t launch_qprep_rows(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt,
                              hipStream_t stream);
+bool qprep_mfma_supported(const elitekv_dims& d, int d_q, int64_t B);
+// Fused decode step: its front kernel runs the first pass of the append of the step's B tokens and the
+// query preparation in one launch.  decode_front_plan says whether the kernels cover the shape and
+// how the append's contraction is split (ks splits of kc weight rows).
+bool decode_front_plan(const elitekv_dims& d, int d_ck, int d_q, int64_t B, int* ks, int* kc);
+hipError_t launch_decode_front(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 bool merge_batch_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits);
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
