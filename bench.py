@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
 # by the readings of a plain copy of known size (profiles/attn_mfma_<workload>.md); workloads that
 # have not been counted report null.
-TRAFFIC_BYTES = {"7b_25_b1_s32768": 160.4e6, "7b_25_b8_s4096": 166.1e6, "13b_25_b16_s8192": 737.6e6,
-                 "7b_12_b64_s2048": 294.2e6, "7b_25_slrd_b1_s32768": 150.5e6, "7b_25_slrd_b8_s4096": 150.4e6}
+TRAFFIC_BYTES = {"7b_25_b1_s32768": 160.5e6, "7b_25_b8_s4096": 166.1e6, "13b_25_b16_s8192": 725.3e6,
+                 "7b_12_b64_s2048": 319.6e6, "7b_25_slrd_b1_s32768": 150.6e6, "7b_25_slrd_b8_s4096": 150.4e6}
 METRIC = "decode attn HBM GB/s (% of peak) + tokens/s, 7B shape 25% cache, 32K ctx"
 
 
@@ -67,7 +67,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="7b_25_b1_s32768")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-comparators", action="store_true")
+    ap.add_argument("--no-comparators", action="store_true",
+                    help="only the decode step: skip the comparators and the multiquery / search / prefill fields")
+    ap.add_argument("--no-multiquery", action="store_true",
+                    help="skip the multiquery field (it launches the attention kernel in another configuration)")
     ap.add_argument("--splits", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -232,7 +235,7 @@ def main():
     if not args.no_comparators:
         result["comparators"] = comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream,
                                             cache_bytes, args)
-        if not d_ck:
+        if not d_ck and not args.no_multiquery:
             result["multiquery"] = multiquery(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
                                               cache_bytes)
         result["ropelite_search"] = ropelite_search(ekv, ev, cfg, dev, stream)

@@ -188,3 +188,28 @@ def test_multiquery_argument_errors():
     need = ekv.elitekv_multiquery_workspace_bytes(d, 2, 3, 128)
     assert need == ekv.elitekv_decode_workspace_bytes(d, 6, 128)       # B*T query rows
     assert mq(wsb=need - 1) == ekv.EWORKSPACE
+
+
+def test_decode_step_argument_errors():
+    d = _dims()
+    step = lambda **kw: lib.elitekv_decode_step(
+        C.byref(d), kw.get("x", FAKE), kw.get("q", FAKE), FAKE, kw.get("slot", FAKE), FAKE, kw.get("B", 1), 128, 128,
+        FAKE, FAKE, FAKE, kw.get("W_uv", FAKE), FAKE, FAKE, FAKE, 128, FAKE, FAKE, kw.get("wsb", 1 << 30), 0, None)
+    assert step(B=0) == ekv.OK
+    assert step(B=-1) == ekv.EINVAL
+    assert step(x=None) == ekv.ENULL and step(q=None) == ekv.ENULL and step(slot=None) == ekv.ENULL
+    assert step(W_uv=FAKE + 4) == ekv.EALIGN
+    need = ekv.elitekv_decode_step_workspace_bytes(d, 1, 128)
+    assert need > 0 and step(wsb=need - 1) == ekv.EWORKSPACE
+    # the step's workspace holds the attention's and what the append needs on top
+    big = ekv.make_dims(4096, 32, 128, 8, 1536, "bf16")
+    for B in (1, 4, 8, 64):
+        assert ekv.elitekv_decode_step_workspace_bytes(big, B, 4096) >= ekv.elitekv_decode_workspace_bytes(big, B, 4096)
+    dc = d.d_c
+    sstep = lambda d_ck, **kw: lib.elitekv_slrd_decode_step(
+        C.byref(d), d_ck, FAKE, FAKE, FAKE, FAKE, FAKE, kw.get("B", 1), 128, 128, FAKE, FAKE, kw.get("A_v", FAKE), FAKE,
+        FAKE, FAKE, FAKE, FAKE, 128, FAKE, FAKE, 1 << 30, 0, None)
+    assert sstep(0) == ekv.EINVAL and sstep(dc) == ekv.EINVAL
+    assert sstep(dc // 2, B=0) == ekv.OK
+    assert sstep(dc // 2, A_v=None) == ekv.ENULL
+    assert ekv.elitekv_slrd_decode_step_workspace_bytes(d, 0, 1, 128) == 0

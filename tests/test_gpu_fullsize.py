@@ -1,7 +1,8 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (automatic
 split count, same strides): the planes are built by the library's own append from seeded hidden
 states, append is checked on sampled rows and decode on sampled (batch row, head) outputs, each
-computed one by one by the float64 oracle from exactly the planes the GPU reads.
+computed one by one by the float64 oracle from exactly the planes the GPU reads; then one decode
+step through the single-call entry point is checked the same way.
 """
 import numpy as np
 import pytest
@@ -79,6 +80,33 @@ def test_full_size_append_and_decode(name):
             gots.append(out[b, h])
     err = orc.max_abs_rel(np.stack(gots), np.stack(refs))
     assert err <= TOL[dt], "max-abs-rel %g" % err
+
+    # one decode step through the single-call entry point, as bench.py times it: a new token per
+    # sequence replaces the last cached row and the query attends to all S tokens
+    x_new = synth.draw_hidden(synth.rng_for(cfg.index, stream=9), B, d)
+    xnd = dev(x_new, dt)
+    slot_new = np.arange(B) * S + (S - 1)
+    out2 = torch.full((B, n_h, d_h), float("nan"), dtype=ekv.torch_dtype(dims), device=DEV)
+    sws = torch.full((ekv.elitekv_decode_step_workspace_bytes(dims, B, S),), 0xFF, dtype=torch.uint8, device=DEV)
+    ekv.elitekv_decode_step(dims, xnd, qd, i32(q_pos), i64(slot_new), i32(seq), S, S, Wked, Wdkvd, Wukd, Wuvd, idxd,
+                            ke, c, out2, sws)
+    torch.cuda.synchronize()
+    out2 = host64(out2)
+    assert np.all(np.isfinite(out2))
+    refs, gots = [], []
+    for b in rows_s:
+        ke_ref, c_ref = orc.append(host64(xnd[b:b + 1]), np.array([S - 1]), Wke64, Wdkv64, idx, d_h, cfg.rope_base)
+        assert orc.max_abs_rel(host64(c[slot_new[b]]), c_ref[0]) <= TOL[dt]
+        assert orc.max_abs_rel(host64(ke[slot_new[b]]), ke_ref[0]) <= TOL[dt]
+        ke_b = host64(ke[b * S:(b + 1) * S])
+        c_b = host64(c[b * S:(b + 1) * S])
+        ref = orc.decode_attn(q64[b:b + 1], [S - 1], [ke_b], [c_b], [S], Wuk64, Wuv64, idx, d_h, cfg.rope_base,
+                              heads=heads_s)
+        for h in heads_s:
+            refs.append(ref[0, h])
+            gots.append(out2[b, h])
+    err = orc.max_abs_rel(np.stack(gots), np.stack(refs))
+    assert err <= TOL[dt], "decode step: max-abs-rel %g" % err
 
 
 def test_prefill_append_with_wide_token_tiles():

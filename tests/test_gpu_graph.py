@@ -15,8 +15,8 @@ from test_gpu_parity import _draw, shape
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("B", [1, 8])
-def test_append_and_decode_replay_from_a_graph(B):
+@pytest.mark.parametrize("B,fused", [(1, False), (8, False), (1, True), (3, True), (8, True)])
+def test_append_and_decode_replay_from_a_graph(B, fused):
     sh, S = shape(512, 32, 128, 8, 1536, "bf16"), 700
     rng, idx, W_ke, W_dkv, W_uk, W_uv, x, q = _draw(sh, B, B, 123 + B)
     dims = dims_of(sh)
@@ -31,7 +31,13 @@ def test_append_and_decode_replay_from_a_graph(B):
     ws = torch.empty(ekv.elitekv_decode_workspace_bytes(dims, B, S), dtype=torch.uint8, device=DEV)
     aws = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, B), 16), dtype=torch.uint8, device=DEV)
 
+    sws = torch.empty(ekv.elitekv_decode_step_workspace_bytes(dims, B, S), dtype=torch.uint8, device=DEV)
+
     def step(stream):
+        if fused:
+            ekv.elitekv_decode_step(dims, xd, qd, pos, slot, seq, S, S, Wked, Wdkvd, Wukd, Wuvd, idxd, ke, c, out, sws,
+                                    stream=stream)
+            return
         ekv.elitekv_append(dims, xd, pos, slot, Wked, Wdkvd, idxd, ke, c, ws=aws, stream=stream)
         ekv.elitekv_decode_attn(dims, qd, pos, seq, S, S, Wukd, Wuvd, idxd, ke, c, out, ws, stream=stream)
 
@@ -49,6 +55,7 @@ def test_append_and_decode_replay_from_a_graph(B):
     for rep in range(4):
         out.fill_(float("nan"))                            # eager work between the replays
         ws.fill_(0xFF)
+        sws.fill_(0xFF)
         c[slot] = 0
         torch.cuda.synchronize()
         graph.replay()
