@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true",
                     help="only the decode step: skip the comparators and the multiquery / search / prefill fields")
+    ap.add_argument("--prefill-tokens", type=int, default=2048,
+                    help="tokens of the append_prefill field (the matrix-core append)")
     ap.add_argument("--no-multiquery", action="store_true",
                     help="skip the multiquery field (it launches the attention kernel in another configuration)")
     ap.add_argument("--splits", type=int, default=0)
@@ -170,6 +172,16 @@ def main():
     ev.record(e1, stream)
     torch.cuda.synchronize()
     ms_per_step = ev.elapsed_ms(e0, e1) / args.steps
+    # four more regions of the same K steps: spread of the measurement (value comes from the first)
+    reps = [ms_per_step]
+    for _ in range(4):
+        ev.record(e0, stream)
+        for i in range(args.steps):
+            step(i)
+        ev.record(e1, stream)
+        torch.cuda.synchronize()
+        reps.append(ev.elapsed_ms(e0, e1) / args.steps)
+    reps.sort()
     # the same work through the two separate entry points (append, then attention), for reference
     for i in range(args.warmup):
         step_two_calls(i)
@@ -223,6 +235,7 @@ def main():
                    "n_splits": ekv.elitekv_decode_auto_splits(dims, B, S) if args.splits == 0 else args.splits},
         "pct_of_hbm_peak": round(100.0 * value_gbs / HBM_PEAK_GBS, 2),
         "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
+        "ms_per_step_median": round(reps[len(reps) // 2], 5), "ms_per_step_min": round(reps[0], 5),
         "ms_per_step_two_calls": round(ms_two_calls, 5),
         "roofline": {"bound": "hbm", "kernel": "split attention kernel of elitekv_decode_attn",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -239,7 +252,19 @@ def main():
             result["multiquery"] = multiquery(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
                                               cache_bytes)
         result["ropelite_search"] = ropelite_search(ekv, ev, cfg, dev, stream)
-        result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream)
+        result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream,
+                                                  T=args.prefill_tokens)
+        # the step against the roofline with everything it has to read once (cache + the four weight
+        # matrices), and against the measured streaming ceiling of this machine
+        other = 2 * (d * (2 * r * n_h + d_c) + (d_ck or d_c) * n_h * (d_h - 2 * r) + (d_c - d_ck) * n_h * d_h)
+        ceil_gbs = result["comparators"]["stream_read_GBs"]
+        result["fractions"] = {
+            "step_cache_bytes_of_peak": round(value_gbs / HBM_PEAK_GBS, 4),
+            "step_all_algorithmic_bytes_of_peak": round((cache_bytes + other) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "step_cache_bytes_of_stream_ceiling": round(value_gbs / ceil_gbs, 4),
+            "attention_kernel_of_peak": round(achieved / HBM_PEAK_GBS, 4),
+            "attention_kernel_of_stream_ceiling": round(achieved / ceil_gbs, 4),
+            "weight_bytes_per_step": other, "stream_ceiling_GBs": ceil_gbs}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, idx_h, W_ke_d, W_dkv_d, W_dkv2_d, W_uk_d, W_uv_d, q_d, x_d, host_planes0,
                                               cache_bytes)
