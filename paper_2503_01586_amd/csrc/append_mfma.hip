@@ -249,7 +249,7 @@ __device__ __forceinline__ void gemm_epilogue(am_f32x16 (&acc)[2][WN], int n0, i
             const int hh = n / (2 * r), jj = (n % (2 * r)) >> 1;
             int ch = elite_idx[hh * r + jj];
             ch = min(max(ch, 0), d_h / 2 - 1);
-            rope_sincos(p, rope.theta[ch], &sn, &cs);
+            rope_sincos_poly(p, rope.theta[ch], &sn, &cs);
             const float a0 = v0 * cs - v1 * sn, a1 = v0 * sn + v1 * cs;
             v0 = a0; v1 = a1;
           }
@@ -258,7 +258,7 @@ __device__ __forceinline__ void gemm_epilogue(am_f32x16 (&acc)[2][WN], int n0, i
             const int hh = n2 / (2 * r), jj = (n2 % (2 * r)) >> 1;
             int ch = elite_idx[hh * r + jj];
             ch = min(max(ch, 0), d_h / 2 - 1);
-            rope_sincos(p, rope.theta[ch], &sn, &cs);
+            rope_sincos_poly(p, rope.theta[ch], &sn, &cs);
             const float a2 = v2 * cs - v3 * sn, a3 = v2 * sn + v3 * cs;
             v2 = a2; v3 = a3;
           }
@@ -392,7 +392,9 @@ constexpr int kGdStage = 32;                    // contraction rows per stage
 constexpr int kGdA = 8 * 1024;                  // bytes of a weight stage
 
 __device__ __forceinline__ int gd_swz8(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
-__device__ __forceinline__ int gd_swz4(int row) { return (((row >> 1) & 1) << 1) | ((row >> 2) & 1); }
+// token blocks (16 rows x 64 bytes): a 16-byte read of 16 lanes = 16 rows at one logical piece; the four
+// rows r, r+4, r+8, r+12 that share a 64-byte bank window take four different pieces
+__device__ __forceinline__ int gd_swz4(int row) { return (row >> 2) & 3; }
 
 __device__ __forceinline__ void gd_dma16(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
@@ -408,6 +410,7 @@ struct GemmDmaLayout {
   static constexpr int LPW = LOADS / 4;                       // ... per wave
   static_assert(LOADS % 4 == 0, "the loads of a stage are divided evenly among the four waves");
   static_assert(LDS_BYTES <= 160 * 1024, "exceeds the LDS of a compute unit");
+  static_assert(NS >= 3 && NS <= 12 && (NS - 2) * LPW <= 63, "ring depth outside what the load counter can express");
 };
 
 template <int WN, int NS>
@@ -522,10 +525,10 @@ __global__ __launch_bounds__(256) void append_gemm_dma_kernel(
     // wait until this wave's loads of stage s have landed (the loads of `ahead` later stages may remain)
     switch (ahead) {
       case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-      case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(1 * L::LPW) : "memory"); break;
-      case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * L::LPW) : "memory"); break;
-      case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * L::LPW) : "memory"); break;
-      default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * L::LPW) : "memory"); break;
+#define EKV_WAIT(K) case K: if constexpr (K <= NS - 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(K * L::LPW) : "memory"); break;
+      EKV_WAIT(1) EKV_WAIT(2) EKV_WAIT(3) EKV_WAIT(4) EKV_WAIT(5) EKV_WAIT(6) EKV_WAIT(7) EKV_WAIT(8) EKV_WAIT(9) EKV_WAIT(10)
+#undef EKV_WAIT
+      default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
     }
     __syncthreads();           // every wave's part of stage s is in LDS; everyone is done with stage s-1
     if (s + NS - 1 < nstages) issue();                          // into the buffer stage s-1 occupied

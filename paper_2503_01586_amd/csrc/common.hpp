@@ -72,4 +72,26 @@ __device__ __forceinline__ void rope_sincos(int32_t pos, double theta, float* sn
   *cs = (q == 0) ? c : (q == 1) ? -s : (q == 2) ? -c : s;
 }
 
+// The same with sin and cos of the reduced argument from their Taylor polynomials (|r| <= pi/4:
+// truncation below 3e-8, i.e. fp32 rounding level) instead of the library routines, whose
+// instruction count dominates the epilogue of the matrix-core append (16 to 64 rotations per lane).
+__device__ __forceinline__ void rope_sincos_poly(int32_t pos, double theta, float* sn, float* cs) {
+  const double a = (double)pos * theta;
+  const double k = rint(a * 0.63661977236758134308);        // a / (pi/2)
+  double r = fma(-k, 1.57079632679489655800e+00, a);        // pi/2, high part
+  r = fma(-k, 6.12323399573676603587e-17, r);               // pi/2, low part
+  const float x = (float)r, x2 = x * x;
+  float ps = fmaf(x2, 2.7557319e-6f, -1.9841270e-4f);       // x^9/9! - x^7/7! ...
+  ps = fmaf(ps, x2, 8.3333333e-3f);
+  ps = fmaf(ps, x2, -1.6666667e-1f);
+  const float s = fmaf(ps * x2, x, x);
+  float pc = fmaf(x2, 2.4801587e-5f, -1.3888889e-3f);       // x^8/8! - x^6/6! ...
+  pc = fmaf(pc, x2, 4.1666667e-2f);
+  pc = fmaf(pc, x2, -0.5f);
+  const float c = fmaf(pc, x2, 1.0f);
+  const int q = (int)((long long)k & 3);
+  *sn = (q == 0) ? s : (q == 1) ? c : (q == 2) ? -s : -c;
+  *cs = (q == 0) ? c : (q == 1) ? -s : (q == 2) ? -c : s;
+}
+
 }  // namespace ekv
