@@ -381,7 +381,8 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
 // ---------------------------------------------------------------------------------------------
 // append_gemm_dma: the same GEMM with both operands brought in by direct global->LDS loads into a
 // ring of NS stages of 32 contraction rows (no register staging, one barrier per stage, the loads
-// of the next NS-1 stages in flight while a stage is multiplied).  A direct load writes 1 KiB
+// of the next NS-2 stages in flight while a stage is multiplied).  2 x WNW waves: two along the
+// 128 columns, WNW along the tokens; the widest tile (256 tokens) runs eight waves, two per SIMD.  A direct load writes 1 KiB
 // (64 lanes x 16 bytes) contiguously, so the LDS layouts are made of 1 KiB blocks:
 //   weights  [32 k][128 n]: blocks of 8 rows x 128 bytes, 16-byte pieces XOR-swizzled by row
 //            (conflict-free transposed reads), block (kb, nb) at (kb*2 + nb) KiB;
@@ -400,26 +401,28 @@ __device__ __forceinline__ void gd_dma16(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
 }
 
-template <int WN, int NS>
+// WN = 32-token tiles per wave, WNW = waves along the tokens (x 2 waves along the columns)
+template <int WN, int NS, int WNW>
 struct GemmDmaLayout {
-  static constexpr int BN = 64 * WN;
+  static constexpr int BN = 32 * WN * WNW;
+  static constexpr int NWAVES = 2 * WNW;
   static constexpr int B_BYTES = BN * 64;                     // token stage
   static constexpr int STAGE = kGdA + B_BYTES;
   static constexpr int LDS_BYTES = NS * STAGE;
   static constexpr int LOADS = STAGE / 1024;                  // direct loads per stage per work-group
-  static constexpr int LPW = LOADS / 4;                       // ... per wave
-  static_assert(LOADS % 4 == 0, "the loads of a stage are divided evenly among the four waves");
+  static constexpr int LPW = LOADS / NWAVES;                  // ... per wave
+  static_assert(LOADS % NWAVES == 0, "the loads of a stage are divided evenly among the waves");
   static_assert(LDS_BYTES <= 160 * 1024, "exceeds the LDS of a compute unit");
   static_assert(NS >= 3 && NS <= 12 && (NS - 2) * LPW <= 63, "ring depth outside what the load counter can express");
 };
 
-template <int WN, int NS>
-__global__ __launch_bounds__(256) void append_gemm_dma_kernel(
+template <int WN, int NS, int WNW>
+__global__ __launch_bounds__(128 * WNW) void append_gemm_dma_kernel(
     const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
     const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const bf16_t* __restrict__ W_dkv2, int d_ck,
     const int32_t* __restrict__ elite_idx, bf16_t* __restrict__ ke_plane, bf16_t* __restrict__ c_plane,
     int64_t plane_rows, int d, int n_h, int d_h, int r, int d_c, RopeTable rope) {
-  using L = GemmDmaLayout<WN, NS>;
+  using L = GemmDmaLayout<WN, NS, WNW>;
   extern __shared__ __attribute__((aligned(16))) char gsm[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
@@ -494,35 +497,8 @@ __global__ __launch_bounds__(256) void append_gemm_dma_kernel(
     b_off[ks] = kGdA + (wn * WN * 2 + (n32 >> 4)) * 1024 + row * 64 + (((2 * ks + hi) ^ gd_swz4(row)) << 4);
   }
 
-  int use_slot = 0;              // ring slot of the stage being multiplied
-  auto compute = [&]() {
-    const char* st = gsm + use_slot * L::STAGE;
-    use_slot = (use_slot + 1 == NS) ? 0 : use_slot + 1;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      am_bf16x8 a[2], b[WN];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const am_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 4096 + a_off[i][0]));
-        const am_s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 4096 + a_off[i][1]));
-        a[i] = __builtin_bit_cast(am_bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
-      }
-#pragma unroll
-      for (int j = 0; j < WN; ++j) b[j] = *reinterpret_cast<const am_bf16x8*>(st + b_off[ks] + j * 2048);
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-  };
-
-  // ---- ring pipeline: stages s+1 .. s+NS-2 stay in flight while stage s is consumed
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < nstages) issue();
-  for (int s = 0; s < nstages; ++s) {
-    const int ahead = min(nstages - 1 - s, NS - 2);             // stages after s that have been issued
-    // wait until this wave's loads of stage s have landed (the loads of `ahead` later stages may remain)
+  // wait until this wave's direct loads have landed except those of the `ahead` most recent stages
+  auto wait_loads = [&](int ahead) {
     switch (ahead) {
       case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
 #define EKV_WAIT(K) case K: if constexpr (K <= NS - 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(K * L::LPW) : "memory"); break;
@@ -530,9 +506,52 @@ __global__ __launch_bounds__(256) void append_gemm_dma_kernel(
 #undef EKV_WAIT
       default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
     }
-    __syncthreads();           // every wave's part of stage s is in LDS; everyone is done with stage s-1
+  };
+  // operands of one stage in registers: both 16-row k-steps
+  struct StageOps {
+    am_bf16x8 a[2][2];           // [ks][32-column tile]
+    am_bf16x8 b[2][WN];          // [ks][32-token tile]
+  };
+  int read_slot = 0;             // ring slot of the next stage to be read into registers; stages are read in order
+  auto read_ops = [&](StageOps& o) {
+    const char* st = gsm + read_slot * L::STAGE;
+    read_slot = (read_slot + 1 == NS) ? 0 : read_slot + 1;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const am_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 4096 + a_off[i][0]));
+        const am_s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 4096 + a_off[i][1]));
+        o.a[ks][i] = __builtin_bit_cast(am_bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
+#pragma unroll
+      for (int j = 0; j < WN; ++j) o.b[ks][j] = *reinterpret_cast<const am_bf16x8*>(st + b_off[ks] + j * 2048);
+    }
+  };
+  auto multiply = [&](const StageOps& o) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[ks][i], o.b[ks][j], acc[i][j], 0, 0, 0);
+  };
+
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nstages) issue();
+  // Ring pipeline: stages s+1 .. s+NS-2 stay in flight while stage s is consumed.  (A version skewed
+  // by one stage -- the operands of stage s+1 read into a second register set while stage s is
+  // multiplied -- hides the LDS latency and the barrier but keeps one stage less in flight; it
+  // measured 5 % slower with eight waves and 20 % slower with four.)
+  for (int s = 0; s < nstages; ++s) {
+    wait_loads(min(nstages - 1 - s, NS - 2));                   // this wave's loads of stage s have landed
+    __syncthreads();             // every wave's part of stage s is in LDS; everyone is done with stage s-1
     if (s + NS - 1 < nstages) issue();                          // into the buffer stage s-1 occupied
-    compute();
+    StageOps ops;
+    read_ops(ops);
+    multiply(ops);
   }
 
   gemm_epilogue<WN>(acc, n0, t0, wm, wn, n32, hi, T, pos, slot, elite_idx, ke_plane, c_plane, plane_rows, n_h, d_h,
@@ -566,21 +585,21 @@ static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <int WN, int NS>
+template <int WN, int NS, int WNW>
 static hipError_t launch_gemm_dma(const AppendArgs& a, hipStream_t stream) {
-  using L = GemmDmaLayout<WN, NS>;
+  using L = GemmDmaLayout<WN, NS, WNW>;
   const elitekv_dims& d = a.dims;
   const int N = 2 * d.r * d.n_heads + d.d_c;
   static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
   if (!attr_done && L::LDS_BYTES > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int64_t tblocks = (a.T + L::BN - 1) / L::BN;
   const dim3 grid((unsigned)((tblocks + 7) / 8 * 8 * (N / kGmCols)));   // token blocks padded to whole rounds of 8 XCDs
-  append_gemm_dma_kernel<WN, NS><<<grid, 256, L::LDS_BYTES, stream>>>(
+  append_gemm_dma_kernel<WN, NS, WNW><<<grid, 128 * WNW, L::LDS_BYTES, stream>>>(
       (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
       (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
       d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
@@ -592,9 +611,9 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
   const int64_t col_blocks = (2 * d.r * d.n_heads + d.d_c) / kGmCols;
   // the widest token tile that still gives every compute unit work
   if (d.d_model % kGdStage == 0) {
-    if (col_blocks * ((a.T + 255) / 256) >= 512) return launch_gemm_dma<4, 6>(a, stream);
-    if (col_blocks * ((a.T + 127) / 128) >= 256) return launch_gemm_dma<2, 4>(a, stream);
-    return launch_gemm_dma<1, 6>(a, stream);
+    if (col_blocks * ((a.T + 255) / 256) >= 512) return launch_gemm_dma<2, 6, 4>(a, stream);
+    if (col_blocks * ((a.T + 127) / 128) >= 256) return launch_gemm_dma<2, 4, 2>(a, stream);
+    return launch_gemm_dma<1, 6, 2>(a, stream);
   }
   if (col_blocks * ((a.T + 255) / 256) >= 1024) return launch_gemm_wn<4>(a, stream);
   return launch_gemm_wn<1>(a, stream);
