@@ -247,8 +247,10 @@ int elitekv_slrd_decode_attn(const elitekv_dims* dims, int32_t d_ck, const void*
  *   For fewer than eight sequences (bf16 shapes of the matrix-core path) the step is four launches:
  *   the first pass of the append together with the query preparation; the attention, whose extra
  *   work-groups add up the append's partial sums, rotate and store the new rows and pass the new
- *   token on as one more split; the merge with the up-projection; the final reduction.  Other
- *   shapes run the two entry points' kernels one after the other.
+ *   token on as one more split; the merge with the up-projection; the final reduction.  With 8 to
+ *   64 sequences the first pass of the append and the query preparation share a launch as well
+ *   (five launches instead of six).  Other shapes run the two entry points' kernels one after
+ *   the other.
  *   All other arguments, layouts, ownership and errors as in elitekv_append and
  *   elitekv_decode_attn.  ws: elitekv_decode_step_workspace_bytes bytes (EWORKSPACE if smaller).
  * ------------------------------------------------------------------------------------------- */

@@ -9,11 +9,16 @@
 #include "common.hpp"
 #include "launch.hpp"
 #include "append_small.hpp"
+#include "append_skinny.hpp"
 #include "qprep_rows.hpp"
+#include "qprep_mfma.hpp"
 
 namespace ekv {
 
 QprepRowsParams make_qprep_rows_params(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt);
+AppendSkinnyParams make_append_skinny_params(const AppendArgs& a, float* partial, int kc);
+int append_skinny_ksplit(const elitekv_dims& d);
+int append_skinny_kc(const elitekv_dims& d, int ks);
 
 constexpr int kFrontBatch = 16;   // weight rows per thread in flight in the append role
 
@@ -84,6 +89,65 @@ hipError_t launch_decode_front(const AppendArgs& ap, const DecodeArgs& a, const 
   const int bt = front_tile(a.B);
   return bt == 1 ? launch_front_bt<1>(ap, a, p, stream) : bt == 2 ? launch_front_bt<2>(ap, a, p, stream)
        : bt == 4 ? launch_front_bt<4>(ap, a, p, stream) : launch_front_bt<8>(ap, a, p, stream);
+}
+
+// ---- batches of eight rows and up: the matrix-core versions of the two roles in one launch; the
+// append's split sums are then added, rotated and stored by append_finish (with many sequences the
+// new-token work-groups of the attention kernel would take compute units from its tile work-groups).
+template <int KS, int TT>
+__global__ __launch_bounds__(256) void decode_front_mfma_kernel(const AppendSkinnyParams A, const QprepRowsParams Q,
+                                                                const RopeTable rope, int n_qprep, int q_blocks,
+                                                                int n_blocks) {
+  extern __shared__ __attribute__((aligned(16))) char fsm[];
+  const int wg = blockIdx.x;
+  if (wg < n_qprep) {
+    qprep_mfma_body<KS>(Q, rope, wg % q_blocks, wg / q_blocks, fsm);          // (block of 128 latent columns, head)
+  } else {
+    const int e = wg - n_qprep;
+    append_skinny_body<TT>(A, e % n_blocks, e / n_blocks, fsm);               // (column block, contraction split)
+  }
+}
+
+bool decode_front_mfma_supported(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p) {
+  const elitekv_dims& d = a.dims;
+  if (!p.mfma || p.fresh || ap.T != a.B) return false;
+  return qprep_mfma_supported(d, p.d_q, a.B) && append_skinny_supported(d, ap.T, ap.d_ck);
+}
+
+template <int KS>
+static hipError_t launch_front_mfma_ks(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  const int N = 2 * d.r * d.n_heads + d.d_c;
+  int ks = append_skinny_ksplit(d);
+  const int kc = append_skinny_kc(d, ks);
+  ks = (d.d_model + kc - 1) / kc;            // splits that still have rows; never more than planned
+  float* partial = (float*)ap.ws;
+  const size_t sm_q = qprep_mfma_lds(d.head_dim, d.r);
+  const size_t sm = sm_q > (size_t)kSkLds ? sm_q : (size_t)kSkLds;
+  const int q_blocks = p.d_q / 128, n_qprep = q_blocks * d.n_heads, n_blocks = N / kSkCols;
+  const AppendSkinnyParams A = make_append_skinny_params(ap, partial, kc);
+  const QprepRowsParams Q = make_qprep_rows_params(a, p, (float*)(a.ws + p.off_qe), (bf16_t*)(a.ws + p.off_qt));
+  const RopeTable rope = make_rope_table(d.rope_base, d.head_dim);
+  const unsigned grid = (unsigned)(n_qprep + n_blocks * ks);
+  if (ap.T <= 32) decode_front_mfma_kernel<KS, 1><<<grid, 256, sm, stream>>>(A, Q, rope, n_qprep, q_blocks, n_blocks);
+  else decode_front_mfma_kernel<KS, 2><<<grid, 256, sm, stream>>>(A, Q, rope, n_qprep, q_blocks, n_blocks);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_append_finish(ap, partial, ks, stream);
+}
+
+hipError_t launch_decode_front_mfma(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
+  const int nd = a.dims.head_dim - 2 * a.dims.r;
+  switch ((nd + 15) / 16) {
+    case 1: return launch_front_mfma_ks<1>(ap, a, p, stream);
+    case 2: return launch_front_mfma_ks<2>(ap, a, p, stream);
+    case 3: return launch_front_mfma_ks<3>(ap, a, p, stream);
+    case 4: return launch_front_mfma_ks<4>(ap, a, p, stream);
+    case 5: return launch_front_mfma_ks<5>(ap, a, p, stream);
+    case 6: return launch_front_mfma_ks<6>(ap, a, p, stream);
+    case 7: return launch_front_mfma_ks<7>(ap, a, p, stream);
+    default: return launch_front_mfma_ks<8>(ap, a, p, stream);
+  }
 }
 
 }  // namespace ekv

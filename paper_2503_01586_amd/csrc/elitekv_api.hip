@@ -364,6 +364,12 @@ static int step_impl(const elitekv_dims* dims, int32_t d_ck, const void* x, cons
     e = launch_decode_front(ap, a, p, stream);
     a.stages = 6;
     if (e == hipSuccess) e = launch_decode_mfma(a, p, stream);
+  } else if (decode_front_mfma_supported(ap, a, p)) {
+    // batches: first pass of the append + query preparation in one launch, the append's finishing
+    // launch, then attention, merge and up-projection
+    e = launch_decode_front_mfma(ap, a, p, stream);
+    a.stages = 6;
+    if (e == hipSuccess) e = launch_decode_mfma(a, p, stream);
   } else {
     e = append_dispatch(ap, stream);
     if (e == hipSuccess) e = p.mfma ? launch_decode_mfma(a, p, stream) : launch_decode_generic(a, p, stream);

@@ -112,6 +112,9 @@ bool qprep_mfma_supported(const elitekv_dims& d, int d_q, int64_t B);
 // how the append's contraction is split (ks splits of kc weight rows).
 bool decode_front_plan(const elitekv_dims& d, int d_ck, int d_q, int64_t B, int* ks, int* kc);
 hipError_t launch_decode_front(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
+// ... for batches of eight rows and up (matrix-core roles; includes the append's finishing launch)
+bool decode_front_mfma_supported(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p);
+hipError_t launch_decode_front_mfma(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 bool merge_batch_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits);
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);

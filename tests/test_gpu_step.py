@@ -26,6 +26,9 @@ STEP_CASES = {
     "bf16_7b_seven_sequences": (shape(4096, 32, 128, 8, 1536, "bf16"), [5, 6, 7, 8, 100, 31, 32]),
     "bf16_7b_eight_sequences": (shape(4096, 32, 128, 8, 1536, "bf16"), [9, 40, 3, 77, 120, 16, 15, 64]),
     "bf16_7b_sixteen_sequences": (shape(4096, 32, 128, 8, 1536, "bf16"), list(range(20, 36))),
+    "bf16_7b_12pct_forty_sequences": (shape(4096, 32, 128, 4, 768, "bf16"), [3 + (7 * i) % 90 for i in range(40)]),
+    "bf16_7b_sixty_four_sequences": (shape(4096, 32, 128, 8, 1536, "bf16"), [1 + (11 * i) % 70 for i in range(64)]),
+    "bf16_13b_sixteen_sequences": (shape(5120, 40, 128, 8, 1920, "bf16"), [10 + 5 * i for i in range(16)]),
     "bf16_13b_one_sequence": (shape(5120, 40, 128, 8, 1920, "bf16"), [200]),
     "bf16_13b_four_sequences": (shape(5120, 40, 128, 8, 1920, "bf16"), [18, 90, 1, 33]),
     "bf16_7b_12pct_two_sequences": (shape(4096, 32, 128, 4, 768, "bf16"), [70, 71]),
