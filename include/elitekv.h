@@ -243,7 +243,8 @@ int elitekv_slrd_decode_attn(const elitekv_dims* dims, int32_t d_ck, const void*
  *   slot[b] = b * batch_stride_rows + seq_len[b] - 1.  For a sequence whose slot[b] is anything
  *   else (out of range: the token is not stored; another row) the row is stored as elitekv_append
  *   stores it but out[b] is unspecified: depending on the shape the new token is attended to from
- *   its fresh row or from whatever row seq_len[b] - 1 of the plane holds.
+ *   its fresh row or from whatever row seq_len[b] - 1 of the plane holds.  seq_len[b] <= 0:
+ *   nothing is attended, out[b] is 0, and the token is still stored at slot[b] if that is in range.
  *   For fewer than eight sequences (bf16 shapes of the matrix-core path) the step is four launches:
  *   the first pass of the append together with the query preparation; the attention, whose extra
  *   work-groups add up the append's partial sums, rotate and store the new rows and pass the new

@@ -110,6 +110,35 @@ def test_step_agrees_with_the_two_calls_and_skips_out_of_range_slots():
     assert torch.equal(c[row], c_before[row])
 
 
+@pytest.mark.parametrize("B", [2, 9])
+def test_step_with_a_sequence_that_attends_to_nothing(B):
+    """seq_len = 0 for the first sequence: its output row is zero, its token is stored all the same."""
+    sh = shape(4096, 32, 128, 8, 1536, "bf16")
+    seqs = [0] + [20 + 3 * i for i in range(B - 1)]
+    stride = 64
+    rng, idx, W_ke, W_dkv, W_uk, W_uv, x, q = _draw(sh, B, B, 5 + B)
+    dims = dims_of(sh)
+    ke, c = _planes(rng, B, stride, 32, 8, 1536, "bf16")
+    pos = np.maximum(np.array(seqs) - 1, 0)
+    slot = np.arange(B) * stride + pos
+    slot[0] = 7                                          # in range, although sequence 0 attends to nothing
+    xd, qd, Wked, Wdkvd, Wukd, Wuvd = (dev(a, "bf16") for a in (x, q, W_ke, W_dkv, W_uk, W_uv))
+    out = torch.full((B, 32, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ws = torch.full((ekv.elitekv_decode_step_workspace_bytes(dims, B, max(seqs)),), 0xFF, dtype=torch.uint8, device=DEV)
+    ekv.elitekv_decode_step(dims, xd, qd, i32(pos), i64(slot), i32(seqs), max(seqs), stride, Wked, Wdkvd, Wukd, Wuvd,
+                            i32(idx), ke, c, out, ws)
+    torch.cuda.synchronize()
+    o = host64(out)
+    assert np.all(o[0] == 0.0) and np.all(np.isfinite(o))
+    ke_ref, c_ref = orc.append(host64(xd), pos, host64(Wked), host64(Wdkvd), idx, 128, sh["rope_base"])
+    assert orc.max_abs_rel(host64(c)[slot], c_ref) <= TOL["bf16"]
+    assert orc.max_abs_rel(host64(ke).reshape(B * stride, 32, -1)[slot], ke_ref) <= TOL["bf16"]
+    ke_g, c_g = host64(ke).reshape(B, stride, 32, -1), host64(c).reshape(B, stride, -1)
+    ref = orc.decode_attn(host64(qd)[1:], pos[1:], ke_g[1:], c_g[1:], seqs[1:], host64(Wukd), host64(Wuvd), idx, 128,
+                          sh["rope_base"])
+    assert orc.max_abs_rel(o[1:], ref) <= TOL["bf16"]
+
+
 def test_step_argument_errors():
     sh = shape(4096, 32, 128, 8, 1536, "bf16")
     dims = dims_of(sh)
