@@ -2,7 +2,8 @@
 //   qprep_rows   : rotated elite query + W_uk absorbed into the rest of the query
 //                  (Section 3.1 score equation, first sum; Section 5, absorption of B^k)
 //   merge_up     : exact log-sum-exp merge of the sequence splits, normalisation, and the W_uv
-//                  up-projection of a chunk of latent columns (Section 3.2, B^v_J)
+//                  up-projection of a chunk of latent columns (Section 3.2, B^v_J), one batch row
+//                  (the version for a batch is merge_mfma.hip)
 //   out_reduce   : sum of the up-projection partials over the latent chunks, cast to bf16
 #include "common.hpp"
 #include "launch.hpp"
@@ -238,217 +239,6 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
 
 }
 
-// ---------------------------------------------------------------------------------------------
-// merge_up_batch.  The same three steps for a decoding batch: one work-group per (chunk of CW
-// latent columns, head) takes ALL batch rows of a tile of up to kMbRows rows, so the chunk of W_uv
-// is read from memory once per tile instead of once per batch row.  It is kept in registers as
-// fp32, thread <-> (output column j, part of the chunk's latent columns), after one transposing
-// pass through LDS; the merged latents of the rows sit in LDS and are read as broadcasts.
-// With fewer rows than row groups, the splits of a row are divided among several groups and their
-// sums are added in a fixed order.
-// ---------------------------------------------------------------------------------------------
-constexpr int kMbRows = 64;             // batch rows per work-group pass
-constexpr int kMbWeightFloats = 4096;   // most (rows x splits) merge weights a work-group keeps in LDS
-
-template <int CW, int DH>
-struct MergeBatchLayout {
-  static constexpr int NKQ = 256 / DH;            // parts of the chunk's columns (2 for d_h = 128, 4 for 64)
-  static constexpr int KPT = CW / NKQ;            // latent columns per thread
-  static constexpr int JPW = DH / 4;              // output columns per wave
-  static constexpr int WROW = DH * 2 + 16;        // bytes of one staged W_uv row (padded)
-  static constexpr int LPR = CW / 8;              // lanes that cover one split's row chunk
-  static constexpr int NG = 256 / LPR;            // row groups working in parallel
-  static constexpr int UROW = CW + 4;             // floats per merged-latent row (padded)
-  static constexpr int UBAR_BYTES = kMbRows * UROW * 4;
-  static constexpr int WST_BYTES = CW * WROW;
-  static constexpr int BIG = UBAR_BYTES > WST_BYTES ? UBAR_BYTES : WST_BYTES;   // the two share LDS
-  static size_t lds_bytes(int rows, int n_splits) { return (size_t)BIG + (size_t)(2 * rows * n_splits + kMbRows) * 4; }
-};
-
-template <int CW, int DH>
-__global__ __launch_bounds__(256) void merge_up_batch_kernel(
-    const float* __restrict__ part_m, const float* __restrict__ part_l,
-    const bf16_t* __restrict__ part_u, const bf16_t* __restrict__ W_uv, float* __restrict__ opart,
-    int B, int n_h, int nhp, int d_c, int n_splits, int rows_per_wg) {
-  using L = MergeBatchLayout<CW, DH>;
-  constexpr int KPT = L::KPT, JPW = L::JPW, WROW = L::WROW, LPR = L::LPR, NG = L::NG, UROW = L::UROW;
-  extern __shared__ __attribute__((aligned(16))) char bsm[];
-  float* ubar = reinterpret_cast<float*>(bsm);                 // [row-slices][UROW] merged latents
-  char* wst = bsm;                                             // [CW][WROW] staged W_uv chunk (earlier)
-  float* invl = reinterpret_cast<float*>(bsm + L::BIG);        // [kMbRows]
-  float* wsp = invl + kMbRows;                                 // [rows][n_splits] split maxima, then weights
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int chunk = blockIdx.x, head = blockIdx.y, b0 = blockIdx.z * rows_per_wg;
-  const int n_chunks = gridDim.x;
-  const int rows = min(rows_per_wg, B - b0);
-  float* lsp = wsp + rows * n_splits;                          // [rows][n_splits] split sums
-  const int col0 = chunk * CW;
-
-  // (1) the chunk of W_uv[:, head, :]: coalesced 16-byte loads, all requested at once
-  constexpr int CPR = DH / 8;              // 16-byte pieces per W_uv row
-  constexpr int WPASS = CW * CPR / 256;    // loads per thread
-  uint4 wld[WPASS];
-#pragma unroll
-  for (int i = 0; i < WPASS; ++i) {
-    const int e = i * 256 + tid, k = e / CPR, c = e % CPR;
-    wld[i] = *reinterpret_cast<const uint4*>(W_uv + ((int64_t)(col0 + k) * n_h + head) * DH + c * 8);
-  }
-  // (2) split maxima and sums of every (row, split) of this head
-  for (int it = tid; it < rows * n_splits; it += 256) {
-    const int64_t gi = ((int64_t)b0 * n_splits + it) * nhp + head;
-    const float ls = part_l[gi];
-    wsp[it] = (ls > 0.f) ? part_m[gi] : -INFINITY;             // an empty split has weight 0
-    lsp[it] = ls;
-  }
-#pragma unroll
-  for (int i = 0; i < WPASS; ++i) {
-    const int e = i * 256 + tid, k = e / CPR, c = e % CPR;
-    *reinterpret_cast<uint4*>(wst + k * WROW + c * 16) = wld[i];
-  }
-  __syncthreads();
-  //     merge weights, thread <-> batch row:  w_s = exp2(m_s - max m),  1 / sum w_s l_s
-  if (tid < rows) {
-    float* wr = wsp + tid * n_splits;
-    const float* lr = lsp + tid * n_splits;
-    float m = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, wr[s]);
-    float lsum = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-      const float w = (wr[s] > -INFINITY) ? exp2f(wr[s] - m) : 0.f;
-      wr[s] = w;
-      lsum += w * lr[s];
-    }
-    invl[tid] = (lsum > 0.f) ? 1.f / lsum : 0.f;
-  }
-  // (3) this thread's column of the chunk, as fp32: j = wave*JPW + lane%JPW, latent columns kq*KPT ..
-  const int jj = wave * JPW + lane % JPW, kq = lane / JPW;
-  float wf[KPT];
-#pragma unroll
-  for (int i = 0; i < KPT; ++i)
-    wf[i] = bf16_bits_to_f32(*reinterpret_cast<const uint16_t*>(wst + (kq * KPT + i) * WROW + jj * 2));
-  __syncthreads();                                             // the staging area becomes ubar
-
-  // (4) merged latent: group <-> (row, slice of the splits); lane <-> 8 columns
-  const int SL = rows < NG ? NG / rows : 1;                    // slices per row
-  const int cl = tid % LPR, g = tid / LPR;
-  if (g < NG && rows * SL <= NG) {
-    // at most one (row, slice) item per group: eight splits at a time
-    const int rs = g;
-    if (rs < rows * SL) {
-      const int rl = rs % rows, sl = rs / rows;
-      const bf16_t* ub = part_u + (((int64_t)(b0 + rl) * n_splits) * nhp + head) * (int64_t)d_c + col0 + cl * 8;
-      const int64_t sstep = (int64_t)nhp * d_c;
-      const float* wr = wsp + rl * n_splits;
-      float acc[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-      for (int s0 = sl; s0 < n_splits; s0 += 8 * SL) {
-        uint4 u[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          u[q] = make_uint4(0, 0, 0, 0);
-          if (s0 + q * SL < n_splits) u[q] = *reinterpret_cast<const uint4*>(ub + (s0 + q * SL) * sstep);
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const float w = (s0 + q * SL < n_splits) ? wr[s0 + q * SL] : 0.f;
-          const uint32_t uu[4] = {u[q].x, u[q].y, u[q].z, u[q].w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            acc[2 * i] = fmaf(w, __uint_as_float(uu[i] << 16), acc[2 * i]);
-            acc[2 * i + 1] = fmaf(w, __uint_as_float(uu[i] & 0xffff0000u), acc[2 * i + 1]);
-          }
-        }
-      }
-      float* ur = ubar + rs * UROW + cl * 8;
-      *reinterpret_cast<float4*>(ur) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-      *reinterpret_cast<float4*>(ur + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    }
-  } else if (g < NG) {
-    // several items per group: two (row, slice) items at a time, four splits each (8 loads of 16 bytes in flight)
-    for (int rs = g; rs < rows * SL; rs += 2 * NG) {
-      const int rs2 = rs + NG;
-      const bool two = rs2 < rows * SL;
-      const int rl0 = rs % rows, sl0 = rs / rows;
-      const int rl1 = two ? rs2 % rows : rl0, sl1 = two ? rs2 / rows : sl0;
-      const int64_t sstep = (int64_t)nhp * d_c;
-      const bf16_t* ub0 = part_u + (((int64_t)(b0 + rl0) * n_splits) * nhp + head) * (int64_t)d_c + col0 + cl * 8;
-      const bf16_t* ub1 = part_u + (((int64_t)(b0 + rl1) * n_splits) * nhp + head) * (int64_t)d_c + col0 + cl * 8;
-      const float* wr0 = wsp + rl0 * n_splits;
-      const float* wr1 = wsp + rl1 * n_splits;
-      float acc0[8], acc1[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc0[i] = acc1[i] = 0.f;
-      for (int s0 = 0; s0 < n_splits; s0 += 4 * SL) {
-        uint4 u0[4], u1[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int sa = s0 + sl0 + q * SL, sb = s0 + sl1 + q * SL;
-          u0[q] = make_uint4(0, 0, 0, 0);
-          u1[q] = make_uint4(0, 0, 0, 0);
-          if (sa < n_splits) u0[q] = *reinterpret_cast<const uint4*>(ub0 + sa * sstep);
-          if (two && sb < n_splits) u1[q] = *reinterpret_cast<const uint4*>(ub1 + sb * sstep);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int sa = s0 + sl0 + q * SL, sb = s0 + sl1 + q * SL;
-          const float w0 = (sa < n_splits) ? wr0[sa] : 0.f;
-          const float w1 = (two && sb < n_splits) ? wr1[sb] : 0.f;
-          const uint32_t a4[4] = {u0[q].x, u0[q].y, u0[q].z, u0[q].w};
-          const uint32_t b4[4] = {u1[q].x, u1[q].y, u1[q].z, u1[q].w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            acc0[2 * i] = fmaf(w0, __uint_as_float(a4[i] << 16), acc0[2 * i]);
-            acc0[2 * i + 1] = fmaf(w0, __uint_as_float(a4[i] & 0xffff0000u), acc0[2 * i + 1]);
-            acc1[2 * i] = fmaf(w1, __uint_as_float(b4[i] << 16), acc1[2 * i]);
-            acc1[2 * i + 1] = fmaf(w1, __uint_as_float(b4[i] & 0xffff0000u), acc1[2 * i + 1]);
-          }
-        }
-      }
-      float* ur = ubar + rs * UROW + cl * 8;
-      *reinterpret_cast<float4*>(ur) = make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
-      *reinterpret_cast<float4*>(ur + 4) = make_float4(acc0[4], acc0[5], acc0[6], acc0[7]);
-      if (two) {
-        float* ur2 = ubar + rs2 * UROW + cl * 8;
-        *reinterpret_cast<float4*>(ur2) = make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
-        *reinterpret_cast<float4*>(ur2 + 4) = make_float4(acc1[4], acc1[5], acc1[6], acc1[7]);
-      }
-    }
-  }
-  __syncthreads();
-  //     slices of a row added in a fixed order, normalised; element (row, column) stays in place
-  for (int e = tid; e < rows * CW; e += 256) {
-    const int rl = e / CW, c = e % CW;
-    float a = 0.f;
-    for (int sl = 0; sl < SL; ++sl) a += ubar[(sl * rows + rl) * UROW + c];
-    ubar[rl * UROW + c] = a * invl[rl];
-  }
-  __syncthreads();
-
-  // (5) up-projection of the chunk, two rows at a time; the column parts meet by shuffles
-  for (int rl = 0; rl < rows; rl += 2) {
-    const float* u0 = ubar + rl * UROW + kq * KPT;
-    const float* u1 = ubar + min(rl + 1, rows - 1) * UROW + kq * KPT;
-    float o0 = 0.f, o1 = 0.f;
-#pragma unroll
-    for (int i = 0; i < KPT; i += 4) {
-      const float4 a = *reinterpret_cast<const float4*>(u0 + i);
-      const float4 c = *reinterpret_cast<const float4*>(u1 + i);
-      o0 = fmaf(a.x, wf[i], o0); o0 = fmaf(a.y, wf[i + 1], o0); o0 = fmaf(a.z, wf[i + 2], o0); o0 = fmaf(a.w, wf[i + 3], o0);
-      o1 = fmaf(c.x, wf[i], o1); o1 = fmaf(c.y, wf[i + 1], o1); o1 = fmaf(c.z, wf[i + 2], o1); o1 = fmaf(c.w, wf[i + 3], o1);
-    }
-#pragma unroll
-    for (int off = JPW; off < 64; off <<= 1) {
-      o0 += __shfl_xor(o0, off, kWave);
-      o1 += __shfl_xor(o1, off, kWave);
-    }
-    if (kq == 0) {
-      opart[(((int64_t)(b0 + rl) * n_h + head) * n_chunks + chunk) * DH + jj] = o0;
-      if (rl + 1 < rows) opart[(((int64_t)(b0 + rl + 1) * n_h + head) * n_chunks + chunk) * DH + jj] = o1;
-    }
-  }
-}
-
 // out[b, h, j] = sum over the latent chunks of the up-projection partials, in a fixed order.
 // (A separate launch rather than a last-arrival epilogue: device-scope fences inside merge_up
 // write back and invalidate the whole L2 of the XCD for every work-group.)
@@ -466,40 +256,10 @@ __global__ __launch_bounds__(256) void out_reduce_kernel(const float* __restrict
   st(out, e, a);
 }
 
-bool merge_batch_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits) {
-  if (B < 2 || d_u % 128 || (d.head_dim != 128 && d.head_dim != 64)) return false;
-  return (B < kMbRows ? B : kMbRows) * n_splits <= kMbWeightFloats;   // (any smaller row tile fits too)
-}
-
-template <int CW, int DH>
-static hipError_t launch_merge_batch(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
-  using L = MergeBatchLayout<CW, DH>;
-  const elitekv_dims& d = a.dims;
-  // rows per work-group: all of them (up to kMbRows) unless that leaves compute units idle
-  int rows = (int)(a.B < kMbRows ? a.B : kMbRows);
-  const int64_t groups = (int64_t)(p.d_u / CW) * d.n_heads;
-  while (rows > 16 && groups * ((a.B + rows - 1) / rows) < 256) rows = (rows + 1) / 2;
-  const size_t sm = L::lds_bytes(rows, p.n_part);
-  static size_t sm_set = 64 * 1024;   // raising the dynamic-LDS limit is idempotent
-  if (sm > sm_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&merge_up_batch_kernel<CW, DH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    if (e != hipSuccess) return e;
-    sm_set = sm;
-  }
-  const dim3 grid(p.d_u / CW, d.n_heads, (unsigned)((a.B + rows - 1) / rows));
-  merge_up_batch_kernel<CW, DH><<<grid, 256, sm, stream>>>(
-      (const float*)(a.ws + p.off_m), (const float*)(a.ws + p.off_l), (const bf16_t*)(a.ws + p.off_u),
-      (const bf16_t*)a.W_uv, (float*)(a.ws + p.off_opart), (int)a.B, d.n_heads, p.head_groups * 32, p.d_u,
-      p.n_part, rows);
-  return hipGetLastError();
-}
-
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
   if (p.merge_batch) {
-    hipError_t e = d.head_dim == 128 ? launch_merge_batch<128, 128>(a, p, stream)
-                                     : launch_merge_batch<128, 64>(a, p, stream);
+    hipError_t e = launch_merge_mfma(a, p, stream);
     if (e != hipSuccess) return e;
     const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
     out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(

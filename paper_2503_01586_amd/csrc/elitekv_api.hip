@@ -87,7 +87,7 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     p->off_m = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_l = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_u = off;  off = align_up(off + np * 32 * du * 2, 256);
-    p->merge_batch = merge_batch_supported(*d, p->d_u, B, p->n_part) ? 1 : 0;
+    p->merge_batch = merge_mfma_supported(*d, p->d_u, B, p->n_part) ? 1 : 0;
     p->up_cw = p->merge_batch ? 128 : (p->d_u % 192 == 0) ? 192 : 64;
     p->off_opart = off;
     off = align_up(off + Bz * nh * (size_t)(p->d_u / p->up_cw) * d->head_dim * sizeof(float), 256);

@@ -115,7 +115,8 @@ hipError_t launch_decode_front(const AppendArgs& ap, const DecodeArgs& a, const 
 // ... for batches of eight rows and up (matrix-core roles; includes the append's finishing launch)
 bool decode_front_mfma_supported(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p);
 hipError_t launch_decode_front_mfma(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
-bool merge_batch_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits);
+bool merge_mfma_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits);
+hipError_t launch_merge_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);
