@@ -87,12 +87,12 @@ hipError_t launch_append_generic(const AppendArgs& a, hipStream_t stream) {
     append_generic_kernel<float><<<grid, kApThreads, 0, stream>>>(
         (const float*)a.x, a.pos, a.slot, a.T, (const float*)a.W_ke, (const float*)a.W_dkv,
         (const float*)a.W_dkv2, a.d_ck, a.elite_idx, (float*)a.ke_plane, (float*)a.c_plane, a.plane_rows, d.d_model, d.n_heads,
-        d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
+        d.head_dim, d.r, d.d_c, rope_table(d.rope_base, d.head_dim));
   } else {
     append_generic_kernel<bf16_t><<<grid, kApThreads, 0, stream>>>(
         (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
         (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows, d.d_model, d.n_heads,
-        d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
+        d.head_dim, d.r, d.d_c, rope_table(d.rope_base, d.head_dim));
   }
   return hipGetLastError();
 }

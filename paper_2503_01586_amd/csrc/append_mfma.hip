@@ -463,7 +463,7 @@ static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
   append_gemm_kernel<WN><<<grid, 256, L::LDS_BYTES, stream>>>(
       (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
       (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows, d.d_model, d.n_heads, d.head_dim, d.r, d.d_c,
-      make_rope_table(d.rope_base, d.head_dim));
+      rope_table(d.rope_base, d.head_dim));
   return hipGetLastError();
 }
 
@@ -484,7 +484,7 @@ static hipError_t launch_gemm_dma(const AppendArgs& a, hipStream_t stream) {
   append_gemm_dma_kernel<WN, NS, WNW><<<grid, 128 * WNW, L::LDS_BYTES, stream>>>(
       (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
       (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
-      d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, make_rope_table(d.rope_base, d.head_dim));
+      d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, rope_table(d.rope_base, d.head_dim));
   return hipGetLastError();
 }
 

@@ -100,7 +100,7 @@ hipError_t launch_append_finish(const AppendArgs& a, const float* partial, int k
   const int N = 2 * d.r * d.n_heads + d.d_c;
   append_finish_kernel<<<dim3((unsigned)a.T, (N + 255) / 256), 256, 0, stream>>>(
       partial, a.pos, a.slot, a.T, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
-      d.n_heads, d.head_dim, d.r, d.d_c, ksplit, make_rope_table(d.rope_base, d.head_dim));
+      d.n_heads, d.head_dim, d.r, d.d_c, ksplit, rope_table(d.rope_base, d.head_dim));
   return hipGetLastError();
 }
 

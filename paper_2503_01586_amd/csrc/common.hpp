@@ -57,6 +57,20 @@ inline RopeTable make_rope_table(double base, int head_dim) {
   return t;
 }
 
+// The table of the calling thread's last (base, head_dim): a decode loop asks for the same one at
+// every launch, and 128 pow() calls are several microseconds of host time.
+inline const RopeTable& rope_table(double base, int head_dim) {
+  thread_local RopeTable table;
+  thread_local double have_base = 0.0;
+  thread_local int have_dim = 0;
+  if (have_base != base || have_dim != head_dim) {
+    table = make_rope_table(base, head_dim);
+    have_base = base;
+    have_dim = head_dim;
+  }
+  return table;
+}
+
 // sin and cos of pos * theta.  The angle is formed and reduced to [-pi/4, pi/4] in double
 // (two-term Cody-Waite, exact for the |k| < 2^20 quadrants that positions up to 2^31 with
 // theta <= 1 can reach in practice); only the reduced argument goes through fp32 sin/cos.

@@ -156,7 +156,7 @@ static void launch_mha_t(const MhaArgs& a, hipStream_t stream) {
   const float scale_log2e = kLog2e / sqrtf((float)d_h);
   mha_attn_kernel<T, LPR><<<dim3(a.n_splits, n_h, (unsigned)a.B), kMhaThreads, sm, stream>>>(
       (const T*)a.q, a.q_pos, a.seq_len, (const T*)a.k_plane, (const T*)a.v_plane, pm, pl, po, n_h,
-      d_h, make_rope_table(d.rope_base, d.head_dim), scale_log2e, a.max_seq_len, a.batch_stride_rows, a.plane_rows, a.n_splits,
+      d_h, rope_table(d.rope_base, d.head_dim), scale_log2e, a.max_seq_len, a.batch_stride_rows, a.plane_rows, a.n_splits,
       a.chunk);
   mha_merge_kernel<T><<<dim3(n_h, (unsigned)a.B), kMhaThreads, 0, stream>>>(pm, pl, po, (T*)a.out, n_h,
                                                                          d_h, a.n_splits);

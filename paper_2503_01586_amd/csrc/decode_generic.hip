@@ -230,7 +230,7 @@ static hipError_t launch_decode_generic_t(const DecodeArgs& a, const DecodePlan&
   if (a.stages & 1)
     qprep_generic_kernel<T><<<dim3(n_h, (unsigned)a.B), kGenThreads, 0, stream>>>(
         (const T*)a.q, a.q_pos, (const T*)a.W_uk, a.elite_idx, qe, qt, n_h, d_h, r, d_q,
-        make_rope_table(d.rope_base, d.head_dim), scale_log2e);
+        rope_table(d.rope_base, d.head_dim), scale_log2e);
 
   const dim3 grid(p.n_splits, n_h, (unsigned)a.B);
   const size_t sm = sizeof(float) * (size_t)(d_q + 2 * r + 2 * kGenTile);

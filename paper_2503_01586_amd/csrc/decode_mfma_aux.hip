@@ -41,7 +41,7 @@ static hipError_t launch_qprep_bt(const DecodeArgs& a, const DecodePlan& p, floa
     sm_set = sm;
   }
   qprep_rows_kernel<BT><<<grid, kQpThreads, sm, stream>>>(make_qprep_rows_params(a, p, qe, qt),
-                                                          make_rope_table(d.rope_base, d.head_dim));
+                                                          rope_table(d.rope_base, d.head_dim));
   return hipGetLastError();
 }
 
@@ -63,7 +63,7 @@ static hipError_t launch_qprep_mfma(const DecodeArgs& a, const DecodePlan& p, fl
   const size_t sm = qprep_mfma_lds(d.head_dim, d.r);
   const dim3 grid(p.d_q / 128, d.n_heads);
   const QprepRowsParams P = make_qprep_rows_params(a, p, qe, qt);
-  const RopeTable rope = make_rope_table(d.rope_base, d.head_dim);
+  const RopeTable rope = rope_table(d.rope_base, d.head_dim);
 #define EKV_QM(KSV) qprep_mfma_kernel<KSV><<<grid, 256, sm, stream>>>(P, rope)
   switch (ks) {
     case 1: EKV_QM(1); break;

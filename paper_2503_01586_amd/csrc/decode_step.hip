@@ -81,7 +81,7 @@ static hipError_t launch_front_bt(const AppendArgs& ap, const DecodeArgs& a, con
   const int n_qprep = (int)(((int64_t)p.d_q * d.n_heads + kQpThreads - 1) / kQpThreads) + 1;   // + the rotation group
   decode_front_kernel<BT><<<n_qprep + n_blocks * p.fr_ks, 256, sm, stream>>>(
       A, make_qprep_rows_params(a, p, (float*)(a.ws + p.off_qe), (bf16_t*)(a.ws + p.off_qt)),
-      make_rope_table(d.rope_base, d.head_dim), n_qprep, n_blocks);
+      rope_table(d.rope_base, d.head_dim), n_qprep, n_blocks);
   return hipGetLastError();
 }
 
@@ -127,7 +127,7 @@ static hipError_t launch_front_mfma_ks(const AppendArgs& ap, const DecodeArgs& a
   const int q_blocks = p.d_q / 128, n_qprep = q_blocks * d.n_heads, n_blocks = N / kSkCols;
   const AppendSkinnyParams A = make_append_skinny_params(ap, partial, kc);
   const QprepRowsParams Q = make_qprep_rows_params(a, p, (float*)(a.ws + p.off_qe), (bf16_t*)(a.ws + p.off_qt));
-  const RopeTable rope = make_rope_table(d.rope_base, d.head_dim);
+  const RopeTable rope = rope_table(d.rope_base, d.head_dim);
   const unsigned grid = (unsigned)(n_qprep + n_blocks * ks);
   if (ap.T <= 32) decode_front_mfma_kernel<KS, 1><<<grid, 256, sm, stream>>>(A, Q, rope, n_qprep, q_blocks, n_blocks);
   else decode_front_mfma_kernel<KS, 2><<<grid, 256, sm, stream>>>(A, Q, rope, n_qprep, q_blocks, n_blocks);

@@ -166,7 +166,7 @@ hipError_t launch_ropelite_search(const float* q, const float* k, const int32_t*
   search_init_kernel<<<(n_h + 63) / 64, 64, 0, stream>>>(emask, n_h);
   const int64_t total = T * n_h * half;
   search_rotate_kernel<<<(unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096), 256, 0, stream>>>(
-      q, k, pos, qr, kr, T, n_h, d_h, make_rope_table(rope_base, d_h));
+      q, k, pos, qr, kr, T, n_h, d_h, rope_table(rope_base, d_h));
   const float scale = 1.f / sqrtf((float)d_h);
   for (int round = 0; round < r; ++round) {
     search_round_kernel<<<dim3(n_qb, n_h), 256, 0, stream>>>(q, k, qr, kr, emask, partial, T, n_h, d_h, scale);
