@@ -452,13 +452,9 @@ static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
   using L = GemmLayout<WN>;
   const elitekv_dims& d = a.dims;
   const int N = 2 * d.r * d.n_heads + d.d_c;
-  static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
-  if (!attr_done && L::LDS_BYTES > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&append_gemm_kernel<WN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&append_gemm_kernel<WN>), L::LDS_BYTES);
+  if (le != hipSuccess) return le;
   const dim3 grid(N / kGmCols, (unsigned)((a.T + L::BN - 1) / L::BN));
   append_gemm_kernel<WN><<<grid, 256, L::LDS_BYTES, stream>>>(
       (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
@@ -472,13 +468,10 @@ static hipError_t launch_gemm_dma(const AppendArgs& a, hipStream_t stream) {
   using L = GemmDmaLayout<WN, NS, WNW>;
   const elitekv_dims& d = a.dims;
   const int N = 2 * d.r * d.n_heads + d.d_c;
-  static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
-  if (!attr_done && L::LDS_BYTES > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW>),
+                                        L::LDS_BYTES);
+  if (le != hipSuccess) return le;
   const int64_t tblocks = (a.T + L::BN - 1) / L::BN;
   const dim3 grid((unsigned)((tblocks + 7) / 8 * 8 * (N / kGmCols)));   // token blocks padded to whole rounds of 8 XCDs
   append_gemm_dma_kernel<WN, NS, WNW><<<grid, 128 * WNW, L::LDS_BYTES, stream>>>(

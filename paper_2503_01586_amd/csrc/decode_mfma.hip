@@ -591,13 +591,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
 template <int NW, int DC_W, int TWO_R, bool SEP>
 static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t stream) {
   using L = AttnMfmaLayout<NW, DC_W, TWO_R>;
-  static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<NW, DC_W, TWO_R, SEP>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, L::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimit lds_limit;
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&attn_mfma_kernel<NW, DC_W, TWO_R, SEP>),
+                                        L::LDS_BYTES);
+  if (le != hipSuccess) return le;
   const int per_row = prm.n_splits + prm.fresh;     // + the new-token work-group of a fused decode step
   const dim3 grid = prm.pair_map ? dim3((unsigned)((per_row * B + 7) / 8 * 16), 1, 1)
                                  : dim3(per_row, prm.head_groups, (unsigned)B);

@@ -33,13 +33,9 @@ static hipError_t launch_qprep_bt(const DecodeArgs& a, const DecodePlan& p, floa
   const size_t sm = qprep_rows_lds(d.n_heads, d.head_dim, d.r, BT);
   const int64_t rows = (int64_t)p.d_q * d.n_heads;
   const dim3 grid((unsigned)((rows + kQpThreads - 1) / kQpThreads) + 1, (unsigned)((a.B + BT - 1) / BT));   // + the rotation group
-  static size_t sm_set = 64 * 1024;   // raising the dynamic-LDS limit is idempotent; done once per size
-  if (sm > sm_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&qprep_rows_kernel<BT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    if (e != hipSuccess) return e;
-    sm_set = sm;
-  }
+  static LdsLimit lds_limit;
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&qprep_rows_kernel<BT>), sm);
+  if (le != hipSuccess) return le;
   qprep_rows_kernel<BT><<<grid, kQpThreads, sm, stream>>>(make_qprep_rows_params(a, p, qe, qt),
                                                           rope_table(d.rope_base, d.head_dim));
   return hipGetLastError();

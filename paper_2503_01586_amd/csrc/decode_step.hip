@@ -65,13 +65,9 @@ static hipError_t launch_front_bt(const AppendArgs& ap, const DecodeArgs& a, con
   const elitekv_dims& d = a.dims;
   const size_t sm_a = (size_t)p.fr_kc * BT * sizeof(float), sm_q = qprep_rows_lds(d.n_heads, d.head_dim, d.r, BT);
   const size_t sm = sm_a > sm_q ? sm_a : sm_q;
-  static size_t sm_set = 60 * 1024;   // raising the dynamic-LDS limit is idempotent; done once per size
-  if (sm > sm_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_front_kernel<BT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    if (e != hipSuccess) return e;
-    sm_set = sm;
-  }
+  static LdsLimit lds_limit;
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&decode_front_kernel<BT>), sm);
+  if (le != hipSuccess) return le;
   const int NE = 2 * d.r * d.n_heads;
   AppendSmallParams A;
   A.x = (const bf16_t*)ap.x; A.T = ap.T; A.W_ke = (const bf16_t*)ap.W_ke; A.W_dkv = (const bf16_t*)ap.W_dkv;

@@ -1,6 +1,7 @@
 // Internal interface between the C-ABI entry points (host validation and planning) and the
 // kernel launchers.  Every launcher only enqueues work on `stream`.
 #pragma once
+#include <atomic>
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -8,6 +9,26 @@
 #include "../../include/elitekv.h"
 
 namespace ekv {
+
+// Raising a kernel's dynamic-LDS limit (the default is 64 KiB, static LDS included) is a per-device setting; it is made
+// once per (kernel instantiation, device, largest size asked for so far).  One LdsLimit per
+// instantiation (a function-local static: zero-initialised, safe to use from several threads).
+constexpr int kMaxDevices = 64;
+struct LdsLimit {
+  std::atomic<size_t> have[kMaxDevices];
+};
+inline hipError_t raise_lds_limit(LdsLimit& st, const void* kernel, size_t bytes) {
+  if (bytes <= 48 * 1024) return hipSuccess;     // with the kernels' static LDS still below the default limit
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < kMaxDevices;
+  if (tracked && st.have[dev].load(std::memory_order_relaxed) >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess && tracked) st.have[dev].store(bytes, std::memory_order_relaxed);
+  return e;
+}
+
 
 // Where each intermediate of one decode call lives inside the caller's workspace.
 struct DecodePlan {

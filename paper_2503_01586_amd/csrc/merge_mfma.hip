@@ -263,13 +263,9 @@ static hipError_t launch_merge_mfma_dh(const DecodeArgs& a, const DecodePlan& p,
   const int64_t groups = (int64_t)(p.d_u / kMmCols) * d.n_heads;
   while (rows > 8 && groups * ((a.B + rows - 1) / rows) < 256) rows = (rows + 1) / 2;
   const size_t sm = L::lds_bytes(rows, p.n_part);
-  static size_t sm_set = 64 * 1024;   // raising the dynamic-LDS limit is idempotent
-  if (sm > sm_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&merge_up_mfma_kernel<DH>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    if (e != hipSuccess) return e;
-    sm_set = sm;
-  }
+  static LdsLimit lds_limit;
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&merge_up_mfma_kernel<DH>), sm);
+  if (le != hipSuccess) return le;
   const dim3 grid(p.d_u / kMmCols, d.n_heads, (unsigned)((a.B + rows - 1) / rows));
   merge_up_mfma_kernel<DH><<<grid, 256, sm, stream>>>(
       (const float*)(a.ws + p.off_m), (const float*)(a.ws + p.off_l), (const bf16_t*)(a.ws + p.off_u),
