@@ -34,6 +34,9 @@ STEP_CASES = {
     "bf16_7b_12pct_two_sequences": (shape(4096, 32, 128, 4, 768, "bf16"), [70, 71]),
     "bf16_odd_hidden_one_sequence": (shape(1000, 32, 128, 8, 1536, "bf16"), [50]),
     "bf16_narrow_hidden_one_sequence": (shape(64, 32, 128, 8, 512, "bf16"), [40]),
+    "bf16_small_heads_two_waves": (shape(512, 8, 64, 4, 128, "bf16"), [77, 16]),          # d_c = 128: two-wave attention
+    "bf16_forty_heads_r4": (shape(1024, 40, 128, 4, 256, "bf16"), [40, 41, 1]),             # two head groups, 2r = 8
+    "bf16_head_dim_64_five_sequences": (shape(768, 16, 64, 8, 512, "bf16"), [9, 100, 33, 64, 2]),
     "fp32_tiny_three_sequences": (synth.CONFIGS["tiny_fp32"].as_dict(), [129, 5, 60]),
 }
 
