@@ -173,6 +173,34 @@ def decode_attn(q, q_pos, ke, c, seq_len, W_uk, W_uv, elite_idx, head_dim: int,
 
 
 # ----------------------------------------------------------------------------------------------
+# The whole attention block of one decode step (Section 2.1: q_t = x_t W^q per head, the heads'
+# outputs concatenated and multiplied by W^o; Section 3: everything in between as above).  The
+# step's token is appended to the cache first and is the last token its query attends to.
+# ----------------------------------------------------------------------------------------------
+def attention_block_step(x, pos, ke_old, c_old, W_q, W_ke, W_dkv, W_uk, W_uv, W_o, elite_idx,
+                         head_dim: int, rope_base: float):
+    """One decode step of the attention block for B independent sequences.
+
+    x [B, d] hidden states of the new tokens; pos [B] their positions; ke_old[b] [S_b, n_h, 2r] and
+    c_old[b] [S_b, d_c] the rows cached so far (lists: S_b may differ, may be 0);
+    W_q [d, n_h, d_h]; W_o [n_h, d_h, d]; the other weights as in append / decode_attn.
+    Returns (y [B, d], ke_new [B, n_h, 2r], c_new [B, d_c]), float64.
+    """
+    x = np.asarray(x, dtype=F64)
+    W_q = np.asarray(W_q, dtype=F64)
+    W_o = np.asarray(W_o, dtype=F64)
+    B = x.shape[0]
+    q = np.einsum("bd,dhj->bhj", x, W_q)                                  # q_t = x_t W^q, head by head
+    ke_new, c_new = append(x, pos, W_ke, W_dkv, elite_idx, head_dim, rope_base)
+    ke_all = [np.concatenate([np.asarray(ke_old[b], dtype=F64), ke_new[b:b + 1]], axis=0) for b in range(B)]
+    c_all = [np.concatenate([np.asarray(c_old[b], dtype=F64), c_new[b:b + 1]], axis=0) for b in range(B)]
+    seq = [ke_all[b].shape[0] for b in range(B)]
+    o = decode_attn(q, pos, ke_all, c_all, seq, W_uk, W_uv, elite_idx, head_dim, rope_base)
+    y = np.einsum("bhj,hjd->bd", o, W_o)                                  # [o_0, ..., o_{n_h-1}] W^o
+    return y, ke_new, c_new
+
+
+# ----------------------------------------------------------------------------------------------
 # Separated low-rank decomposition (Section 3.2, "Separated Low-Rank Decomposition"): the
 # non-elite key block and the value block are factorised separately,
 #     W^k_{e^,0:n_h-1} ~ A^k B^k_S,   W^v_{0:n_h-1} ~ A^v B^v_S,
