@@ -251,6 +251,9 @@ def main():
         if not d_ck and not args.no_multiquery:
             result["multiquery"] = multiquery(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
                                               cache_bytes)
+        if not d_ck and B < 8:
+            result["block_step"] = block_step(ekv, ev, cfg, dims, planes, x_d, pos_d, slot_d, seq_d, W_ke_d, W_dkv_d, W_uk_d,
+                                              W_uv_d, idx_d, dev, dt, stream, cache_bytes, args)
         result["ropelite_search"] = ropelite_search(ekv, ev, cfg, dev, stream)
         result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream,
                                                   T=args.prefill_tokens)
@@ -362,6 +365,52 @@ def multiquery(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, strea
     return {"queries_per_sequence": T, "ms_per_call": round(ms, 5), "us_per_query": round(ms * 1e3 / (B * T), 3),
             "cache_bytes_consumed_GBs": round(cache_bytes * T / (ms * 1e-3) / 1e9, 1),
             "query_tokens_per_s": round(B * T / (ms * 1e-3), 1)}
+
+
+def block_step(ekv, ev, cfg, dims, planes, x_d, pos_d, slot_d, seq_d, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, idx_d, dev, dt,
+               stream, cache_bytes, args):
+    """The whole attention block of the step (q = x W_q in front, W_o behind) in one call, next to
+    the same work as torch matmuls around elitekv_decode_step."""
+    import torch
+    B, S, d, n_h, d_h = cfg.batch, cfg.context, cfg.d_model, cfg.n_heads, cfg.head_dim
+    g = torch.Generator(device=dev)
+    g.manual_seed(15863)
+    W_q = (torch.randn(d, n_h, d_h, device=dev, dtype=torch.float32, generator=g) / d ** 0.5).to(dt)
+    W_o = (torch.randn(n_h, d_h, d, device=dev, dtype=torch.float32, generator=g) / (n_h * d_h) ** 0.5).to(dt)
+    y = torch.empty(B, d, dtype=dt, device=dev)
+    out = torch.empty(B, n_h, d_h, dtype=dt, device=dev)
+    ws = torch.empty(ekv.elitekv_block_step_workspace_bytes(dims, B, S, args.splits), dtype=torch.uint8, device=dev)
+    sws = torch.empty(ekv.elitekv_decode_step_workspace_bytes(dims, B, S, args.splits), dtype=torch.uint8, device=dev)
+    Wq2, Wo2 = W_q.reshape(d, n_h * d_h), W_o.reshape(n_h * d_h, d)
+    n = max(20, args.steps // 2)
+
+    def fused(i):
+        ke_p, c_p = planes[i % len(planes)]
+        ekv.elitekv_block_step(dims, x_d, pos_d, slot_d, seq_d, S, S, W_q, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, W_o, idx_d,
+                               ke_p, c_p, y, ws, n_splits=args.splits, stream=stream)
+
+    def unfused(i):
+        ke_p, c_p = planes[i % len(planes)]
+        q = torch.matmul(x_d, Wq2).reshape(B, n_h, d_h)
+        ekv.elitekv_decode_step(dims, x_d, q, pos_d, slot_d, seq_d, S, S, W_ke_d, W_dkv_d, W_uk_d, W_uv_d, idx_d, ke_p,
+                                c_p, out, sws, n_splits=args.splits, stream=stream)
+        torch.matmul(out.reshape(B, n_h * d_h), Wo2, out=y)
+
+    res = {}
+    e0, e1 = ev.create(), ev.create()
+    for name, fn in (("ms_per_call", fused), ("ms_matmuls_around_decode_step", unfused)):
+        for i in range(5):
+            fn(i)
+        ev.record(e0, stream)
+        for i in range(n):
+            fn(i)
+        ev.record(e1, stream)
+        torch.cuda.synchronize()
+        res[name] = round(ev.elapsed_ms(e0, e1) / n, 5)
+    weights = 2 * (2 * d * n_h * d_h + d * (2 * cfg.r * n_h + cfg.d_c) + cfg.d_c * n_h * (2 * d_h - 2 * cfg.r))
+    res["algorithmic_bytes"] = cache_bytes + weights
+    res["all_bytes_GBs"] = round((cache_bytes + weights) / (res["ms_per_call"] * 1e-3) / 1e9, 1)
+    return res
 
 
 def ropelite_search(ekv, ev, cfg, dev, stream, T=512, iters=3):

@@ -264,6 +264,36 @@ int elitekv_decode_step(const elitekv_dims* dims, const void* x, const void* q, 
                         int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
                         void* hip_stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * The whole attention block of one decode step (Section 2.1: q_t = x_t W^q per head in front, the
+ * concatenated heads times W^o behind; Section 5: B^k and B^v stay absorbed into the neighbouring
+ * products, nothing is materialised).  For every sequence b:
+ *     q[b]  = x[b] W_q                      (rounded to dims->dtype, as a model would hold it)
+ *     the token is appended as in elitekv_append (x[b], pos[b], slot[b])
+ *     o[b]  = elitekv_decode_attn over the sequence's cached tokens and the new one (q_pos = pos)
+ *     y[b]  = [o[b,0,:] .. o[b,n_h-1,:]] W_o
+ * with the meaning of seq_len and slot of elitekv_decode_step (the new token is the last one
+ * attended to and slot[b] = b * batch_stride_rows + seq_len[b] - 1).
+ *   W_q   [d_model, n_h, d_h]      dims->dtype
+ *   W_o   [n_h, d_h, d_model]      dims->dtype
+ *   y     [B, d_model]             written, dims->dtype
+ *   the other arguments as in elitekv_decode_step; ws: elitekv_block_step_workspace_bytes bytes.
+ * Seven launches: the first pass of the append and of x W_q in one weight-streaming launch; the sum
+ * of the query's contraction splits; the query preparation; the attention with its new-token
+ * work-groups; the merge with the up-projection; out W_o read straight from the merge's
+ * column-chunk partials; the sum of its contraction splits.
+ * EUNSUPPORTED unless the shape takes the fused path of elitekv_decode_step (bf16, matrix-core
+ * shapes, fewer than eight sequences, joint latent) and d_model and n_h d_h are multiples of 64;
+ * other errors as there.
+ * ------------------------------------------------------------------------------------------- */
+size_t elitekv_block_step_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
+                                          int32_t n_splits);
+int elitekv_block_step(const elitekv_dims* dims, const void* x, const int32_t* pos, const int64_t* slot,
+                       const int32_t* seq_len, int64_t B, int64_t max_seq_len, int64_t batch_stride_rows,
+                       const void* W_q, const void* W_ke, const void* W_dkv, const void* W_uk, const void* W_uv,
+                       const void* W_o, const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows,
+                       void* y, void* ws, size_t ws_bytes, int32_t n_splits, void* hip_stream);
+
 /* The same step for separated latents: elitekv_slrd_append followed by elitekv_slrd_decode_attn. */
 size_t elitekv_slrd_decode_step_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B,
                                                 int64_t max_seq_len, int32_t n_splits);

@@ -63,6 +63,8 @@ def _load():
         "elitekv_decode_step_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_decode_step": (C.c_int, [DP, P, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, I64, P, P, SZ, I32,
                                           P]),
+        "elitekv_block_step_workspace_bytes": (SZ, [DP, I64, I64, I32]),
+        "elitekv_block_step": (C.c_int, [DP, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, P, P, I64, P, P, SZ, I32, P]),
         "elitekv_slrd_decode_step_workspace_bytes": (SZ, [DP, I32, I64, I64, I32]),
         "elitekv_slrd_decode_step": (C.c_int, [DP, I32, P, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, P, I64, P,
                                                P, SZ, I32, P]),
@@ -257,6 +259,22 @@ def elitekv_decode_step(dims, x, q, pos, slot, seq_len, max_seq_len, batch_strid
                                   _ptr(W_uv), _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
                                   _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
     _check(st, "elitekv_decode_step")
+
+
+def elitekv_block_step_workspace_bytes(dims, B, max_seq_len, n_splits=0) -> int:
+    return _lib.elitekv_block_step_workspace_bytes(C.byref(dims), int(B), int(max_seq_len), int(n_splits))
+
+
+def elitekv_block_step(dims, x, pos, slot, seq_len, max_seq_len, batch_stride_rows, W_q, W_ke, W_dkv, W_uk, W_uv, W_o,
+                       elite_idx, ke_plane, c_plane, y, ws, n_splits=0, stream=None, B=None, plane_rows=None):
+    B = x.shape[0] if B is None else B
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_block_step(C.byref(dims), _ptr(x), _ptr(pos), _ptr(slot), _ptr(seq_len), int(B),
+                                 int(max_seq_len), int(batch_stride_rows), _ptr(W_q), _ptr(W_ke), _ptr(W_dkv),
+                                 _ptr(W_uk), _ptr(W_uv), _ptr(W_o), _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane),
+                                 int(plane_rows), _ptr(y), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
+    _check(st, "elitekv_block_step")
 
 
 def elitekv_slrd_decode_step_workspace_bytes(dims, d_ck, B, max_seq_len, n_splits=0) -> int:

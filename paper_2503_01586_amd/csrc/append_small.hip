@@ -82,6 +82,7 @@ hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream) {
   P.x = (const bf16_t*)a.x; P.T = a.T; P.W_ke = (const bf16_t*)a.W_ke; P.W_dkv = (const bf16_t*)a.W_dkv;
   P.W_dkv2 = (const bf16_t*)a.W_dkv2; P.partial = partial; P.d_ck = a.d_ck; P.d = d.d_model; P.NE = NE; P.d_c = d.d_c;
   P.kc = kc;
+  P.W_q = nullptr; P.q_cols = 0; P.x_opart = nullptr; P.x_heads = 0; P.x_chunks = 0; P.x_dh = 1;
 #define EKV_AS(TT)                                                                                   \
   append_small_kernel<TT><<<dim3(N / kAsCols, ks, (unsigned)((a.T + TT - 1) / TT)), kAsThreads,      \
                             (size_t)kc * TT * sizeof(float), stream>>>(P)

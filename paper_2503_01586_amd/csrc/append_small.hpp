@@ -22,12 +22,20 @@ struct AppendSmallParams {
   const bf16_t* W_dkv2;
   float* partial;         // [contraction splits][T][N] sums of this call
   int d_ck, d, NE, d_c, kc;
+  // optional fourth block of output columns behind the cache row: x W_q (q_cols = n_h d_h, a multiple
+  // of 64; 0 = none).  N = NE + d_c + q_cols.
+  const bf16_t* W_q;
+  int q_cols;
+  // XS = 1 only: x is not given as bf16 rows but as the column-chunk partials of the attention's
+  // up-projection, x[t, h d_h + j] = bf16(sum_c x_opart[t, h, c, j])  (what out_reduce would store)
+  const float* x_opart;
+  int x_heads, x_chunks, x_dh;
 };
 
 // Work-group (bx, by, bz) = (column block, contraction split, token tile); TT = tokens per pass,
 // KB = weight rows per thread requested at once (all loads of a work-group are in flight together
-// when kc <= 32 KB); xs = dynamic LDS of kc * TT floats.
-template <int TT, int KB>
+// when kc <= 32 KB); XS = where x comes from (see AppendSmallParams); xs = dynamic LDS of kc * TT floats.
+template <int TT, int KB, int XS = 0>
 __device__ __forceinline__ void append_small_body(const AppendSmallParams& P, int bx, int by, int bz, float* xs) {
   const bf16_t* __restrict__ x = P.x;
   const int64_t T = P.T;
@@ -39,14 +47,19 @@ __device__ __forceinline__ void append_small_body(const AppendSmallParams& P, in
   __shared__ float red[4][8][TT][8];                    // [wave][column chunk][token][8 cols]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rg = lane >> 3, cchunk = lane & 7;
-  const int N = NE + d_c;
+  const int N = NE + d_c + P.q_cols;
   const int n0 = bx * kAsCols;
   const int k0 = by * kc;
   const int64_t t0 = (int64_t)bz * TT;
 
   const bf16_t* wbase;
   int64_t wstride;
-  weight_column(n0, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wbase, &wstride);   // a block lies in one matrix
+  if (n0 < NE + d_c) {
+    weight_column(n0, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wbase, &wstride);   // a block lies in one matrix
+  } else {
+    wbase = P.W_q + (n0 - NE - d_c);
+    wstride = P.q_cols;
+  }
   wbase += cchunk * 8;
 
   // the weight rows of the first batch are requested before anything else: they are the long pole
@@ -66,8 +79,21 @@ __device__ __forceinline__ void append_small_body(const AppendSmallParams& P, in
   // queued weight traffic they would return late); the weight rows follow at once.
   auto load_x = [&](int kk, float (&xv)[TT]) {
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt)
-      xv[tt] = (kk < kc && t0 + tt < T && k0 + kk < d) ? ld(x, (t0 + tt) * d + k0 + kk) : 0.f;
+    for (int tt = 0; tt < TT; ++tt) {
+      const bool ok = kk < kc && t0 + tt < T && k0 + kk < d;
+      if (XS == 0) {
+        xv[tt] = ok ? ld(x, (t0 + tt) * d + k0 + kk) : 0.f;
+      } else {
+        float v = 0.f;
+        if (ok) {
+          const int k = k0 + kk, h = k / P.x_dh, j = k - h * P.x_dh;
+          const float* op = P.x_opart + (((t0 + tt) * P.x_heads + h) * (int64_t)P.x_chunks) * P.x_dh + j;
+          for (int c = 0; c < P.x_chunks; ++c) v += op[(int64_t)c * P.x_dh];
+          v = bf16_bits_to_f32(f32_to_bf16_bits(v));
+        }
+        xv[tt] = v;
+      }
+    }
   };
   float xfirst[TT];
   load_x(tid, xfirst);

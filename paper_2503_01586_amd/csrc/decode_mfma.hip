@@ -52,7 +52,8 @@ struct AttnMfmaParams {
   // the merge as one more split.  n_part = partials per batch row (n_splits, or n_splits + 1 here).
   int n_part;
   int fresh;              // 1: fused decode step
-  const float* fr_partial;   // [fr_ks][batch][N] sums of the append's contraction splits
+  const float* fr_partial;   // [fr_ks][batch][fr_stride] sums of the append's contraction splits (a cache row first)
+  int fr_stride;
   const float2* fr_sincos;   // [batch][n_h * r]  (sin, cos) of the new token's elite chunks
   const int64_t* fr_slot;    // [batch] destination rows
   int fr_ks;
@@ -157,7 +158,7 @@ __device__ __forceinline__ void new_token_role(const AttnMfmaParams& p, int hg, 
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         v[u] = (s0 + u < p.fr_ks)
-                   ? *reinterpret_cast<const float2*>(p.fr_partial + ((int64_t)(s0 + u) * p.batch + b) * N + n)
+                   ? *reinterpret_cast<const float2*>(p.fr_partial + ((int64_t)(s0 + u) * p.batch + b) * p.fr_stride + n)
                    : make_float2(0.f, 0.f);
 #pragma unroll
       for (int u = 0; u < 8; ++u) { a0 += v[u].x; a1 += v[u].y; }
@@ -655,11 +656,11 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.batch = (int)a.B; prm.pair_map = p.head_groups == 2 ? 1 : 0;
   prm.d_q = p.d_q; prm.d_u = p.d_u; prm.q_per_seq = a.q_per_seq;
   prm.n_part = p.n_part; prm.fresh = p.fresh;
-  prm.fr_partial = nullptr; prm.fr_sincos = nullptr; prm.fr_slot = nullptr; prm.fr_ks = 0;
+  prm.fr_partial = nullptr; prm.fr_sincos = nullptr; prm.fr_slot = nullptr; prm.fr_ks = 0; prm.fr_stride = 0;
   prm.fr_ke_out = nullptr; prm.fr_c_out = nullptr;
   if (p.fresh) {
     prm.fr_partial = (const float*)(a.ws + p.off_apart); prm.fr_sincos = (const float2*)(a.ws + p.off_sincos);
-    prm.fr_slot = a.fr_slot; prm.fr_ks = p.fr_ks;
+    prm.fr_slot = a.fr_slot; prm.fr_ks = p.fr_ks; prm.fr_stride = p.fr_stride;
     prm.fr_ke_out = (bf16_t*)a.fr_ke_out; prm.fr_c_out = (bf16_t*)a.fr_c_out;
   }
 

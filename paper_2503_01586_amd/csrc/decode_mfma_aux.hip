@@ -256,7 +256,7 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
   const elitekv_dims& d = a.dims;
   if (p.merge_batch) {
     hipError_t e = launch_merge_mfma(a, p, stream);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || a.no_out_reduce) return e;
     const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
     out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
         (const float*)(a.ws + p.off_opart), (bf16_t*)a.out, d.head_dim, p.d_u / 128, total);
@@ -279,7 +279,7 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
   else { if (d.head_dim == 128) EKV_MU(64, 128); else EKV_MU(64, 64); }
 #undef EKV_MU
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || a.no_out_reduce) return e;
   const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
   out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(opart, (bf16_t*)a.out, d.head_dim,
                                                                         p.d_u / cw, total);

@@ -73,6 +73,7 @@ static hipError_t launch_front_bt(const AppendArgs& ap, const DecodeArgs& a, con
   A.x = (const bf16_t*)ap.x; A.T = ap.T; A.W_ke = (const bf16_t*)ap.W_ke; A.W_dkv = (const bf16_t*)ap.W_dkv;
   A.W_dkv2 = (const bf16_t*)ap.W_dkv2; A.partial = (float*)(a.ws + p.off_apart); A.d_ck = ap.d_ck; A.d = d.d_model;
   A.NE = NE; A.d_c = d.d_c; A.kc = p.fr_kc;
+  A.W_q = nullptr; A.q_cols = 0; A.x_opart = nullptr; A.x_heads = 0; A.x_chunks = 0; A.x_dh = 1;
   const int n_blocks = (NE + d.d_c) / kAsCols;
   const int n_qprep = (int)(((int64_t)p.d_q * d.n_heads + kQpThreads - 1) / kQpThreads) + 1;   // + the rotation group
   decode_front_kernel<BT><<<n_qprep + n_blocks * p.fr_ks, 256, sm, stream>>>(
@@ -85,6 +86,115 @@ hipError_t launch_decode_front(const AppendArgs& ap, const DecodeArgs& a, const 
   const int bt = front_tile(a.B);
   return bt == 1 ? launch_front_bt<1>(ap, a, p, stream) : bt == 2 ? launch_front_bt<2>(ap, a, p, stream)
        : bt == 4 ? launch_front_bt<4>(ap, a, p, stream) : launch_front_bt<8>(ap, a, p, stream);
+}
+
+// ---- whole attention block of a step (Section 2.1: q = x W^q in front, [o_0 .. o_{n_h-1}] W^o behind).
+// block_front: the first pass of the append and of the query projection in one weight-streaming
+// launch (the same x, the columns of W_q simply follow the cache row's columns); q_finish adds the
+// query's split sums and rounds them (every q-prep work-group needs the whole query: summing the
+// splits there, 193 times over, was measured at 25 us).  oproj: y = out W^o by the same
+// weight-streaming body, whose x is read as the sum of the merge's column-chunk partials, so the
+// merge needs no reduction launch; y_finish adds the contraction splits of y.
+template <int TT>
+__global__ __launch_bounds__(kAsThreads) void block_front_kernel(const AppendSmallParams P) {
+  extern __shared__ __attribute__((aligned(16))) float bfx[];
+  append_small_body<TT, kFrontBatch, 0>(P, blockIdx.x, blockIdx.y, 0, bfx);
+}
+
+template <int TT>
+__global__ __launch_bounds__(kAsThreads) void oproj_kernel(const AppendSmallParams P) {
+  extern __shared__ __attribute__((aligned(16))) float opx[];
+  append_small_body<TT, kFrontBatch, 1>(P, blockIdx.x, blockIdx.y, 0, opx);
+}
+
+// q[b, c] = bf16(sum over the contraction splits of the x W_q columns of the front pass)
+__global__ __launch_bounds__(256) void q_finish_kernel(const float* __restrict__ partial, bf16_t* __restrict__ q, int ks,
+                                                       int64_t B, int stride, int col0, int q_cols) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [B, q_cols]
+  if (e >= B * q_cols) return;
+  const int64_t b = e / q_cols;
+  const int c = (int)(e - b * q_cols);
+  float a = 0.f;
+  for (int s = 0; s < ks; ++s) a += partial[((int64_t)s * B + b) * stride + col0 + c];
+  st(q, e, a);
+}
+
+__global__ __launch_bounds__(256) void y_finish_kernel(const float* __restrict__ partial, bf16_t* __restrict__ y,
+                                                       int ks, int64_t total) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [B, d_model]
+  if (e >= total) return;
+  float a = 0.f;
+  for (int s = 0; s < ks; ++s) a += partial[(int64_t)s * total + e];
+  st(y, e, a);
+}
+
+// contraction splits of a weight-streaming pass over `rows` weight rows: at most 512 rows per split
+// (sixteen per thread, all in flight at once), whole 32-row steps
+static void stream_splits(int rows, int* ks, int* kc) {
+  int s = (rows + 511) / 512;
+  if (s < 1) s = 1;
+  int c = (rows + s - 1) / s;
+  c = (c + 31) / 32 * 32;
+  *ks = (rows + c - 1) / c;
+  *kc = c;
+}
+
+bool block_step_plan(const elitekv_dims& d, int64_t B, int* fr_ks, int* fr_kc, int* y_ks, int* y_kc) {
+  if (B < 1 || B > kAsTokens || d.d_model % kAsCols || (d.n_heads * d.head_dim) % kAsCols) return false;
+  stream_splits(d.d_model, fr_ks, fr_kc);
+  stream_splits(d.n_heads * d.head_dim, y_ks, y_kc);
+  return true;
+}
+
+template <int TT>
+static hipError_t launch_block_front_tt(const AppendArgs& ap, const void* W_q, const DecodeArgs& a, const DecodePlan& p,
+                                        hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  const int NE = 2 * d.r * d.n_heads, q_cols = d.n_heads * d.head_dim;
+  AppendSmallParams A;
+  A.x = (const bf16_t*)ap.x; A.T = ap.T; A.W_ke = (const bf16_t*)ap.W_ke; A.W_dkv = (const bf16_t*)ap.W_dkv;
+  A.W_dkv2 = (const bf16_t*)ap.W_dkv2; A.partial = (float*)(a.ws + p.off_apart); A.d_ck = ap.d_ck; A.d = d.d_model;
+  A.NE = NE; A.d_c = d.d_c; A.kc = p.fr_kc;
+  A.W_q = (const bf16_t*)W_q; A.q_cols = q_cols; A.x_opart = nullptr; A.x_heads = 0; A.x_chunks = 0; A.x_dh = 1;
+  const dim3 grid((NE + d.d_c + q_cols) / kAsCols, p.fr_ks);
+  block_front_kernel<TT><<<grid, kAsThreads, (size_t)p.fr_kc * TT * sizeof(float), stream>>>(A);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t total = ap.T * (int64_t)q_cols;
+  q_finish_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(A.partial, (bf16_t*)(a.ws + p.off_qfin), p.fr_ks,
+                                                                     ap.T, p.fr_stride, NE + d.d_c, q_cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_block_front(const AppendArgs& ap, const void* W_q, const DecodeArgs& a, const DecodePlan& p,
+                              hipStream_t stream) {
+  const int tt = front_tile(a.B);
+  return tt == 1 ? launch_block_front_tt<1>(ap, W_q, a, p, stream) : tt == 2 ? launch_block_front_tt<2>(ap, W_q, a, p, stream)
+       : tt == 4 ? launch_block_front_tt<4>(ap, W_q, a, p, stream) : launch_block_front_tt<8>(ap, W_q, a, p, stream);
+}
+
+template <int TT>
+static hipError_t launch_oproj_tt(const DecodeArgs& a, const DecodePlan& p, const void* W_o, void* y, hipStream_t stream) {
+  const elitekv_dims& d = a.dims;
+  AppendSmallParams A;
+  A.x = nullptr; A.T = a.B; A.W_ke = nullptr; A.W_dkv = (const bf16_t*)W_o; A.W_dkv2 = nullptr;
+  A.partial = (float*)(a.ws + p.off_ypart); A.d_ck = d.d_model; A.d = d.n_heads * d.head_dim; A.NE = 0; A.d_c = d.d_model;
+  A.kc = p.y_kc; A.W_q = nullptr; A.q_cols = 0;
+  A.x_opart = (const float*)(a.ws + p.off_opart); A.x_heads = d.n_heads; A.x_chunks = p.d_u / p.up_cw; A.x_dh = d.head_dim;
+  const dim3 grid(d.d_model / kAsCols, p.y_ks);
+  oproj_kernel<TT><<<grid, kAsThreads, (size_t)p.y_kc * TT * sizeof(float), stream>>>(A);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t total = a.B * (int64_t)d.d_model;
+  y_finish_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>((const float*)(a.ws + p.off_ypart), (bf16_t*)y,
+                                                                     p.y_ks, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_oproj(const DecodeArgs& a, const DecodePlan& p, const void* W_o, void* y, hipStream_t stream) {
+  const int tt = front_tile(a.B);
+  return tt == 1 ? launch_oproj_tt<1>(a, p, W_o, y, stream) : tt == 2 ? launch_oproj_tt<2>(a, p, W_o, y, stream)
+       : tt == 4 ? launch_oproj_tt<4>(a, p, W_o, y, stream) : launch_oproj_tt<8>(a, p, W_o, y, stream);
 }
 
 // ---- batches of eight rows and up: the matrix-core versions of the two roles in one launch; the

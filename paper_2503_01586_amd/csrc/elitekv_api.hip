@@ -38,8 +38,9 @@ static int32_t auto_splits_generic(const elitekv_dims* d, int64_t B, int64_t max
 // Decide the path and lay the workspace out.  Returns a status.
 // d_ck = 0: joint latent; d_ck > 0: separated latents, a cache row is [c^k (d_ck) | c^v (d_c - d_ck)]
 // want_fresh: plan the fused decode step (the newest token enters as one more split) if the kernels cover it
+// block: plan the whole-block step (EUNSUPPORTED unless the fused step's kernels cover the shape)
 static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t max_seq, int32_t n_splits,
-                       DecodePlan* p, bool want_fresh = false) {
+                       DecodePlan* p, bool want_fresh = false, bool block = false) {
   int st = check_dims(d);
   if (st) return st;
   if (B < 0 || max_seq < 0 || n_splits < 0) return ELITEKV_EINVAL;
@@ -62,6 +63,13 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     int ks = 0, kc = 0;
     if (want_fresh && B > 0 && decode_front_plan(*d, d_ck, p->d_q, B, &ks, &kc)) {
       p->fresh = 1; p->fr_ks = ks; p->fr_kc = kc;
+      p->fr_stride = 2 * d->r * d->n_heads + d->d_c;
+    }
+    if (block) {
+      int yks = 0, ykc = 0;
+      if (!p->fresh || d_ck != 0 || !block_step_plan(*d, B, &ks, &kc, &yks, &ykc)) return ELITEKV_EUNSUPPORTED;
+      p->fr_ks = ks; p->fr_kc = kc; p->y_ks = yks; p->y_kc = ykc;
+      p->fr_stride += d->n_heads * d->head_dim;            // x W_q is computed alongside the cache row
     }
     int64_t ns = n_splits;
     if (ns == 0) {
@@ -93,11 +101,18 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     off = align_up(off + Bz * nh * (size_t)(p->d_u / p->up_cw) * d->head_dim * sizeof(float), 256);
     if (p->fresh) {
       p->off_apart = off;
-      off = align_up(off + (size_t)p->fr_ks * Bz * (size_t)(2 * d->r * d->n_heads + d->d_c) * sizeof(float), 256);
+      off = align_up(off + (size_t)p->fr_ks * Bz * (size_t)p->fr_stride * sizeof(float), 256);
       p->off_sincos = off;
       off = align_up(off + Bz * nh * (size_t)d->r * 2 * sizeof(float), 256);
     }
+    if (block) {
+      p->off_qfin = off;
+      off = align_up(off + Bz * nh * (size_t)d->head_dim * 2, 256);
+      p->off_ypart = off;
+      off = align_up(off + (size_t)p->y_ks * Bz * (size_t)d->d_model * sizeof(float), 256);
+    }
   } else {
+    if (block) return ELITEKV_EUNSUPPORTED;
     p->mfma = 0;
     p->head_groups = 1;
     p->n_splits = n_splits > 0 ? n_splits : auto_splits_generic(d, Bq, seq);
@@ -303,6 +318,7 @@ static DecodeArgs decode_args(const elitekv_dims* dims, int32_t d_ck, const void
   a.elite_idx = elite_idx; a.ke_plane = ke_plane; a.c_plane = c_plane; a.plane_rows = plane_rows; a.out = out;
   a.ws = (char*)ws; a.stages = stages; a.q_per_seq = q_per_seq;
   a.fr_slot = nullptr; a.fr_ke_out = nullptr; a.fr_c_out = nullptr;
+  a.no_out_reduce = 0;
   return a;
 }
 
@@ -391,6 +407,50 @@ int elitekv_decode_step(const elitekv_dims* dims, const void* x, const void* q, 
   if (!dims) return ELITEKV_ENULL;
   return step_impl(dims, 0, x, q, pos, slot, seq_len, B, max_seq_len, batch_stride_rows, W_ke, W_dkv, nullptr, W_uk,
                    W_uv, elite_idx, ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream);
+}
+
+/* ---- whole attention block of a decode step ---- */
+
+size_t elitekv_block_step_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len, int32_t n_splits) {
+  DecodePlan p;
+  if (plan_decode(dims, 0, B, max_seq_len, n_splits, &p, true, true)) return 0;
+  return p.total;
+}
+
+int elitekv_block_step(const elitekv_dims* dims, const void* x, const int32_t* pos, const int64_t* slot,
+                       const int32_t* seq_len, int64_t B, int64_t max_seq_len, int64_t batch_stride_rows,
+                       const void* W_q, const void* W_ke, const void* W_dkv, const void* W_uk, const void* W_uv,
+                       const void* W_o, const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows,
+                       void* y, void* ws, size_t ws_bytes, int32_t n_splits, void* hip_stream) {
+  if (!dims) return ELITEKV_ENULL;
+  if (B == 0) return check_dims(dims);                       // nothing to do
+  DecodePlan p;
+  int st = plan_decode(dims, 0, B, max_seq_len, n_splits, &p, true, true);
+  if (st) return st;
+  st = append_check(dims, dims->d_c, x, pos, slot, B, W_ke, W_dkv, nullptr, elite_idx, ke_plane, c_plane, plane_rows,
+                    ws, ws_bytes, 0);
+  if (st) return st;
+  // the query and the attention output stay inside the workspace: x stands in for q and y for out in the checks
+  st = decode_check(dims, p, x, pos, seq_len, B, batch_stride_rows, W_uk, W_uv, elite_idx, ke_plane, c_plane,
+                    plane_rows, y, ws, ws_bytes);
+  if (st || B == 0) return st;
+  if (!W_q || !W_o) return ELITEKV_ENULL;
+  if (!aligned16(W_q) || !aligned16(W_o)) return ELITEKV_EALIGN;
+  const hipStream_t stream = (hipStream_t)hip_stream;
+  const AppendArgs ap = append_args(dims, dims->d_c, x, pos, slot, B, W_ke, W_dkv, nullptr, elite_idx, ke_plane,
+                                    c_plane, plane_rows, nullptr);
+  DecodeArgs a = decode_args(dims, 0, (const char*)ws + p.off_qfin, pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk,
+                             W_uv, elite_idx, ke_plane, c_plane, plane_rows, nullptr, ws, 6, 1);
+  a.fr_slot = slot; a.fr_ke_out = ke_plane; a.fr_c_out = c_plane;
+  a.no_out_reduce = 1;
+  // (1) first pass of the append and of x W_q  (2) the query's contraction splits summed, rounded
+  // (3) q-prep  (4) attention, whose new-token work-groups finish the append  (5) merge +
+  // up-projection, chunk partials kept  (6) out W_o from the chunk partials  (7) sum of its splits
+  hipError_t e = launch_block_front(ap, W_q, a, p, stream);
+  if (e == hipSuccess) e = launch_qprep_rows(a, p, (float*)(a.ws + p.off_qe), (bf16_t*)(a.ws + p.off_qt), stream);
+  if (e == hipSuccess) e = launch_decode_mfma(a, p, stream);
+  if (e == hipSuccess) e = launch_oproj(a, p, W_o, y, stream);
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
 }
 
 size_t elitekv_slrd_decode_step_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B,

@@ -52,7 +52,11 @@ struct DecodePlan {
   int32_t n_part;       // partials per batch row: n_splits + fresh
   int32_t fr_ks;        // contraction splits of the step's append
   int32_t fr_kc;        // ... rows of the weight matrices per split (a multiple of 32)
-  size_t off_apart;     // the append's split sums           fp32 [fr_ks, B, 2 r n_h + d_c]
+  size_t off_apart;     // the append's split sums           fp32 [fr_ks, B, fr_stride]
+  int32_t fr_stride;    // floats per token in them: 2 r n_h + d_c, + n_h d_h when x W_q is computed alongside
+  size_t off_qfin;      // whole-block step: the query x W_q, summed over the splits   bf16 [B, n_h, d_h]
+  size_t off_ypart;     // whole-block step: split sums of the output projection  fp32 [y_ks, B, d_model]
+  int32_t y_ks, y_kc;
   size_t off_sincos;    // (sin, cos) of the rotated chunks  fp32 [B, n_h r, 2]
   size_t total;
 };
@@ -78,6 +82,8 @@ struct DecodeArgs {
   const int64_t* fr_slot;
   void* fr_ke_out;
   void* fr_c_out;
+  // whole-block step only: the merge leaves its column-chunk partials for the output projection (no out_reduce)
+  int32_t no_out_reduce;
 };
 
 struct AppendArgs {
@@ -133,6 +139,12 @@ bool qprep_mfma_supported(const elitekv_dims& d, int d_q, int64_t B);
 // how the append's contraction is split (ks splits of kc weight rows).
 bool decode_front_plan(const elitekv_dims& d, int d_ck, int d_q, int64_t B, int* ks, int* kc);
 hipError_t launch_decode_front(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
+// whole-block step: the split plans of its two weight-streaming passes, its first launch (append + x W_q)
+// and its last two (out W_o from the merge's chunk partials, then the sum of the splits)
+bool block_step_plan(const elitekv_dims& d, int64_t B, int* fr_ks, int* fr_kc, int* y_ks, int* y_kc);
+hipError_t launch_block_front(const AppendArgs& ap, const void* W_q, const DecodeArgs& a, const DecodePlan& p,
+                              hipStream_t stream);   // + the sum of the query's contraction splits into ws + off_qfin
+hipError_t launch_oproj(const DecodeArgs& a, const DecodePlan& p, const void* W_o, void* y, hipStream_t stream);
 // ... for batches of eight rows and up (matrix-core roles; includes the append's finishing launch)
 bool decode_front_mfma_supported(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p);
 hipError_t launch_decode_front_mfma(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);

@@ -213,3 +213,20 @@ def test_decode_step_argument_errors():
     assert sstep(dc // 2, B=0) == ekv.OK
     assert sstep(dc // 2, A_v=None) == ekv.ENULL
     assert ekv.elitekv_slrd_decode_step_workspace_bytes(d, 0, 1, 128) == 0
+
+
+def test_block_step_argument_errors():
+    big = ekv.make_dims(4096, 32, 128, 8, 1536, "bf16")
+    blk = lambda **kw: lib.elitekv_block_step(
+        C.byref(kw.get("dims", big)), kw.get("x", FAKE), FAKE, FAKE, FAKE, kw.get("B", 1), 128, 128,
+        kw.get("W_q", FAKE), FAKE, FAKE, FAKE, FAKE, kw.get("W_o", FAKE), FAKE, FAKE, FAKE, 128, FAKE, FAKE,
+        kw.get("wsb", 1 << 30), 0, None)
+    assert blk(B=0) == ekv.OK
+    assert blk(x=None) == ekv.ENULL and blk(W_q=None) == ekv.ENULL and blk(W_o=None) == ekv.ENULL
+    assert blk(W_o=FAKE + 8) == ekv.EALIGN
+    need = ekv.elitekv_block_step_workspace_bytes(big, 1, 128)
+    assert need > 0 and blk(wsb=need - 1) == ekv.EWORKSPACE
+    # shapes outside the fused path of the decode step are not covered
+    assert blk(B=8) == ekv.EUNSUPPORTED
+    assert blk(dims=_dims()) == ekv.EUNSUPPORTED                      # fp32
+    assert ekv.elitekv_block_step_workspace_bytes(big, 8, 128) == 0
