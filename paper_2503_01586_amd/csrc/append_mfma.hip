@@ -263,16 +263,15 @@ __global__ __launch_bounds__(256) void append_gemm_kernel(
 // ---------------------------------------------------------------------------------------------
 // append_gemm_dma: the same GEMM with both operands brought in by direct global->LDS loads into a
 // ring of NS stages of 32 contraction rows (no register staging, one barrier per stage, the loads
-// of the next NS-2 stages in flight while a stage is multiplied).  2 x WNW waves: two along the
-// 128 columns, WNW along the tokens; the widest tile (256 tokens) runs eight waves, two per SIMD.  A direct load writes 1 KiB
+// of the next NS-2 stages in flight while a stage is multiplied).  CM x WNW waves: CM along the
+// 64 CM columns, WNW along the tokens; the widest tiles run eight waves, two per SIMD.  A direct load writes 1 KiB
 // (64 lanes x 16 bytes) contiguously, so the LDS layouts are made of 1 KiB blocks:
-//   weights  [32 k][128 n]: blocks of 8 rows x 128 bytes, 16-byte pieces XOR-swizzled by row
-//            (conflict-free transposed reads), block (kb, nb) at (kb*2 + nb) KiB;
+//   weights  [32 k][64 CM n]: blocks of 8 rows x 128 bytes, 16-byte pieces XOR-swizzled by row
+//            (conflict-free transposed reads), block (kb, nb) at (kb*CM + nb) KiB;
 //   tokens   [BN t][32 k]:  blocks of 16 rows x 64 bytes, pieces XOR-swizzled by row.
 // Needs d_model % 32 == 0 (whole stages); other shapes take append_gemm_kernel.
 // ---------------------------------------------------------------------------------------------
 constexpr int kGdStage = 32;                    // contraction rows per stage
-constexpr int kGdA = 8 * 1024;                  // bytes of a weight stage
 
 __device__ __forceinline__ int gd_swz8(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 // token blocks (16 rows x 64 bytes): a 16-byte read of 16 lanes = 16 rows at one logical piece; the four
@@ -283,13 +282,16 @@ __device__ __forceinline__ void gd_dma16(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
 }
 
-// WN = 32-token tiles per wave, WNW = waves along the tokens (x 2 waves along the columns)
-template <int WN, int NS, int WNW>
+// WN = 32-token tiles per wave, WNW = waves along the tokens, CM = waves along the columns (64 columns each)
+template <int WN, int NS, int WNW, int CM>
 struct GemmDmaLayout {
-  static constexpr int BN = 32 * WN * WNW;
-  static constexpr int NWAVES = 2 * WNW;
+  static constexpr int BN = 32 * WN * WNW;                    // tokens per work-group
+  static constexpr int COLS = 64 * CM;                        // output columns per work-group
+  static constexpr int NWAVES = CM * WNW;
+  static constexpr int A_BYTES = kGdStage * COLS * 2;         // weight stage
+  static constexpr int WB = A_BYTES / 1024;                   // ... in 1 KiB blocks (kb = 0..3, nb = 0..CM-1)
   static constexpr int B_BYTES = BN * 64;                     // token stage
-  static constexpr int STAGE = kGdA + B_BYTES;
+  static constexpr int STAGE = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = NS * STAGE;
   static constexpr int LOADS = STAGE / 1024;                  // direct loads per stage per work-group
   static constexpr int LPW = LOADS / NWAVES;                  // ... per wave
@@ -298,45 +300,45 @@ struct GemmDmaLayout {
   static_assert(NS >= 3 && NS <= 12 && (NS - 2) * LPW <= 63, "ring depth outside what the load counter can express");
 };
 
-template <int WN, int NS, int WNW>
-__global__ __launch_bounds__(128 * WNW) void append_gemm_dma_kernel(
+template <int WN, int NS, int WNW, int CM>
+__global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
     const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
     const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const bf16_t* __restrict__ W_dkv2, int d_ck,
     const int32_t* __restrict__ elite_idx, bf16_t* __restrict__ ke_plane, bf16_t* __restrict__ c_plane,
     int64_t plane_rows, int d, int n_h, int d_h, int r, int d_c, RopeTable rope) {
-  using L = GemmDmaLayout<WN, NS, WNW>;
+  using L = GemmDmaLayout<WN, NS, WNW, CM>;
   extern __shared__ __attribute__((aligned(16))) char gsm[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
+  const int wm = wave % CM, wn = wave / CM;
   const int n32 = lane & 31, hi = lane >> 5, i16 = lane & 15, q16 = lane >> 4;
   const int NE = 2 * r * n_h;
   // Work-groups go to the eight XCDs round-robin by linear index.  All column blocks of one token
   // block are given to the SAME XCD, one after the other, so the token tile is fetched into that
   // XCD's L2 once and re-used by every column block instead of being fetched by eight L2s.
-  const int col_blocks = (NE + d_c) / kGmCols;
+  const int col_blocks = (NE + d_c) / L::COLS;
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
   const int64_t tblock = (int64_t)(seq / col_blocks) * 8 + xcd;
-  const int n0 = (seq % col_blocks) * kGmCols;
+  const int n0 = (seq % col_blocks) * L::COLS;
   const int64_t t0 = tblock * L::BN;
   if (t0 >= T) return;
   const int nstages = d / kGdStage;
 
-  // ---- loader.  Wave w issues loads w*LPW .. w*LPW+LPW-1 of a stage; load index < 8 is weight block
-  // (kb = idx/2, nb = idx%2), the others are token blocks of 16 rows.
+  // ---- loader.  Wave w issues loads w*LPW .. w*LPW+LPW-1 of a stage; load index < WB is weight block
+  // (kb = idx / CM, nb = idx % CM), the others are token blocks of 16 rows.
   const char* gsrc[L::LPW];      // this lane's global address for the next stage to be requested
   int64_t gstep[L::LPW];         // bytes to advance per stage
 #pragma unroll
   for (int u = 0; u < L::LPW; ++u) {
     const int idx = wave * L::LPW + u;
-    if (idx < 8) {
-      const int kb = idx >> 1, nb = idx & 1, row = lane >> 3, pc = (lane & 7) ^ gd_swz8(row);
+    if (idx < L::WB) {
+      const int kb = idx / CM, nb = idx % CM, row = lane >> 3, pc = (lane & 7) ^ gd_swz8(row);
       const bf16_t* wb;
       int64_t ws;
       weight_column(n0 + nb * 64, NE, d_ck, d_c, W_ke, W_dkv, W_dkv2, &wb, &ws);
       gsrc[u] = reinterpret_cast<const char*>(wb + (int64_t)(kb * 8 + row) * ws + pc * 8);
       gstep[u] = (int64_t)kGdStage * ws * 2;
     } else {
-      const int tb = idx - 8, row = lane >> 2, pc = (lane & 3) ^ gd_swz4(row);
+      const int tb = idx - L::WB, row = lane >> 2, pc = (lane & 3) ^ gd_swz4(row);
       const int64_t t = min(t0 + tb * 16 + row, T - 1);        // rows past the end repeat the last token
       gsrc[u] = reinterpret_cast<const char*>(x + t * d + pc * 8);
       gstep[u] = (int64_t)kGdStage * 2;
@@ -369,14 +371,14 @@ __global__ __launch_bounds__(128 * WNW) void append_gemm_dma_kernel(
     for (int e = 0; e < 2; ++e) {
       const int r8 = 4 * e + (i16 >> 2);
       const int piece = (i << 2) | ((q16 & 1) << 1) | ((i16 & 3) >> 1);       // 16-byte piece inside the 128-byte row
-      a_off[i][e] = ((q16 >> 1) * 2 + wm) * 1024 + r8 * 128 + ((piece ^ gd_swz8(r8)) << 4) + ((i16 & 1) << 3);
+      a_off[i][e] = ((q16 >> 1) * CM + wm) * 1024 + r8 * 128 + ((piece ^ gd_swz8(r8)) << 4) + ((i16 & 1) << 3);
     }
   // tokens: row n32 of tile j (block 2*(wn*WN + j) + n32/16), piece 2*ks + hi
   int b_off[2];                  // [ks]
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     const int row = n32 & 15;
-    b_off[ks] = kGdA + (wn * WN * 2 + (n32 >> 4)) * 1024 + row * 64 + (((2 * ks + hi) ^ gd_swz4(row)) << 4);
+    b_off[ks] = L::A_BYTES + (wn * WN * 2 + (n32 >> 4)) * 1024 + row * 64 + (((2 * ks + hi) ^ gd_swz4(row)) << 4);
   }
 
   // wait until this wave's direct loads have landed except those of the `ahead` most recent stages
@@ -402,8 +404,9 @@ __global__ __launch_bounds__(128 * WNW) void append_gemm_dma_kernel(
     for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const am_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 4096 + a_off[i][0]));
-        const am_s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 4096 + a_off[i][1]));
+        // a k-step is two 8-row weight blocks per 64-column block: 2 * CM KiB
+        const am_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 2048 * CM + a_off[i][0]));
+        const am_s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 2048 * CM + a_off[i][1]));
         o.a[ks][i] = __builtin_bit_cast(am_bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
       }
 #pragma unroll
@@ -463,18 +466,18 @@ static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <int WN, int NS, int WNW>
+template <int WN, int NS, int WNW, int CM>
 static hipError_t launch_gemm_dma(const AppendArgs& a, hipStream_t stream) {
-  using L = GemmDmaLayout<WN, NS, WNW>;
+  using L = GemmDmaLayout<WN, NS, WNW, CM>;
   const elitekv_dims& d = a.dims;
   const int N = 2 * d.r * d.n_heads + d.d_c;
   static LdsLimit lds_limit;
-  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW>),
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW, CM>),
                                         L::LDS_BYTES);
   if (le != hipSuccess) return le;
   const int64_t tblocks = (a.T + L::BN - 1) / L::BN;
-  const dim3 grid((unsigned)((tblocks + 7) / 8 * 8 * (N / kGmCols)));   // token blocks padded to whole rounds of 8 XCDs
-  append_gemm_dma_kernel<WN, NS, WNW><<<grid, 128 * WNW, L::LDS_BYTES, stream>>>(
+  const dim3 grid((unsigned)((tblocks + 7) / 8 * 8 * (N / L::COLS)));   // token blocks padded to whole rounds of 8 XCDs
+  append_gemm_dma_kernel<WN, NS, WNW, CM><<<grid, 64 * CM * WNW, L::LDS_BYTES, stream>>>(
       (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
       (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
       d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, rope_table(d.rope_base, d.head_dim));
@@ -486,9 +489,16 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
   const int64_t col_blocks = (2 * d.r * d.n_heads + d.d_c) / kGmCols;
   // the widest token tile that still gives every compute unit work
   if (d.d_model % kGdStage == 0) {
-    if (col_blocks * ((a.T + 255) / 256) >= 512) return launch_gemm_dma<2, 6, 4>(a, stream);
-    if (col_blocks * ((a.T + 127) / 128) >= 256) return launch_gemm_dma<2, 4, 2>(a, stream);
-    return launch_gemm_dma<1, 6, 2>(a, stream);
+    const int N = 2 * d.r * d.n_heads + d.d_c;
+    // 256 x 256 tiles, one work-group per compute unit: a third fewer operand bytes per flop, 13 % faster
+    // than 256 x 128 whenever its work-groups fill the 256 compute units evenly -- one full round, or
+    // enough rounds that the ragged last one costs less than that (measured: slower at 260-320
+    // work-groups and at 128, faster at 224-256 and from 360 on)
+    const int64_t wide = N % 256 == 0 ? (N / 256) * ((a.T + 255) / 256) : 0;
+    if (wide >= 352 || (wide >= 224 && wide <= 256)) return launch_gemm_dma<4, 4, 2, 4>(a, stream);
+    if (col_blocks * ((a.T + 255) / 256) >= 512) return launch_gemm_dma<2, 6, 4, 2>(a, stream);
+    if (col_blocks * ((a.T + 127) / 128) >= 256) return launch_gemm_dma<2, 4, 2, 2>(a, stream);
+    return launch_gemm_dma<1, 6, 2, 2>(a, stream);
   }
   if (col_blocks * ((a.T + 255) / 256) >= 1024) return launch_gemm_wn<4>(a, stream);
   return launch_gemm_wn<1>(a, stream);

@@ -109,14 +109,17 @@ def test_full_size_append_and_decode(name):
     assert err <= TOL[dt], "decode step: max-abs-rel %g" % err
 
 
-def test_prefill_append_with_wide_token_tiles():
-    """An append large enough for the widest token tiles of the GEMM path (7B shape at 12.5 % cache,
-    33 100 tokens, not a multiple of any tile): sampled rows against the oracle, and the rows
+@pytest.mark.parametrize("name,T", [("7b_12_b64_s2048", 33100), ("7b_25_b1_s32768", 16500),
+                                    ("13b_25_b16_s8192", 13100)])
+def test_prefill_append_with_wide_token_tiles(name, T):
+    """Appends large enough for the widest tiles of the GEMM path (256 tokens x 256 columns; token
+    counts that are not a multiple of any tile): sampled rows against the oracle -- every 32-token
+    sub-tile of the first and of the ragged last tile, and rows around tile borders -- and the rows
     around the destination range stay untouched."""
-    cfg = synth.CONFIGS["7b_12_b64_s2048"]
+    cfg = synth.CONFIGS[name]
     n_h, d_h, r, d_c, d = cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c, cfg.d_model
     dims = dims_of(cfg)
-    T, guard = 33100, 7
+    guard = 7
     rng = synth.rng_for(cfg.index, stream=11)
     idx = synth.draw_elite_idx(rng, n_h, d_h, r)
     W_ke, W_dkv, _, _ = synth.draw_weights(rng, d, n_h, d_h, r, d_c)
@@ -132,7 +135,43 @@ def test_prefill_append_with_wide_token_tiles():
     assert bool((ke[:guard] == 3.0).all()) and bool((ke[T + guard:] == 3.0).all())
     assert bool((c[:guard] == 3.0).all()) and bool((c[T + guard:] == 3.0).all())
     Wke64, Wdkv64 = host64(Wked), host64(Wdkvd)
-    for t in (0, 1, 255, 256, 257, 12345, 32767, 32768, T - 2, T - 1):
-        ke_ref, c_ref = orc.append(host64(xd[t:t + 1]), pos_h[t:t + 1], Wke64, Wdkv64, idx, d_h, cfg.rope_base)
-        assert orc.max_abs_rel(host64(c[slot_h[t]]), c_ref[0]) <= TOL["bf16"]
-        assert orc.max_abs_rel(host64(ke[slot_h[t]]), ke_ref[0]) <= TOL["bf16"]
+    last0 = (T - 1) // 256 * 256
+    rows = sorted(set(list(range(0, 256, 19)) + [1, 31, 32, 127, 128, 255, 256, 257, 2047, 2048, 12345 % T, T // 2]
+                      + list(range(last0, T, 13)) + [T - 2, T - 1]))
+    rows_t = torch.tensor(rows, device=DEV)
+    ke_ref, c_ref = orc.append(host64(xd[rows_t]), pos_h[rows], Wke64, Wdkv64, idx, d_h, cfg.rope_base)
+    srows = torch.tensor(slot_h[rows], device=DEV)
+    for i, t in enumerate(rows):
+        assert orc.max_abs_rel(host64(c[srows[i]]), c_ref[i]) <= TOL["bf16"], "latent row %d" % t
+        assert orc.max_abs_rel(host64(ke[srows[i]]), ke_ref[i]) <= TOL["bf16"], "elite row %d" % t
+
+
+def test_slrd_prefill_append_with_wide_tiles():
+    """S-LRD prefill through the widest GEMM tiles, with the A^k / A^v boundary (column 512 + 576)
+    inside a 256-column tile: sampled rows against the oracle."""
+    d, n_h, d_h, r, d_ck, d_cv, T = 4096, 32, 128, 8, 576, 960, 16500
+    dims = ekv.make_dims(d, n_h, d_h, r, d_ck + d_cv, "bf16", 10000.0)
+    rng = np.random.default_rng(20250)
+    idx = synth.draw_elite_idx(rng, n_h, d_h, r)
+    W_ke = rng.standard_normal((d, n_h, 2 * r)) / np.sqrt(d)
+    A_k = rng.standard_normal((d, d_ck)) / np.sqrt(d)
+    A_v = rng.standard_normal((d, d_cv)) / np.sqrt(d)
+    Wked, Akd, Avd = dev(W_ke, "bf16"), dev(A_k, "bf16"), dev(A_v, "bf16")
+    xd = torch.from_numpy(rng.standard_normal((T, d), dtype=np.float32)).to(torch.bfloat16).to(DEV)
+    pos_h = rng.integers(0, 4096, size=T)
+    slot_h = rng.permutation(T + 5)[:T]
+    ke = torch.full((T + 5, n_h, 2 * r), 3.0, dtype=torch.bfloat16, device=DEV)
+    c = torch.full((T + 5, d_ck + d_cv), 3.0, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(max(ekv.elitekv_slrd_append_workspace_bytes(dims, d_ck, T), 16), dtype=torch.uint8, device=DEV)
+    ekv.elitekv_slrd_append(dims, d_ck, xd, i32(pos_h), i64(slot_h), Wked, Akd, Avd, i32(idx), ke, c, ws=ws)
+    torch.cuda.synchronize()
+    untouched = torch.tensor(np.setdiff1d(np.arange(T + 5), slot_h), device=DEV)
+    assert bool((c[untouched] == 3.0).all()) and bool((ke[untouched] == 3.0).all())
+    rows = sorted(set(list(range(0, 256, 23)) + [255, 256, 8191, 8192, 16383, 16384] + list(range(16384, T, 11))))
+    ke_ref, ck_ref, cv_ref = orc.slrd_append(host64(xd[torch.tensor(rows, device=DEV)]), pos_h[rows], host64(Wked),
+                                             host64(Akd), host64(Avd), idx, d_h, 10000.0)
+    srows = torch.tensor(slot_h[rows], device=DEV)
+    c_g, ke_g = host64(c[srows]), host64(ke[srows])
+    assert orc.max_abs_rel(c_g[:, :d_ck], ck_ref) <= TOL["bf16"]
+    assert orc.max_abs_rel(c_g[:, d_ck:], cv_ref) <= TOL["bf16"]
+    assert orc.max_abs_rel(ke_g, ke_ref) <= TOL["bf16"]
