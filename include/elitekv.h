@@ -187,6 +187,28 @@ int elitekv_multiquery_attn(const elitekv_dims* dims, const void* q, const int32
                             int32_t n_splits, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Many queries per sequence (a prefill, a long prompt chunk).  Same arguments, layouts, meaning of
+ * kv_len and result as elitekv_multiquery_attn (Section 2.1: query t sees the keys and values of
+ * the tokens up to step t), but the multiplications are ordered for many queries: the keys
+ * [stored rotated elite dims | c B^k_J,h] and values c B^v_J,h (Section 3.1 score equation,
+ * Section 3.2 J-LRD) of the first max_seq_len rows of every sequence are rebuilt ONCE into the
+ * workspace, and every query then runs ordinary attention (Section 2.1) against them, instead of
+ * absorbing B^k into each query (Section 5), which costs d_c / d_h times more per (query, key).
+ *   q [B, T, n_h, d_h]   q_pos [B * T]   kv_len [B * T]   out [B, T, n_h, d_h]   (device pointers)
+ * bf16, head_dim 128, r in {4, 8}, d_c a multiple of 32, n_h (2 d_h - 2 r) a multiple of 128 and
+ * max_seq_len > 64 run this path; every other shape is handed to elitekv_multiquery_attn (and its
+ * limits apply).  Rows of a sequence beyond the largest kv_len of its queries are never read by the
+ * attention, but the first max_seq_len rows of the latent plane are read by the rebuild.
+ * Workspace: the _workspace_bytes function (about B * max_seq_len * n_h * (2 d_h - 2 r) * 2 bytes).
+ * Errors as elitekv_decode_attn; EUNSUPPORTED if B * T > 2^24.
+ * ------------------------------------------------------------------------------------------- */
+size_t elitekv_prefill_attn_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t T, int64_t max_seq_len);
+int elitekv_prefill_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos, const int32_t* kv_len,
+                         int64_t B, int64_t T, int64_t max_seq_len, int64_t batch_stride_rows, const void* W_uk,
+                         const void* W_uv, const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                         int64_t plane_rows, void* out, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Separated low-rank decomposition (Section 3.2, "Separated Low-Rank Decomposition"):
  *     W^k_{e^,0:n_h-1} ~ A^k B^k_S,   W^v_{0:n_h-1} ~ A^v B^v_S,
  * a token caches two latents, c^k = x A^k (d_ck columns) and c^v = x A^v (d_cv columns), next to its

@@ -54,6 +54,8 @@ def _load():
         "elitekv_ropelite_search": (C.c_int, [P, P, P, I64, I32, I32, I32, C.c_double, P, P, P, SZ, P]),
         "elitekv_multiquery_workspace_bytes": (SZ, [DP, I64, I64, I64, I32]),
         "elitekv_multiquery_attn": (C.c_int, [DP, P, P, P, I64, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32, P]),
+        "elitekv_prefill_attn_workspace_bytes": (SZ, [DP, I64, I64, I64]),
+        "elitekv_prefill_attn": (C.c_int, [DP, P, P, P, I64, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, P]),
         "elitekv_slrd_param_count": (C.c_int, [DP, I32, C.POINTER(I64)]),
         "elitekv_slrd_append_workspace_bytes": (SZ, [DP, I32, I64]),
         "elitekv_slrd_append": (C.c_int, [DP, I32, P, P, P, I64, P, P, P, P, P, P, I64, P, SZ, P]),
@@ -205,6 +207,23 @@ def elitekv_multiquery_attn(dims, q, q_pos, kv_len, max_seq_len, batch_stride_ro
                                       _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows), _ptr(out),
                                       _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
     _check(st, "elitekv_multiquery_attn")
+
+
+def elitekv_prefill_attn_workspace_bytes(dims, B, T, max_seq_len) -> int:
+    return _lib.elitekv_prefill_attn_workspace_bytes(C.byref(dims), int(B), int(T), int(max_seq_len))
+
+
+def elitekv_prefill_attn(dims, q, q_pos, kv_len, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx, ke_plane,
+                         c_plane, out, ws, stream=None, plane_rows=None):
+    """q [B, T, n_h, d_h]; q_pos, kv_len [B, T] (int32)."""
+    B, T = q.shape[0], q.shape[1]
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_prefill_attn(C.byref(dims), _ptr(q), _ptr(q_pos), _ptr(kv_len), int(B), int(T),
+                                   int(max_seq_len), int(batch_stride_rows), _ptr(W_uk), _ptr(W_uv),
+                                   _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows), _ptr(out),
+                                   _ptr(ws), ws_bytes, _stream(stream))
+    _check(st, "elitekv_prefill_attn")
 
 
 def elitekv_slrd_param_count(dims, d_ck) -> int:

@@ -518,6 +518,36 @@ int elitekv_multiquery_attn(const elitekv_dims* dims, const void* q, const int32
                      ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, 7, (int32_t)T);
 }
 
+/* ---- many queries per sequence (prefill): K and V rebuilt once per cached row, then flash attention ---- */
+
+size_t elitekv_prefill_attn_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t T, int64_t max_seq_len) {
+  if (check_dims(dims) || B < 0 || T < 1 || max_seq_len < 0) return 0;
+  if (prefill_flash_supported(*dims, T, max_seq_len)) return prefill_flash_workspace(*dims, B, T, max_seq_len);
+  return elitekv_multiquery_workspace_bytes(dims, B, T, max_seq_len, 0);
+}
+
+int elitekv_prefill_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos, const int32_t* kv_len,
+                         int64_t B, int64_t T, int64_t max_seq_len, int64_t batch_stride_rows, const void* W_uk,
+                         const void* W_uv, const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                         int64_t plane_rows, void* out, void* ws, size_t ws_bytes, void* hip_stream) {
+  int st = check_dims(dims);
+  if (st) return st;
+  if (B < 0 || T < 1 || max_seq_len < 0 || batch_stride_rows < 0 || plane_rows < 0) return ELITEKV_EINVAL;
+  if (!prefill_flash_supported(*dims, T, max_seq_len))       // other shapes: every query as a decode query
+    return elitekv_multiquery_attn(dims, q, q_pos, kv_len, B, T, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+                                   ke_plane, c_plane, plane_rows, out, ws, ws_bytes, 0, hip_stream);
+  if (B == 0) return ELITEKV_OK;
+  if (B * T > (1LL << 24) || B * dims->n_heads > (1 << 20)) return ELITEKV_EUNSUPPORTED;
+  if (!q || !q_pos || !kv_len || !W_uk || !W_uv || !elite_idx || !ke_plane || !c_plane || !out || !ws) return ELITEKV_ENULL;
+  if (!aligned16(q) || !aligned16(W_uk) || !aligned16(W_uv) || !aligned16(ke_plane) || !aligned16(c_plane) ||
+      !aligned16(out) || !aligned16(ws))
+    return ELITEKV_EALIGN;
+  if (ws_bytes < prefill_flash_workspace(*dims, B, T, max_seq_len)) return ELITEKV_EWORKSPACE;
+  const DecodeArgs a = decode_args(dims, 0, q, q_pos, kv_len, B * T, max_seq_len, batch_stride_rows, W_uk, W_uv,
+                                   elite_idx, ke_plane, c_plane, plane_rows, out, ws, 7, (int32_t)T);
+  return launch_prefill_flash(a, B, T, (hipStream_t)hip_stream) == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
 /* ---- separated low-rank decomposition (two latents per token, stored side by side) ---- */
 
 int elitekv_slrd_param_count(const elitekv_dims* dims, int32_t d_ck, int64_t* n_params) {

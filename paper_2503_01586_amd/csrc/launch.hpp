@@ -152,6 +152,11 @@ bool merge_mfma_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_s
 hipError_t launch_merge_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
+// many queries per sequence: keys and values rebuilt from the latent once per cached row (with the append's
+// matrix-core GEMM), then flash attention; a.B = B * T query rows, a.seq_len = the visible rows of each
+bool prefill_flash_supported(const elitekv_dims& d, int64_t T, int64_t max_seq_len);
+size_t prefill_flash_workspace(const elitekv_dims& d, int64_t B, int64_t T, int64_t max_seq_len);
+hipError_t launch_prefill_flash(const DecodeArgs& a, int64_t B, int64_t T, hipStream_t stream);
 hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);
 size_t search_workspace_bytes(int64_t T, int n_h, int d_h);
 hipError_t launch_ropelite_search(const float* q, const float* k, const int32_t* pos, int64_t T, int n_h, int d_h,

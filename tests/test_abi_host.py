@@ -190,6 +190,28 @@ def test_multiquery_argument_errors():
     assert mq(wsb=need - 1) == ekv.EWORKSPACE
 
 
+def test_prefill_argument_errors():
+    big = ekv.make_dims(4096, 32, 128, 8, 1536, "bf16")
+    pf = lambda **kw: lib.elitekv_prefill_attn(C.byref(kw.get("dims", big)), kw.get("q", FAKE), FAKE, FAKE, kw.get("B", 2),
+                                               kw.get("T", 300), kw.get("S", 512), 512, FAKE, kw.get("W_uv", FAKE), FAKE,
+                                               FAKE, FAKE, 1024, FAKE, FAKE, kw.get("wsb", 1 << 40), None)
+    assert pf(T=0) == ekv.EINVAL and pf(B=-1) == ekv.EINVAL and pf(S=-1) == ekv.EINVAL
+    assert pf(B=0) == ekv.OK
+    assert pf(q=None) == ekv.ENULL
+    assert pf(W_uv=FAKE + 2) == ekv.EALIGN
+    assert pf(B=1 << 20, T=1 << 10) == ekv.EUNSUPPORTED
+    need = ekv.elitekv_prefill_attn_workspace_bytes(big, 2, 300, 512)
+    # the rebuilt keys and values of 2 x 512 rows dominate: n_h (2 d_h - 2 r) bf16 elements per row
+    rebuilt = 2 * 512 * 32 * (2 * 128 - 16) * 2
+    assert rebuilt <= need <= rebuilt + 2 * 300 * 32 * 128 * 2 + 512 * 12 + 4 * 256
+    assert pf(wsb=need - 1) == ekv.EWORKSPACE
+    # shapes outside the flash path (fp32, short caches) are the several-queries call, with its limits
+    d = _dims()
+    assert ekv.elitekv_prefill_attn_workspace_bytes(d, 2, 3, 128) == ekv.elitekv_multiquery_workspace_bytes(d, 2, 3, 128)
+    assert ekv.elitekv_prefill_attn_workspace_bytes(big, 2, 300, 64) == ekv.elitekv_multiquery_workspace_bytes(big, 2, 300, 64)
+    assert pf(dims=d, B=300, T=300) == ekv.EUNSUPPORTED
+
+
 def test_decode_step_argument_errors():
     d = _dims()
     step = lambda **kw: lib.elitekv_decode_step(

@@ -1,0 +1,122 @@
+"""GPU parity of attention with MANY queries per sequence (elitekv_prefill_attn: keys and values
+rebuilt once per cached row, then flash attention) against the float64 oracle, through the C ABI.
+The oracle computes every query by the decode definition (reconstructed keys and values, textbook
+attention), so it is run on a seeded sample of the queries (all heads of each); every query is also
+compared with the library's own absorbed-form path (elitekv_multiquery_attn), which has its own
+oracle test.  Bound: 2e-2 (bf16), max-abs-rel."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2503_01586_amd as ekv
+from oracle import elitekv_oracle as orc
+
+from gpu_util import DEV, TOL, dev, dims_of, host64, i32
+from test_gpu_parity import _draw, shape
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # name: (shape, cached rows per sequence, T, kind of visibility, sampled queries per sequence)
+    # causal: the T queries are the last T tokens of the sequence; random: any visible length, zeros included
+    "small_two_seqs_causal": (shape(64, 8, 128, 8, 256, "bf16"), [300, 191], 150, "causal", 24),
+    "small_three_blocks_random": (shape(64, 8, 128, 8, 256, "bf16"), [333], 300, "random", 32),
+    "small_full_prefill_r4": (shape(64, 8, 128, 4, 384, "bf16"), [257, 129], 129, "causal", 20),
+    "7b_full_prefill": (shape(64, 32, 128, 8, 1536, "bf16"), [200], 200, "causal", 10),
+    "7b_12pct_chunk_over_context": (shape(64, 32, 128, 4, 768, "bf16"), [130, 257], 70, "causal", 6),
+    "13b_full_prefill": (shape(64, 40, 128, 8, 1920, "bf16"), [97], 97, "causal", 6),
+}
+
+
+def _run(name):
+    sh, rows, T, kind, n_sample = CASES[name]
+    dt = sh["dtype"]
+    B, stride, S = len(rows), max(rows) + 3, max(rows)
+    n_h, d_h = sh["n_heads"], sh["head_dim"]
+    rng, idx, W_ke, W_dkv, W_uk, W_uv, x, _ = _draw(sh, B * stride, B, 4200 + len(name))
+    q = rng.standard_normal((B, T, n_h, d_h))
+    dims = dims_of(sh)
+    pos = np.tile(np.arange(stride), B)
+    ke64, c64 = orc.append(x, pos, W_ke, W_dkv, idx, d_h, sh["rope_base"])
+    # rows a sequence does not own yet hold NaN: nothing may read them into a result
+    # (the rebuild does read the first S latent rows of every sequence; what it makes of them is never used)
+    for b, n in enumerate(rows):
+        ke64[b * stride + n:(b + 1) * stride] = np.nan
+        c64[b * stride + n:(b + 1) * stride] = np.nan
+    ked, cd = dev(ke64, dt), dev(c64, dt)
+    qd, Wukd, Wuvd = dev(q, dt), dev(W_uk, dt), dev(W_uv, dt)
+    if kind == "causal":
+        q_pos = np.array([[max(n - T + t, 0) for t in range(T)] for n in rows])
+        kv_len = np.array([[max(n - T + t + 1, 0) for t in range(T)] for n in rows])
+    else:
+        kv_len = np.stack([rng.integers(0, n + 1, size=T) for n in rows])
+        kv_len[:, ::17] = 0
+        kv_len[:, 5] = np.array(rows)
+        q_pos = np.maximum(kv_len - 1, 0)
+    out = torch.full((B, T, n_h, d_h), float("nan"), dtype=ekv.torch_dtype(dims), device=DEV)
+    nws = ekv.elitekv_prefill_attn_workspace_bytes(dims, B, T, S)
+    assert nws > 0
+    ws = torch.full((nws,), 0xFF, dtype=torch.uint8, device=DEV)      # poisoned: nothing may depend on old contents
+    ekv.elitekv_prefill_attn(dims, qd, i32(q_pos.reshape(-1)), i32(kv_len.reshape(-1)), S, stride, Wukd, Wuvd,
+                             i32(idx), ked, cd, out, ws)
+    torch.cuda.synchronize()
+    o = host64(out)
+    assert np.all(np.isfinite(o)), name
+    assert np.all(o[kv_len == 0] == 0.0)
+    return sh, rows, T, B, stride, rng, idx, qd, q_pos, kv_len, ked, cd, Wukd, Wuvd, dims, o, n_sample, S
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_prefill_matches_oracle_on_sampled_queries(name):
+    sh, rows, T, B, stride, rng, idx, qd, q_pos, kv_len, ked, cd, Wukd, Wuvd, dims, o, n_sample, S = _run(name)
+    n_h, d_h = sh["n_heads"], sh["head_dim"]
+    # first, last, block edges and random queries
+    pick = sorted(set([0, T - 1, min(127, T - 1), min(128, T - 1)] + list(rng.choice(T, size=n_sample, replace=False))))
+    ke_h = np.nan_to_num(host64(ked)).reshape(B, stride, n_h, -1)
+    c_h = np.nan_to_num(host64(cd)).reshape(B, stride, -1)
+    ref = orc.multiquery_attn(host64(qd)[:, pick], q_pos[:, pick], ke_h, c_h, kv_len[:, pick], host64(Wukd),
+                              host64(Wuvd), idx, d_h, sh["rope_base"])
+    assert orc.max_abs_rel(o[:, pick], ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("name", ["small_two_seqs_causal", "small_three_blocks_random", "7b_full_prefill"])
+def test_prefill_agrees_with_the_absorbed_form_on_every_query(name):
+    sh, rows, T, B, stride, rng, idx, qd, q_pos, kv_len, ked, cd, Wukd, Wuvd, dims, o, n_sample, S = _run(name)
+    out2 = torch.full_like(torch.empty(B, T, sh["n_heads"], sh["head_dim"], dtype=torch.bfloat16, device=DEV), float("nan"))
+    ws = torch.empty(ekv.elitekv_multiquery_workspace_bytes(dims, B, T, S), dtype=torch.uint8, device=DEV)
+    ked2, cd2 = torch.nan_to_num(ked), torch.nan_to_num(cd)
+    ekv.elitekv_multiquery_attn(dims, qd, i32(q_pos.reshape(-1)), i32(kv_len.reshape(-1)), S, stride, Wukd, Wuvd,
+                                i32(idx), ked2, cd2, out2, ws)
+    torch.cuda.synchronize()
+    o2 = host64(out2)
+    # two bf16 computations of the same quantity, each within 2e-2 of the exact result
+    scale = np.max(np.abs(o2))
+    assert np.max(np.abs(o - o2)) <= 2 * TOL["bf16"] * scale
+
+
+def test_prefill_is_repeatable_bit_for_bit():
+    a = _run("small_three_blocks_random")[15]
+    b = _run("small_three_blocks_random")[15]
+    assert np.array_equal(a, b)
+
+
+def test_other_shapes_take_the_decode_kernels():
+    """head_dim 64 is outside the flash kernel: the call is served query by query and still matches."""
+    sh = shape(64, 4, 64, 4, 128, "bf16")
+    rows, T = [90], 20
+    B, stride = 1, 95
+    rng, idx, W_ke, W_dkv, W_uk, W_uv, x, _ = _draw(sh, stride, B, 77)
+    q = rng.standard_normal((B, T, 4, 64))
+    dims = dims_of(sh)
+    ke64, c64 = orc.append(x, np.arange(stride), W_ke, W_dkv, idx, 64, sh["rope_base"])
+    ked, cd, qd, Wukd, Wuvd = dev(ke64, "bf16"), dev(c64, "bf16"), dev(q, "bf16"), dev(W_uk, "bf16"), dev(W_uv, "bf16")
+    q_pos = np.array([[90 - T + t for t in range(T)]])
+    kv_len = q_pos + 1
+    out = torch.full((B, T, 4, 64), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(ekv.elitekv_prefill_attn_workspace_bytes(dims, B, T, 90), dtype=torch.uint8, device=DEV)
+    ekv.elitekv_prefill_attn(dims, qd, i32(q_pos.reshape(-1)), i32(kv_len.reshape(-1)), 90, stride, Wukd, Wuvd, i32(idx),
+                             ked, cd, out, ws)
+    torch.cuda.synchronize()
+    ref = orc.multiquery_attn(host64(qd), q_pos, host64(ked).reshape(B, stride, 4, -1), host64(cd).reshape(B, stride, -1),
+                              kv_len, host64(Wukd), host64(Wuvd), idx, 64, sh["rope_base"])
+    assert orc.max_abs_rel(host64(out), ref) <= TOL["bf16"]
