@@ -111,9 +111,9 @@ __device__ __forceinline__ void gemm_epilogue(am_f32x16 (&acc)[2][WN], int n0, i
   for (int j = 0; j < WN; ++j) {
     const int64_t t = t0 + wn * 32 * WN + j * 32 + n32;
     if (t >= T) continue;
-    const int64_t row = slot[t];
+    const int64_t row = slot ? slot[t] : t;                  // no slot list: rows are written in place
     if (row < 0 || row >= plane_rows) continue;
-    const int32_t p = pos[t];
+    const int32_t p = pos ? pos[t] : 0;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll

@@ -8,13 +8,14 @@
 // v_j,h = c_j B^v_J,h  (Section 3.2, J-LRD), 2 d_c (2 d_h - 2r) flops per (token, head), then
 // ordinary attention (Section 2.1) at 4 d_h flops per (query, token, head).  Three steps:
 //
-//   1. pack_query_kernel   q^ = [R(pos theta_i) q_i for i in I_h (slot order) | q's non-elite dims,
-//                          ascending], scaled by log2(e)/sqrt(d_h), bf16          (Section 3.1 score equation)
-//   2. the matrix-core GEMM of the cache append (launch_append_gemm) run on the latent rows:
+//   1. the matrix-core GEMM of the cache append (launch_append_gemm) run on the latent rows:
 //                          KV[j, :] = c_j [B^k_J | B^v_J]   (no elite columns, no rotation)
-//   3. prefill_attn_kernel flash attention: S^T = K Q^T, online softmax, O^T += V^T P^T.
+//   2. prefill_attn_kernel flash attention: S^T = K Q^T, online softmax, O^T += V^T P^T, with the
+//                          query packed on the way in: q^ = [R(pos theta_i) q_i for i in I_h (slot
+//                          order) | q's non-elite dims, ascending], scaled by log2(e)/sqrt(d_h)
+//                          (Section 3.1 score equation)
 //
-// Step 3, one work-group = 4 waves x 32 queries of one (sequence, head); a 64-key tile of K and V
+// Step 2, one work-group = 4 waves x 32 or 64 queries of one (sequence, head); a 64-key tile of K and V
 // comes in by direct global->LDS loads, double-buffered.  Per wave and tile:
 //   S^T[key, query]   32x32x16 MFMA, A = key rows from LDS (16-byte reads), B = the wave's queries,
 //                     held in registers for the whole pass;
@@ -29,6 +30,7 @@
 // tiles the later query blocks re-read come from that XCD's L2.
 #include "common.hpp"
 #include "launch.hpp"
+#include <stdlib.h>
 
 namespace ekv {
 
@@ -39,15 +41,16 @@ typedef __attribute__((ext_vector_type(8))) short pf_s16x8;
 typedef __attribute__((address_space(3))) pf_s16x4 pf_lds_s16x4_t;
 
 constexpr int kPfDh = 128;                       // head dim of the compiled kernel
-constexpr int kPfQB = 128;                       // queries per block (4 waves x 32)
 constexpr int kPfTile = 64;                      // keys per tile
 constexpr int kPfRow = kPfDh * 2;                // bytes of a staged K or V row
 constexpr int kPfPlane = kPfTile * kPfRow;       // one K (or V) tile: 16 KiB
 constexpr int kPfStage = 2 * kPfPlane;           // K + V
-constexpr int kPfLds = 2 * kPfStage + 64;        // two stages + the block's reduction scratch
+constexpr int kPfLds = 2 * kPfStage + 64 + 256;  // two stages + the block's reduction scratch + the head's chunk order
 
 struct PrefillParams {
-  const bf16_t* qp;          // [B * T, n_h, d_h]  packed queries
+  const bf16_t* q;           // [B * T, n_h, d_h]  queries as the caller holds them (un-rotated)
+  const int32_t* q_pos;      // [B * T]
+  const int32_t* elite_idx;  // [n_h, r]
   const bf16_t* ke_plane;    // [plane_rows, n_h, 2r]
   const bf16_t* kv;          // [B, S, NKV]  rebuilt [non-elite key dims of every head | values of every head]
   const int32_t* kv_len;     // [B * T] rows of its sequence each query attends to
@@ -55,9 +58,11 @@ struct PrefillParams {
   int n_h, T, B;
   int nqb;                   // query blocks per sequence
   int npair;                 // work-groups per (sequence, head): pairs of query blocks
+  float scale;               // log2(e) / sqrt(d_h)
   int64_t S;                 // rows per sequence in kv
   int64_t NKV, NK;           // row width of kv; first value column
   int64_t batch_stride_rows, plane_rows, max_seq_len;
+  RopeTable rope;
 };
 
 // staged rows are 16 chunks of 16 bytes; chunk c of row `row` sits at chunk c ^ pf_swz(row): 16 rows read at
@@ -77,11 +82,20 @@ __device__ __forceinline__ uint32_t pf_pack2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-template <int TWO_R>
-__global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const PrefillParams p) {
+// log2-domain slack before a query's running maximum is raised: probabilities stay below 2^8
+constexpr float kPfSlack = 8.f;
+
+// QB = 32-query blocks per wave: a work-group handles 4 * 32 * QB queries.  With QB = 2 every K and V
+// fragment read from LDS feeds two MFMAs (half the LDS traffic per flop) at one wave per SIMD; with
+// QB = 1 two work-groups share a compute unit.
+template <int TWO_R, int QB>
+__global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void prefill_attn_kernel(const PrefillParams p) {
   constexpr int KCH = TWO_R / 8;                 // leading 16-byte chunks of a key row that come from the elite plane
+  constexpr int R = TWO_R / 2;
+  constexpr int QBLK = 128 * QB;                 // queries per work-group pass
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int* red = reinterpret_cast<int*>(smem + 2 * kPfStage);
+  int* order = red + 16;                         // order[pp]: the chunk of q that is pair pp of the packed query
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n32 = lane & 31, g = lane >> 5, i16 = lane & 15, q16 = lane >> 4;
 
@@ -94,6 +108,19 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const PrefillParam
   const int b = ph / p.n_h, h = ph % p.n_h;
   const int64_t row0 = (int64_t)b * p.batch_stride_rows;
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem);
+
+  // ---- the packed query's dim order (Section 3.1 score equation): the head's elite chunks in slot
+  // order, then the other chunks ascending -- the order of a rebuilt key row [ke | c B^k]
+  if (wave == 0) {
+    int slot = -1;
+    for (int j = 0; j < R; ++j)
+      if (p.elite_idx[h * R + j] == lane) slot = j;
+    const unsigned long long elite = __ballot(slot >= 0);
+    const int rank = __popcll(~elite & ((1ull << lane) - 1ull));   // non-elite chunks below this one
+    const int pp = slot >= 0 ? slot : R + rank;
+    order[lane] = 0;                                               // (repeated elite indices leave holes: keep them in range)
+    if (pp < kPfDh / 2) order[pp] = lane;
+  }
 
   // ---- loader: wave w fills rows 16w .. 16w+15 of the K tile and of the V tile, four rows per load;
   // lane l fills (row l/16, chunk position l%16) and fetches the logical chunk the swizzle puts there
@@ -116,32 +143,30 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const PrefillParam
   for (int half = 0; half < 2; ++half) {
     const int qblk = half == 0 ? p.nqb - 1 - pr : pr;
     if (half == 1 && qblk == p.nqb - 1 - pr) break;          // the middle block of an odd count
-    const int tq = qblk * kPfQB + wave * 32 + n32;            // this lane's query
-    const bool q_ok = tq < p.T;
-    const int64_t qrow = (int64_t)b * p.T + (q_ok ? tq : p.T - 1);
-    int64_t len64 = q_ok ? (int64_t)p.kv_len[qrow] : 0;
-    len64 = min(len64, p.max_seq_len);
-    len64 = min(len64, p.plane_rows - row0);
-    len64 = min(len64, p.S);
-    const int len = (int)max(len64, (int64_t)0);
+    int len[QB];
+    int64_t qrow[QB];
+    bool q_ok[QB];
+    int wmax = 0;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const int tq = qblk * QBLK + (wave * QB + qb) * 32 + n32;   // this lane's query of block qb
+      q_ok[qb] = tq < p.T;
+      qrow[qb] = (int64_t)b * p.T + (q_ok[qb] ? tq : p.T - 1);
+      int64_t len64 = q_ok[qb] ? (int64_t)p.kv_len[qrow[qb]] : 0;
+      len64 = min(len64, p.max_seq_len);
+      len64 = min(len64, p.plane_rows - row0);
+      len64 = min(len64, p.S);
+      len[qb] = (int)max(len64, (int64_t)0);
+      wmax = max(wmax, len[qb]);
+    }
     // the block's largest visible length bounds the key loop
-    int wmax = len;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) wmax = max(wmax, __shfl_xor(wmax, o, kWave));
     __syncthreads();                                          // the previous block is done with red[] and the tiles
     if (lane == 0) red[wave] = wmax;
-    __syncthreads();
+    __syncthreads();                                          // (also: order[] is complete)
     const int kv_hi = max(max(red[0], red[1]), max(red[2], red[3]));
     const int ntiles = (kv_hi + kPfTile - 1) / kPfTile;
-
-    // the wave's queries as the B operand: lane = query n32, dims 16*ks + 8*g ..
-    pf_bf16x8 Qb[kPfDh / 16];
-    {
-      const bf16_t* qsrc = p.qp + (qrow * p.n_h + h) * kPfDh + 8 * g;
-#pragma unroll
-      for (int ks = 0; ks < kPfDh / 16; ++ks)
-        Qb[ks] = __builtin_bit_cast(pf_bf16x8, *reinterpret_cast<const pf_s16x8*>(qsrc + 16 * ks));
-    }
 
     auto issue = [&](int tile, int buf) {
       const uint32_t kl = __builtin_amdgcn_readfirstlane(lds0 + buf * kPfStage + wave * 4096);
@@ -157,13 +182,49 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const PrefillParam
         pf_dma16(vrow, kl + kPfPlane + u * 1024);
       }
     };
+    if (ntiles > 0) issue(0, 0);                              // in flight while the queries are prepared
 
-    pf_f32x16 oacc[kPfDh / 32];
+    // the wave's queries as the B operand: lane = query n32, packed dims 16*ks + 8*g .. of block qb,
+    // gathered pair by pair from q in the packed order; elite pairs (the first R) rotated to the
+    // query's position (Section 2.2, eq. 1a); everything scaled by log2(e)/sqrt(d_h)
+    pf_bf16x8 Qb[QB][kPfDh / 16];
 #pragma unroll
-    for (int dt = 0; dt < kPfDh / 32; ++dt) oacc[dt] = (pf_f32x16)(0.f);
-    float m_run = -INFINITY, l_run = 0.f;
+    for (int qb = 0; qb < QB; ++qb) {
+      const bf16_t* qsrc = p.q + (qrow[qb] * p.n_h + h) * kPfDh;
+      const int32_t qp = p.q_pos[qrow[qb]];
+#pragma unroll
+      for (int ks = 0; ks < kPfDh / 16; ++ks) {
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int pp = 8 * ks + 4 * g + j;
+          const int ch = order[pp];
+          const uint32_t raw = *reinterpret_cast<const uint32_t*>(qsrc + 2 * ch);
+          float a = bf16_bits_to_f32(raw & 0xffffu), c = bf16_bits_to_f32(raw >> 16);
+          if (8 * ks < R) {                                   // k-steps that can hold elite pairs (compile-time)
+            if (pp < R) {
+              float sn, cs;
+              rope_sincos_poly(qp, p.rope.theta[ch], &sn, &cs);
+              const float a2 = a * cs - c * sn, c2 = a * sn + c * cs;
+              a = a2; c = c2;
+            }
+          }
+          w[j] = pf_pack2(a * p.scale, c * p.scale);
+        }
+        Qb[qb][ks] = __builtin_bit_cast(pf_bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+      }
+    }
 
-    if (ntiles > 0) issue(0, 0);
+    pf_f32x16 oacc[QB][kPfDh / 32];
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+      for (int dt = 0; dt < kPfDh / 32; ++dt) oacc[qb][dt] = (pf_f32x16)(0.f);
+      m_run[qb] = -INFINITY;
+      l_run[qb] = 0.f;
+    }
+
     for (int it = 0; it < ntiles; ++it) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's part of tile `it` has landed
       __syncthreads();                                        // ... everyone's; and tile it-1 has been read by all
@@ -172,57 +233,31 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const PrefillParam
       const char* Vt = Kt + kPfPlane;
       const int key0 = it * kPfTile;
 
-      // ---- scores: two 32-key blocks
-      pf_f32x16 sacc[2] = {(pf_f32x16)(0.f), (pf_f32x16)(0.f)};
+      // ---- scores: two 32-key blocks per query block.  All key fragments of the tile are requested
+      // before the first MFMA (the compiler would otherwise read each one right before its use and
+      // expose the LDS latency sixteen times); sched_barrier keeps the requests where they are.
+      pf_bf16x8 kf[kPfDh / 16][2];
 #pragma unroll
       for (int ks = 0; ks < kPfDh / 16; ++ks) {
         const int off = k_row_off + (((2 * ks + g) ^ k_swz) << 4);
-        const pf_bf16x8 a0 = *reinterpret_cast<const pf_bf16x8*>(Kt + off);
-        const pf_bf16x8 a1 = *reinterpret_cast<const pf_bf16x8*>(Kt + off + 32 * kPfRow);
-        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, Qb[ks], sacc[0], 0, 0, 0);
-        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, Qb[ks], sacc[1], 0, 0, 0);
+        kf[ks][0] = *reinterpret_cast<const pf_bf16x8*>(Kt + off);
+        kf[ks][1] = *reinterpret_cast<const pf_bf16x8*>(Kt + off + 32 * kPfRow);
       }
-      // register v of block kb is key key0 + kb*32 + 8*(v/4) + 4*g + v%4 for this lane's query
-      if (__any(key0 + kPfTile > len)) {
+      __builtin_amdgcn_sched_barrier(0);
+      pf_f32x16 sacc[QB][2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+      for (int qb = 0; qb < QB; ++qb) { sacc[qb][0] = (pf_f32x16)(0.f); sacc[qb][1] = (pf_f32x16)(0.f); }
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = key0 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-            sacc[kb][v] = key < len ? sacc[kb][v] : -INFINITY;
-          }
-      }
-      // ---- online softmax (log2 domain: the packed query carries log2(e)/sqrt(d_h))
-      float tmax = -INFINITY;
+      for (int ks = 0; ks < kPfDh / 16; ++ks)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[kb][v]);
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-      const float m_new = fmaxf(m_run, tmax);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;  // nothing visible yet: every exponential below is 0
-      const float alpha = exp2f(m_run - m_use);
-      m_run = m_new;
-      float psum = 0.f;
-      pf_bf16x8 Pb[2][2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float pv = exp2f(sacc[kb][8 * s2 + j] - m_use);
-            psum += pv;
-            Pb[kb][s2][j] = (__bf16)pv;
-          }
-      l_run = l_run * alpha + psum;
-      if (__any(alpha != 1.f)) {
-#pragma unroll
-        for (int dt = 0; dt < kPfDh / 32; ++dt) oacc[dt] *= alpha;
-      }
-      // ---- values: k-slot (g, j) of k-step (kb, s2) is key kb*32 + 16*s2 + 8*(j/4) + 4*g + j%4
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int qb = 0; qb < QB; ++qb) {
+          sacc[qb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][0], Qb[qb][ks], sacc[qb][0], 0, 0, 0);
+          sacc[qb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][1], Qb[qb][ks], sacc[qb][1], 0, 0, 0);
+        }
+      // ---- value fragments of the first 32 keys, requested ahead of the softmax arithmetic.
+      // k-slot (g, j) of k-step (kb, s2) is key kb*32 + 16*s2 + 8*(j/4) + 4*g + j%4
+      pf_bf16x8 vf[2][2][kPfDh / 32];
+      auto read_v = [&](int kb) {
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
           const char* vlo = Vt + (kb * 32 + 16 * s2 + v_r) * kPfRow + v_byte;
@@ -232,69 +267,90 @@ __global__ __launch_bounds__(256, 2) void prefill_attn_kernel(const PrefillParam
             const pf_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((pf_lds_s16x4_t*)(vlo + ((ch ^ v_lo_swz) << 4)));
             const pf_s16x4 hi =
                 __builtin_amdgcn_ds_read_tr16_b64_v4i16((pf_lds_s16x4_t*)(vlo + 8 * kPfRow + ((ch ^ v_hi_swz) << 4)));
-            const pf_s16x8 a16 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(pf_bf16x8, a16), Pb[kb][s2], oacc[dt], 0, 0, 0);
+            vf[kb][s2][dt] = __builtin_bit_cast(pf_bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
           }
         }
+      };
+      read_v(0);
+      __builtin_amdgcn_sched_barrier(0);
+      pf_bf16x8 Pb[QB][2][2];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        // register v of block kb is key key0 + kb*32 + 8*(v/4) + 4*g + v%4 for this lane's query
+        if (__any(key0 + kPfTile > len[qb])) {
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int key = key0 + kb * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+              sacc[qb][kb][v] = key < len[qb] ? sacc[qb][kb][v] : -INFINITY;
+            }
+        }
+        // ---- online softmax (log2 domain: the packed query carries log2(e)/sqrt(d_h))
+        float t0 = fmaxf(sacc[qb][0][0], sacc[qb][1][0]);
+#pragma unroll
+        for (int v = 1; v < 16; ++v) t0 = fmaxf(t0, fmaxf(sacc[qb][0][v], sacc[qb][1][v]));
+        const float tmax = fmaxf(t0, __shfl_xor(t0, 32, kWave));
+        // the reference maximum is raised only when a score exceeds it by more than the slack
+        const float m_new = (tmax > m_run[qb] + kPfSlack || m_run[qb] == -INFINITY) ? tmax : m_run[qb];
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;  // nothing visible yet: every exponential below is 0
+        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_use);
+        m_run[qb] = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              const float pv = __builtin_amdgcn_exp2f(sacc[qb][kb][8 * s2 + j] - m_use);
+              psum += pv;
+              Pb[qb][kb][s2][j] = (__bf16)pv;
+            }
+        l_run[qb] = l_run[qb] * alpha + psum;
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+          for (int dt = 0; dt < kPfDh / 32; ++dt) oacc[qb][dt] *= alpha;
+        }
+      }
+      // ---- values: the fragments of the second 32 keys are requested before the first MFMAs
+      read_v(1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int dt = 0; dt < kPfDh / 32; ++dt)
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+              oacc[qb][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][s2][dt], Pb[qb][kb][s2], oacc[qb][dt], 0, 0, 0);
     }
 
     // ---- normalise and store: register 4*j + i of tile dt is dim 32*dt + 8*j + 4*g + i of the lane's query
-    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;       // a query that sees nothing gets a zero row
-    if (q_ok) {
-      bf16_t* orow = p.out + (qrow * p.n_h + h) * kPfDh + 4 * g;
 #pragma unroll
-      for (int dt = 0; dt < kPfDh / 32; ++dt)
+    for (int qb = 0; qb < QB; ++qb) {
+      const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, kWave);
+      const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;     // a query that sees nothing gets a zero row
+      if (q_ok[qb]) {
+        bf16_t* orow = p.out + (qrow[qb] * p.n_h + h) * kPfDh + 4 * g;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          uint2 pk;
-          pk.x = pf_pack2(oacc[dt][4 * j] * inv, oacc[dt][4 * j + 1] * inv);
-          pk.y = pf_pack2(oacc[dt][4 * j + 2] * inv, oacc[dt][4 * j + 3] * inv);
-          *reinterpret_cast<uint2*>(orow + 32 * dt + 8 * j) = pk;
-        }
+        for (int dt = 0; dt < kPfDh / 32; ++dt)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            uint2 pk;
+            pk.x = pf_pack2(oacc[qb][dt][4 * j] * inv, oacc[qb][dt][4 * j + 1] * inv);
+            pk.y = pf_pack2(oacc[qb][dt][4 * j + 2] * inv, oacc[qb][dt][4 * j + 3] * inv);
+            *reinterpret_cast<uint2*>(orow + 32 * dt + 8 * j) = pk;
+          }
+      }
     }
   }
 }
 
-// One wave per (query row, head): lane l owns chunk l of the head (dims 2l, 2l+1).
-__global__ __launch_bounds__(256) void pack_query_kernel(const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos,
-                                                         const int32_t* __restrict__ elite_idx, bf16_t* __restrict__ qp,
-                                                         int64_t rows, int n_h, int d_h, int r, RopeTable rope, float scale) {
-  const int lane = threadIdx.x & 63;
-  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (item >= rows * n_h) return;                            // uniform over the wave
-  const int64_t row = item / n_h;
-  const int h = (int)(item % n_h);
-  const bool live = lane < d_h / 2;
-  int slot = -1;
-  for (int j = 0; j < r; ++j)
-    if (elite_idx[h * r + j] == lane) slot = j;
-  const unsigned long long elite = __ballot(slot >= 0);
-  const int rank = __popcll(~elite & ((1ull << lane) - 1ull));   // non-elite chunks below this one
-  if (!live) return;
-  const uint32_t w = *reinterpret_cast<const uint32_t*>(q + item * d_h + 2 * lane);
-  float a = bf16_bits_to_f32(w & 0xffffu), c = bf16_bits_to_f32(w >> 16);
-  int dst;
-  if (slot >= 0) {
-    float sn, cs;
-    rope_sincos(q_pos[row], rope.theta[lane], &sn, &cs);
-    const float a2 = a * cs - c * sn, c2 = a * sn + c * cs;
-    a = a2; c = c2;
-    dst = 2 * slot;
-  } else {
-    dst = 2 * r + 2 * rank;
-  }
-  if (dst + 1 < d_h) *reinterpret_cast<uint32_t*>(qp + item * d_h + dst) = pf_pack2(a * scale, c * scale);
-}
-
-// rows of the rebuilt K/V buffer are written in place: slot[t] = t; the GEMM's epilogue also reads a
-// position per row, which nothing uses without elite columns
-__global__ void prefill_rows_kernel(int64_t* slot, int32_t* pos, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) { slot[i] = i; pos[i] = 0; }
-}
-
 // ---------------------------------------------------------------------------------------------
+static int pf_qb_override = getenv("EKV_PF_QB") ? atoi(getenv("EKV_PF_QB")) : 0;   // TEMP tuning knob
+
 static elitekv_dims rebuild_dims(const elitekv_dims& d) {
   elitekv_dims g = d;
   g.d_model = d.d_c;                                         // contraction over the latent
@@ -313,11 +369,22 @@ bool prefill_flash_supported(const elitekv_dims& d, int64_t T, int64_t max_seq_l
 
 static size_t pf_align(size_t v) { return (v + 255) / 256 * 256; }
 
-// workspace: [slot int64 S][pos int32 S][packed queries][rebuilt K/V of all sequences]
+// workspace: the rebuilt K/V rows of all sequences
 size_t prefill_flash_workspace(const elitekv_dims& d, int64_t B, int64_t T, int64_t max_seq_len) {
-  const size_t S = (size_t)max_seq_len;
-  return pf_align(S * 8) + pf_align(S * 4) + pf_align((size_t)B * T * d.n_heads * d.head_dim * 2) +
-         pf_align((size_t)B * S * (size_t)rebuild_dims(d).d_c * 2);
+  (void)T;
+  return pf_align((size_t)B * (size_t)max_seq_len * (size_t)rebuild_dims(d).d_c * 2);
+}
+
+template <int TWO_R, int QB>
+static hipError_t launch_pf(PrefillParams& p, int64_t B, int64_t T, hipStream_t stream) {
+  p.nqb = (int)((T + 128 * QB - 1) / (128 * QB));
+  p.npair = (p.nqb + 1) / 2;
+  const int64_t pairs = (B * p.n_h + 7) / 8 * 8;             // (sequence, head) pairs, padded to whole rounds of the XCDs
+  static LdsLimit lim;
+  const hipError_t e = raise_lds_limit(lim, reinterpret_cast<const void*>(&prefill_attn_kernel<TWO_R, QB>), kPfLds);
+  if (e != hipSuccess) return e;
+  prefill_attn_kernel<TWO_R, QB><<<(unsigned)(pairs * p.npair), 256, kPfLds, stream>>>(p);
+  return hipGetLastError();
 }
 
 hipError_t launch_prefill_flash(const DecodeArgs& a, int64_t B, int64_t T, hipStream_t stream) {
@@ -325,55 +392,33 @@ hipError_t launch_prefill_flash(const DecodeArgs& a, int64_t B, int64_t T, hipSt
   const int64_t S = a.max_seq_len;
   const elitekv_dims gd = rebuild_dims(d);
   const int64_t NK = (int64_t)d.n_heads * (d.head_dim - 2 * d.r), NKV = gd.d_c;
-  char* ws = a.ws;
-  int64_t* slot = reinterpret_cast<int64_t*>(ws);   ws += pf_align((size_t)S * 8);
-  int32_t* pos = reinterpret_cast<int32_t*>(ws);    ws += pf_align((size_t)S * 4);
-  bf16_t* qp = reinterpret_cast<bf16_t*>(ws);       ws += pf_align((size_t)B * T * d.n_heads * d.head_dim * 2);
-  bf16_t* kv = reinterpret_cast<bf16_t*>(ws);
-
-  prefill_rows_kernel<<<(unsigned)((S + 255) / 256), 256, 0, stream>>>(slot, pos, S);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const int64_t items = B * T * d.n_heads;
-  pack_query_kernel<<<(unsigned)((items + 3) / 4), 256, 0, stream>>>(
-      (const bf16_t*)a.q, a.q_pos, a.elite_idx, qp, B * T, d.n_heads, d.head_dim, d.r,
-      rope_table(d.rope_base, d.head_dim), kLog2e / sqrtf((float)d.head_dim));
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  bf16_t* kv = reinterpret_cast<bf16_t*>(a.ws);
 
   // K/V of every sequence's first S rows (rows past the end of the planes are left out)
+  hipError_t e = hipSuccess;
   for (int64_t b = 0; b < B; ++b) {
     const int64_t row0 = b * a.batch_stride_rows;
     const int64_t rows = S < a.plane_rows - row0 ? S : a.plane_rows - row0;
     if (rows <= 0) continue;
     AppendArgs g;
     g.dims = gd; g.d_ck = (int32_t)NK; g.W_dkv = a.W_uk; g.W_dkv2 = a.W_uv; g.W_ke = nullptr;
-    g.x = (const bf16_t*)a.c_plane + row0 * d.d_c; g.pos = pos; g.slot = slot; g.T = rows;
+    g.x = (const bf16_t*)a.c_plane + row0 * d.d_c; g.pos = nullptr; g.slot = nullptr; g.T = rows;   // rows written in place
     g.elite_idx = nullptr; g.ke_plane = nullptr; g.c_plane = kv + b * S * NKV; g.plane_rows = S; g.ws = nullptr;
     e = launch_append_gemm(g, stream);
     if (e != hipSuccess) return e;
   }
 
   PrefillParams p;
-  p.qp = qp; p.ke_plane = (const bf16_t*)a.ke_plane; p.kv = kv; p.kv_len = a.seq_len; p.out = (bf16_t*)a.out;
+  p.q = (const bf16_t*)a.q; p.q_pos = a.q_pos; p.elite_idx = a.elite_idx;
+  p.ke_plane = (const bf16_t*)a.ke_plane; p.kv = kv; p.kv_len = a.seq_len; p.out = (bf16_t*)a.out;
   p.n_h = d.n_heads; p.T = (int)T; p.B = (int)B;
-  p.nqb = (int)((T + kPfQB - 1) / kPfQB);
-  p.npair = (p.nqb + 1) / 2;
+  p.scale = kLog2e / sqrtf((float)d.head_dim);
   p.S = S; p.NKV = NKV; p.NK = NK;
   p.batch_stride_rows = a.batch_stride_rows; p.plane_rows = a.plane_rows; p.max_seq_len = a.max_seq_len;
-  const int64_t pairs = (B * d.n_heads + 7) / 8 * 8;         // (sequence, head) pairs, padded to whole rounds of the XCDs
-  const int64_t groups = pairs * p.npair;
-  static LdsLimit lim8, lim16;
-  if (2 * d.r == 16) {
-    e = raise_lds_limit(lim16, reinterpret_cast<const void*>(&prefill_attn_kernel<16>), kPfLds);
-    if (e != hipSuccess) return e;
-    prefill_attn_kernel<16><<<(unsigned)groups, 256, kPfLds, stream>>>(p);
-  } else {
-    e = raise_lds_limit(lim8, reinterpret_cast<const void*>(&prefill_attn_kernel<8>), kPfLds);
-    if (e != hipSuccess) return e;
-    prefill_attn_kernel<8><<<(unsigned)groups, 256, kPfLds, stream>>>(p);
-  }
-  return hipGetLastError();
+  p.rope = rope_table(d.rope_base, d.head_dim);
+  const int qb = pf_qb_override > 0 ? pf_qb_override : 1;
+  if (2 * d.r == 16) return qb == 2 ? launch_pf<16, 2>(p, B, T, stream) : launch_pf<16, 1>(p, B, T, stream);
+  return qb == 2 ? launch_pf<8, 2>(p, B, T, stream) : launch_pf<8, 1>(p, B, T, stream);
 }
 
 }  // namespace ekv
