@@ -7,7 +7,7 @@ The default workload is the 7B shape at 25 % cache, batch 1, 32K context.  Input
 in HBM before the timed region.  The timed steps cycle over several distinct copies of the
 cache planes (>= 1 GiB in total) so that the 256 MB Infinity Cache cannot serve the reads.
 
-Prints one JSON line; see the design doc for the meaning of each field.
+Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -254,6 +254,9 @@ def main():
         if not d_ck and B < 8:
             result["block_step"] = block_step(ekv, ev, cfg, dims, planes, x_d, pos_d, slot_d, seq_d, W_ke_d, W_dkv_d, W_uk_d,
                                               W_uv_d, idx_d, dev, dt, stream, cache_bytes, args)
+        if not d_ck:
+            result["prefill_attn"] = prefill_attn(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
+                                                  T=args.prefill_tokens)
         result["ropelite_search"] = ropelite_search(ekv, ev, cfg, dev, stream)
         result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream,
                                                   T=args.prefill_tokens)
@@ -434,6 +437,43 @@ def ropelite_search(ekv, ev, cfg, dev, stream, T=512, iters=3):
     ms = ev.elapsed_ms(e0, e1) / iters
     evals = T * (T + 1) / 2 * n_h * r * (d_h // 2)      # (causal pair, chunk) evaluations over all rounds
     return {"tokens": T, "rounds": r, "ms_per_layer": round(ms, 4), "G_pair_chunk_evals_per_s": round(evals / ms / 1e6, 1)}
+
+
+def prefill_attn(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream, T=2048, iters=20):
+    """Causal attention of a T-token prompt of one sequence over its own T cache rows (the step after
+    the prefill-sized append): keys and values rebuilt once per row on the matrix cores, then flash
+    attention.  Flops counted: the rebuild GEMM + 4 d_h per visible (query, key, head) pair."""
+    import torch
+    n_h, d_h, r, d_c = cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c
+    ke_p, c_p = planes[0]
+    T = int(min(T, c_p.shape[0]))
+    g = torch.Generator(device=dev)
+    g.manual_seed(15862)
+    q = torch.randn(1, T, n_h, d_h, device=dev, dtype=torch.float32, generator=g).to(dt)
+    pos = torch.arange(T, device=dev, dtype=torch.int32)
+    kv = pos + 1
+    out = torch.empty(1, T, n_h, d_h, dtype=dt, device=dev)
+    ws = torch.empty(ekv.elitekv_prefill_attn_workspace_bytes(dims, 1, T, T), dtype=torch.uint8, device=dev)
+
+    def call():
+        ekv.elitekv_prefill_attn(dims, q, pos, kv, T, T, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out, ws, stream=stream)
+    for _ in range(3):
+        call()
+    e0, e1 = ev.create(), ev.create()
+    ev.record(e0, stream)
+    for _ in range(iters):
+        call()
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms = ev.elapsed_ms(e0, e1) / iters
+    fl_rebuild = 2.0 * T * d_c * n_h * (2 * d_h - 2 * r)
+    fl_attn = 4.0 * d_h * n_h * (T * (T + 1) / 2)
+    tf = (fl_rebuild + fl_attn) / (ms * 1e-3) / 1e12
+    return {"tokens": T, "ms": round(ms, 5), "TFLOPs": round(tf, 1), "bound": "mfma", "peak_TFLOPs": 2500.0,
+            "frac": round(tf / 2500.0, 4), "rebuild_GFLOP": round(fl_rebuild / 1e9, 1),
+            "attention_GFLOP": round(fl_attn / 1e9, 1),
+            "absorbed_form_GFLOP": round(n_h * (4.0 * d_c + 4 * r) * (T * (T + 1) / 2) / 1e9, 1),
+            "query_tokens_per_s": round(T / (ms * 1e-3), 1)}
 
 
 def append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream, T=2048, iters=20):
