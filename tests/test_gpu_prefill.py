@@ -25,6 +25,8 @@ CASES = {
     "7b_full_prefill": (shape(64, 32, 128, 8, 1536, "bf16"), [200], 200, "causal", 10),
     "7b_12pct_chunk_over_context": (shape(64, 32, 128, 4, 768, "bf16"), [130, 257], 70, "causal", 6),
     "13b_full_prefill": (shape(64, 40, 128, 8, 1920, "bf16"), [97], 97, "causal", 6),
+    # more work-groups than compute units, three sequences, five query blocks (an unpaired middle one)
+    "many_work_groups": (shape(64, 32, 128, 8, 256, "bf16"), [700, 650, 720], 640, "causal", 5),
 }
 
 
@@ -79,7 +81,8 @@ def test_prefill_matches_oracle_on_sampled_queries(name):
     assert orc.max_abs_rel(o[:, pick], ref) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("name", ["small_two_seqs_causal", "small_three_blocks_random", "7b_full_prefill"])
+@pytest.mark.parametrize("name", ["small_two_seqs_causal", "small_three_blocks_random", "7b_full_prefill",
+                                  "many_work_groups"])
 def test_prefill_agrees_with_the_absorbed_form_on_every_query(name):
     sh, rows, T, B, stride, rng, idx, qd, q_pos, kv_len, ked, cd, Wukd, Wuvd, dims, o, n_sample, S = _run(name)
     out2 = torch.full_like(torch.empty(B, T, sh["n_heads"], sh["head_dim"], dtype=torch.bfloat16, device=DEV), float("nan"))
