@@ -175,3 +175,46 @@ def test_slrd_prefill_append_with_wide_tiles():
     assert orc.max_abs_rel(c_g[:, :d_ck], ck_ref) <= TOL["bf16"]
     assert orc.max_abs_rel(c_g[:, d_ck:], cv_ref) <= TOL["bf16"]
     assert orc.max_abs_rel(ke_g, ke_ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("name,T", [("7b_25_b1_s32768", 2048), ("7b_12_b64_s2048", 2048), ("13b_25_b16_s8192", 2048),
+                                    ("7b_25_b1_s32768", 4500)])
+def test_full_size_prefill_attention(name, T):
+    """elitekv_prefill_attn in the configuration bench.py times (one sequence, the T-token prompt attends
+    causally to its own T cache rows; 4500 tokens: two work-groups per compute unit, a ragged last block):
+    the planes come from the library's append of seeded hidden states; sampled (query, head) outputs are
+    computed one by one by the float64 oracle from exactly the planes the GPU reads."""
+    cfg = synth.CONFIGS[name]
+    n_h, d_h, r, d_c, d = cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c, cfg.d_model
+    dims = dims_of(cfg)
+    rng = synth.rng_for(cfg.index, stream=13)
+    idx = synth.draw_elite_idx(rng, n_h, d_h, r)
+    W_ke, W_dkv, W_uk, W_uv = synth.draw_weights(rng, d, n_h, d_h, r, d_c)
+    Wked, Wdkvd, Wukd, Wuvd = (dev(a, "bf16") for a in (W_ke, W_dkv, W_uk, W_uv))
+    idxd = i32(idx)
+    xd = torch.from_numpy(rng.standard_normal((T, d), dtype=np.float32)).to(torch.bfloat16).to(DEV)
+    qd = torch.from_numpy(rng.standard_normal((1, T, n_h, d_h), dtype=np.float32)).to(torch.bfloat16).to(DEV)
+    ke = torch.zeros(T, n_h, 2 * r, dtype=torch.bfloat16, device=DEV)
+    c = torch.zeros(T, d_c, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(max(ekv.elitekv_append_workspace_bytes(dims, T), 16), dtype=torch.uint8, device=DEV)
+    pos = torch.arange(T, dtype=torch.int32, device=DEV)
+    ekv.elitekv_append(dims, xd, pos, torch.arange(T, dtype=torch.int64, device=DEV), Wked, Wdkvd, idxd, ke, c, ws=ws)
+    out = torch.full((1, T, n_h, d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
+    pws = torch.full((ekv.elitekv_prefill_attn_workspace_bytes(dims, 1, T, T),), 0xFF, dtype=torch.uint8, device=DEV)
+    ekv.elitekv_prefill_attn(dims, qd, pos, pos + 1, T, T, Wukd, Wuvd, idxd, ke, c, out, pws)
+    torch.cuda.synchronize()
+    o = host64(out)
+    assert np.all(np.isfinite(o))
+    heads_s = [0, n_h // 2 + 1, n_h - 1]
+    queries = sorted(set([0, 1, 63, 64, 127, 128, 129, T // 2 + 7, T - 129, T - 2, T - 1]))
+    ke64, c64, q64 = host64(ke), host64(c), host64(qd)
+    Wuk64, Wuv64 = host64(Wukd), host64(Wuvd)
+    refs, gots = [], []
+    for t in queries:
+        ref = orc.decode_attn(q64[0, t:t + 1], [t], [ke64], [c64], [t + 1], Wuk64, Wuv64, idx, d_h, cfg.rope_base,
+                              heads=heads_s)
+        for h in heads_s:
+            refs.append(ref[0, h])
+            gots.append(o[0, t, h])
+    err = orc.max_abs_rel(np.stack(gots), np.stack(refs))
+    assert err <= TOL["bf16"], "max-abs-rel %g" % err

@@ -61,3 +61,40 @@ def test_append_and_decode_replay_from_a_graph(B, fused):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, want), "replay %d differs from the eager step" % rep
+
+
+def test_prefill_attention_replays_from_a_graph():
+    """The prefill call is launches only (one GEMM per sequence + the flash kernel): captured and replayed."""
+    sh, rows, T = shape(64, 8, 128, 8, 256, "bf16"), [300, 260], 200
+    B, stride, S = 2, 310, 300
+    rng, idx, _, _, W_uk, W_uv, _, _ = _draw(sh, 1, 1, 321)
+    dims = dims_of(sh)
+    ke64, c64 = synth.draw_cache_planes(rng, B * stride, 8, 8, 256)
+    ke, c = dev(ke64, "bf16"), dev(c64, "bf16")
+    qd = dev(rng.standard_normal((B, T, 8, 128)), "bf16")
+    Wukd, Wuvd, idxd = dev(W_uk, "bf16"), dev(W_uv, "bf16"), i32(idx)
+    q_pos = i32(np.concatenate([np.arange(n - T, n) for n in rows]))
+    kv_len = q_pos + 1
+    out = torch.zeros(B, T, 8, 128, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(ekv.elitekv_prefill_attn_workspace_bytes(dims, B, T, S), dtype=torch.uint8, device=DEV)
+
+    def call(stream):
+        ekv.elitekv_prefill_attn(dims, qd, q_pos, kv_len, S, stride, Wukd, Wuvd, idxd, ke, c, out, ws, stream=stream)
+
+    call(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = out.clone()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        call(side.cuda_stream)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            call(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), "replay %d differs from the eager call" % rep
