@@ -123,3 +123,41 @@ def test_other_shapes_take_the_decode_kernels():
     ref = orc.multiquery_attn(host64(qd), q_pos, host64(ked).reshape(B, stride, 4, -1), host64(cd).reshape(B, stride, -1),
                               kv_len, host64(Wukd), host64(Wuvd), idx, 64, sh["rope_base"])
     assert orc.max_abs_rel(host64(out), ref) <= TOL["bf16"]
+
+
+def test_prefill_with_scores_that_keep_rising():
+    """The running maximum of a query has to be raised many times along the keys (and is lowered never):
+    the latent rows are multiples g(j) of one direction, so a head's score is g(j) times a per-(query, head)
+    constant, rising for some and falling for others, far beyond the kernel's slack of 8 (log2 domain)."""
+    import elitekv_synth as synth
+    sh = shape(64, 8, 128, 8, 256, "bf16")
+    S, T, n_h, d_c = 500, 200, 8, 256
+    rng, idx, _, _, W_uk, W_uv, _, _ = _draw(sh, 1, 1, 78)
+    ke64, c64 = synth.draw_cache_planes(rng, S, n_h, sh["r"], d_c)
+    v = rng.standard_normal(d_c)
+    g = np.linspace(0.0, 15.0, S) + 0.3 * np.sin(np.arange(S))
+    c64 = 0.05 * c64 + g[:, None] * v[None, :]
+    q = rng.standard_normal((1, T, n_h, 128))
+    dims = dims_of(sh)
+    ked, cd, qd, Wukd, Wuvd = dev(ke64, "bf16"), dev(c64, "bf16"), dev(q, "bf16"), dev(W_uk, "bf16"), dev(W_uv, "bf16")
+    q_pos = np.arange(S - T, S)[None]
+    kv_len = q_pos + 1
+    q64, Wuk64, c_r = host64(qd)[0], host64(Wukd), host64(cd)
+    rise = []
+    for h in range(n_h):
+        qt = q64[:, h][:, orc.nonelite_dims(idx[h], 128)] @ Wuk64[:, h, :].T           # [T, d_c]
+        s = (qt @ c_r.T) * np.log2(np.e) / np.sqrt(128.0)
+        rise.append(s[:, S - T] - s[:, 0])
+    rise = np.concatenate(rise)
+    assert rise.max() > 24.0 and rise.min() < -24.0
+    out = torch.full((1, T, n_h, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(ekv.elitekv_prefill_attn_workspace_bytes(dims, 1, T, S), dtype=torch.uint8, device=DEV)
+    ekv.elitekv_prefill_attn(dims, qd, i32(q_pos.reshape(-1)), i32(kv_len.reshape(-1)), S, S, Wukd, Wuvd, i32(idx),
+                             ked, cd, out, ws)
+    torch.cuda.synchronize()
+    o = host64(out)
+    assert np.all(np.isfinite(o))
+    pick = list(range(0, T, 9)) + [T - 1]
+    ref = orc.multiquery_attn(host64(qd)[:, pick], q_pos[:, pick], host64(ked).reshape(1, S, n_h, -1),
+                              c_r.reshape(1, S, -1), kv_len[:, pick], Wuk64, host64(Wuvd), idx, 128, sh["rope_base"])
+    assert orc.max_abs_rel(o[:, pick], ref) <= TOL["bf16"]
