@@ -356,8 +356,14 @@ static elitekv_dims rebuild_dims(const elitekv_dims& d) {
   return g;
 }
 
+// Below this many queries per sequence the absorbed form (every query through the decode kernels) is the
+// cheaper order: rebuilding a row costs 2 d_c (2 d_h - 2r) flops per head, about what 60-70 absorbed queries
+// cost on it at their measured rates.
+constexpr int kPfMinQueries = 48;
+
 bool prefill_flash_supported(const elitekv_dims& d, int64_t T, int64_t max_seq_len) {
   if (d.dtype != ELITEKV_BF16 || d.head_dim != kPfDh) return false;
+  if (T < kPfMinQueries) return false;
   if (2 * d.r != 8 && 2 * d.r != 16) return false;
   if (d.d_c % 32 || T < 1 || max_seq_len <= 64 || max_seq_len > (1 << 30)) return false;
   const elitekv_dims g = rebuild_dims(d);

@@ -210,6 +210,8 @@ def test_prefill_argument_errors():
     assert ekv.elitekv_prefill_attn_workspace_bytes(d, 2, 3, 128) == ekv.elitekv_multiquery_workspace_bytes(d, 2, 3, 128)
     assert ekv.elitekv_prefill_attn_workspace_bytes(big, 2, 300, 64) == ekv.elitekv_multiquery_workspace_bytes(big, 2, 300, 64)
     assert pf(dims=d, B=300, T=300) == ekv.EUNSUPPORTED
+    # few queries per sequence: the absorbed form is the cheaper order, the call is the several-queries call
+    assert ekv.elitekv_prefill_attn_workspace_bytes(big, 2, 8, 512) == ekv.elitekv_multiquery_workspace_bytes(big, 2, 8, 512)
 
 
 def test_decode_step_argument_errors():
