@@ -167,10 +167,12 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void prefill_attn_kernel(cons
     const int kv_hi = max(max(red[0], red[1]), max(red[2], red[3]));
     const int ntiles = (kv_hi + kPfTile - 1) / kPfTile;
 
-    auto issue = [&](int tile, int buf) {
+    // the loads of a tile in four parts (u = 0..3: four rows of K and of V per wave each); a tile index past the
+    // last one stands for the last one (such copies are never read)
+    auto issue_part = [&](int tile, int buf, int u) {
       const uint32_t kl = __builtin_amdgcn_readfirstlane(lds0 + buf * kPfStage + wave * 4096);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      tile = min(tile, ntiles - 1);
+      {
         const int row = wave * 16 + u * 4 + ld_r;
         const int lc = (lane & 15) ^ pf_swz(row);
         const int64_t t = min(tile * kPfTile + row, kv_hi - 1);   // rows past the end repeat the last visible one
@@ -180,6 +182,10 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void prefill_attn_kernel(cons
         const char* vrow = kv_seq + t * p.NKV * 2 + (p.NK + (int64_t)h * kPfDh + lc * 8) * 2;
         pf_dma16(vrow, kl + kPfPlane + u * 1024);
       }
+    };
+    auto issue = [&](int tile, int buf) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) issue_part(tile, buf, u);
     };
     if (ntiles > 0) issue(0, 0);                              // in flight while the queries are prepared
 
@@ -227,7 +233,6 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void prefill_attn_kernel(cons
     for (int it = 0; it < ntiles; ++it) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's part of tile `it` has landed
       __syncthreads();                                        // ... everyone's; and tile it-1 has been read by all
-      if (it + 1 < ntiles) issue(it + 1, (it + 1) & 1);
       const char* Kt = smem + (it & 1) * kPfStage;
       const char* Vt = Kt + kPfPlane;
       const int key0 = it * kPfTile;
@@ -246,13 +251,21 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void prefill_attn_kernel(cons
       pf_f32x16 sacc[QB][2];
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) { sacc[qb][0] = (pf_f32x16)(0.f); sacc[qb][1] = (pf_f32x16)(0.f); }
+      // The next tile's loads are requested BEHIND the first score MFMAs: vector work (here the address
+      // arithmetic) overlaps MFMAs of the same wave that were issued before it, not those of the other wave.
 #pragma unroll
-      for (int ks = 0; ks < kPfDh / 16; ++ks)
+      for (int ks = 0; ks < kPfDh / 16; ++ks) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
           sacc[qb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][0], Qb[qb][ks], sacc[qb][0], 0, 0, 0);
           sacc[qb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][1], Qb[qb][ks], sacc[qb][1], 0, 0, 0);
         }
+        if (ks < 4) {
+          asm volatile("" : "+v"(sacc[0][1]));                // (keeps the MFMAs above the requests below)
+          issue_part(it + 1, (it + 1) & 1, ks);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
       // ---- value fragments of the first 32 keys, requested ahead of the softmax arithmetic.
       // k-slot (g, j) of k-step (kb, s2) is key kb*32 + 16*s2 + 8*(j/4) + 4*g + j%4
       pf_bf16x8 vf[2][2][kPfDh / 32];
@@ -325,6 +338,7 @@ __global__ __launch_bounds__(256, QB == 1 ? 2 : 1) void prefill_attn_kernel(cons
             for (int qb = 0; qb < QB; ++qb)
               oacc[qb][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kb][s2][dt], Pb[qb][kb][s2], oacc[qb][dt], 0, 0, 0);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the spare copy of the last tile has landed before the stages are reused
 
     // ---- normalise and store: register 4*j + i of tile dt is dim 32*dt + 8*j + 4*g + i of the lane's query
 #pragma unroll
