@@ -287,6 +287,20 @@ def multiquery_attn(q, q_pos, ke, c, kv_len, W_uk, W_uv, elite_idx, head_dim: in
     return out
 
 
+def slrd_multiquery_attn(q, q_pos, ke, c_k, c_v, kv_len, B_k, B_v, elite_idx, head_dim: int, rope_base: float):
+    """Several queries per sequence of an S-LRD model (Section 3.2): query (b, t) is one instance of
+    slrd_decode_attn over the first kv_len[b][t] rows of sequence b.  Shapes as multiquery_attn, with
+    the two latents c_k[b], c_v[b] and their up-projections B_k, B_v in place of c, W_uk, W_uv."""
+    q = np.asarray(q, dtype=F64)
+    B, T = q.shape[:2]
+    out = np.zeros_like(q)
+    for b in range(B):
+        for t in range(T):
+            out[b, t] = slrd_decode_attn(q[b, t][None], [int(q_pos[b][t])], [ke[b]], [c_k[b]], [c_v[b]],
+                                         [int(kv_len[b][t])], B_k, B_v, elite_idx, head_dim, rope_base)[0]
+    return out
+
+
 # ----------------------------------------------------------------------------------------------
 # RoPElite search (Section 3.1, Algorithm 1): the greedy choice of each head's elite chunks.
 # Round after round, every chunk that is not yet elite is tried as the one additional rotated chunk;

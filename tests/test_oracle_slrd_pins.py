@@ -159,6 +159,46 @@ def test_s4_closed_forms():
         assert np.max(np.abs(zero[h] - (x @ A_v).mean(axis=0) @ B_v[:, h, :])) < TOL
 
 
+def test_s6_several_queries_equal_masked_causal_attention():
+    """Exact separate factors, the last T tokens as queries: one masked [T, S] score matrix per head
+    from un-rotated full keys with relative rotations on the elite chunks (Section 2.2 eq. 1b,
+    Section 2.1 for the softmax), values from the full value projection."""
+    d, n_h, d_h, r, S, T, base = 20, 2, 8, 2, 9, 4, 1000.0
+    rng, Wk, Wv, idx, x, _, _, _ = _full_model(81, d, n_h, d_h, r, S)
+    W_ke, A_k, A_v, B_k, B_v = _exact_slrd_weights(rng, Wk, Wv, idx)
+    ke, ck, cv = orc.slrd_append(x, np.arange(S), W_ke, A_k, A_v, idx, d_h, base)
+    q = rng.standard_normal((1, T, n_h, d_h))
+    q_pos = np.arange(S - T, S)[None]
+    got = orc.slrd_multiquery_attn(q, q_pos, [ke], [ck], [cv], q_pos + 1, B_k, B_v, idx, d_h, base)[0]
+    k_raw = np.einsum("sd,dhe->she", x, Wk)
+    v = np.einsum("sd,dhe->she", x, Wv)
+    th = _theta_plain(d_h, base)
+    for h in range(n_h):
+        elite = set(int(i) for i in idx[h])
+        s = np.full((T, S), -np.inf)
+        for t in range(T):
+            for j in range(int(q_pos[0, t]) + 1):          # the mask: no later token is visible
+                acc = 0.0
+                for i in range(d_h // 2):
+                    qa, qb = q[0, t, h, 2 * i], q[0, t, h, 2 * i + 1]
+                    ka, kb = k_raw[j, h, 2 * i], k_raw[j, h, 2 * i + 1]
+                    if i in elite:
+                        # (R(m th) q) . (R(n th) k) = q^T R((n - m) th) k, R(a) = [[cos a, -sin a], [sin a, cos a]]
+                        a = (j - int(q_pos[0, t])) * th[i]
+                        acc += (qa * ka + qb * kb) * math.cos(a) + (qb * ka - qa * kb) * math.sin(a)
+                    else:
+                        acc += qa * ka + qb * kb
+                s[t, j] = acc / math.sqrt(d_h)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        assert np.max(np.abs(got[:, h, :] - p @ v[:, h, :])) < TOL
+    # a query that sees nothing returns zeros; visibility is per query, not per sequence
+    z = orc.slrd_multiquery_attn(q, q_pos, [ke], [ck], [cv], np.array([[0, 1, 0, S]]), B_k, B_v, idx, d_h, base)[0]
+    assert np.all(z[0] == 0.0) and np.all(z[2] == 0.0)
+    assert np.max(np.abs(z[1] - np.einsum("d,dhe->he", x[0], Wv))) < TOL
+    assert np.max(np.abs(z[3] - got[3])) == 0.0
+
+
 def test_s5_size_formulas():
     """Section 3.2: cache 2 r n_h + d_ck + d_cv per token; with d = d_h n_h the storage cost
     simplifies to (2 d_ck + 2 d_cv + 2 r n_h) d - 2 d_ck r n_h."""
