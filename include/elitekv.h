@@ -253,6 +253,22 @@ int elitekv_slrd_decode_attn(const elitekv_dims* dims, int32_t d_ck, const void*
                              int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
                              void* hip_stream);
 
+/*
+ * Several queries per sequence of an S-LRD model: elitekv_multiquery_attn (Section 2.1: query (b, t)
+ * sees the first kv_len rows of sequence b) with the keys and values of elitekv_slrd_decode_attn
+ * (Section 3.2).  q [B, T, n_h, d_h], q_pos and kv_len [B * T], out [B, T, n_h, d_h]; B_k, B_v and
+ * the planes as in elitekv_slrd_decode_attn; workspace from the _workspace_bytes function.
+ * EINVAL if T < 1 or d_ck is out of range, EUNSUPPORTED if B * T > 65535.
+ */
+size_t elitekv_slrd_multiquery_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t T,
+                                               int64_t max_seq_len, int32_t n_splits);
+int elitekv_slrd_multiquery_attn(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                                 const int32_t* kv_len, int64_t B, int64_t T, int64_t max_seq_len,
+                                 int64_t batch_stride_rows, const void* B_k, const void* B_v,
+                                 const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                                 int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                                 void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * One decode step in one call: the B new tokens (one per sequence) are appended to the cache and
  * each sequence's query attends to its cached tokens and to its new token.  With

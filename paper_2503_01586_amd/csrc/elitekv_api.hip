@@ -594,6 +594,27 @@ int elitekv_slrd_decode_attn(const elitekv_dims* dims, int32_t d_ck, const void*
                      ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, 7);
 }
 
+size_t elitekv_slrd_multiquery_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t T,
+                                               int64_t max_seq_len, int32_t n_splits) {
+  DecodePlan p;
+  if (d_ck <= 0 || B < 0 || T < 1 || B * T > 65535 || plan_decode(dims, d_ck, B * T, max_seq_len, n_splits, &p))
+    return 0;
+  return p.total;
+}
+
+int elitekv_slrd_multiquery_attn(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                                 const int32_t* kv_len, int64_t B, int64_t T, int64_t max_seq_len,
+                                 int64_t batch_stride_rows, const void* B_k, const void* B_v,
+                                 const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                                 int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
+                                 void* hip_stream) {
+  if (!dims) return ELITEKV_ENULL;
+  if (d_ck <= 0 || B < 0 || T < 1) return ELITEKV_EINVAL;
+  if (B * T > 65535) return ELITEKV_EUNSUPPORTED;
+  return decode_impl(dims, d_ck, q, q_pos, kv_len, B * T, max_seq_len, batch_stride_rows, B_k, B_v, elite_idx,
+                     ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, 7, (int32_t)T);
+}
+
 int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
                         const int32_t* seq_len, int64_t B, int64_t max_seq_len,
                         int64_t batch_stride_rows, const void* W_uk, const void* W_uv,

@@ -190,6 +190,25 @@ def test_multiquery_argument_errors():
     assert mq(wsb=need - 1) == ekv.EWORKSPACE
 
 
+def test_slrd_multiquery_argument_errors():
+    d = _dims()
+    dc = d.d_c
+    mq = lambda d_ck, **kw: lib.elitekv_slrd_multiquery_attn(
+        C.byref(d), d_ck, kw.get("q", FAKE), FAKE, FAKE, kw.get("B", 2), kw.get("T", 3), 128, 128, FAKE, FAKE, FAKE,
+        FAKE, FAKE, 256, FAKE, FAKE, kw.get("wsb", 1 << 30), 0, None)
+    assert mq(0) == ekv.EINVAL and mq(dc) == ekv.EINVAL                                  # 0 < d_ck < d_c
+    assert mq(dc // 2, T=0) == ekv.EINVAL and mq(dc // 2, B=-1) == ekv.EINVAL
+    assert mq(dc // 2, B=0) == ekv.OK
+    assert mq(dc // 2, B=300, T=300) == ekv.EUNSUPPORTED
+    assert mq(dc // 2, q=None) == ekv.ENULL
+    need = ekv.elitekv_slrd_multiquery_workspace_bytes(d, dc // 2, 2, 3, 128)
+    assert need == ekv.elitekv_slrd_decode_workspace_bytes(d, dc // 2, 6, 128)           # B*T query rows
+    assert need > 0 and mq(dc // 2, wsb=need - 1) == ekv.EWORKSPACE
+    assert ekv.elitekv_slrd_multiquery_workspace_bytes(d, 0, 2, 3, 128) == 0
+    assert lib.elitekv_slrd_multiquery_attn(None, 4, FAKE, FAKE, FAKE, 1, 1, 128, 128, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                            256, FAKE, FAKE, 1 << 30, 0, None) == ekv.ENULL
+
+
 def test_prefill_argument_errors():
     big = ekv.make_dims(4096, 32, 128, 8, 1536, "bf16")
     pf = lambda **kw: lib.elitekv_prefill_attn(C.byref(kw.get("dims", big)), kw.get("q", FAKE), FAKE, FAKE, kw.get("B", 2),

@@ -129,6 +129,68 @@ def test_slrd_decode_matches_oracle_on_same_planes(name):
         assert orc.max_abs_rel(o, outs[0]) <= TOL[dt]
 
 
+MULTIQUERY_CASES = {
+    # name: (shape, cached rows per sequence, T, splits)
+    "fp32_tiny": (shape(64, 3, 24, 5, 20, 37, "fp32"), [40, 7, 130], 5, [0, 2]),
+    "bf16_7b_576_960_chunk_of_4": (shape(64, 32, 128, 8, 576, 960, "bf16"), [300, 65], 4, [0, 3]),
+    "bf16_7b_768_768_chunk_of_16": (shape(64, 32, 128, 8, 768, 768, "bf16"), [200], 16, [0]),
+    "bf16_12pct_384_384_chunk_of_9": (shape(64, 32, 128, 4, 384, 384, "bf16"), [130], 9, [0]),
+    "bf16_13b_960_960_chunk_of_3": (shape(64, 40, 128, 8, 960, 960, "bf16"), [97, 160], 3, [0, 2]),
+}
+
+
+@pytest.mark.parametrize("name", list(MULTIQUERY_CASES))
+def test_slrd_multiquery_matches_oracle(name):
+    """The queries are the last T tokens of each sequence; a sequence shorter than the chunk leaves
+    its first queries with nothing to see (zeros)."""
+    sh, rows, T, splits = MULTIQUERY_CASES[name]
+    dt, d_ck = sh["dtype"], sh["d_ck"]
+    n_h, d_h = sh["n_heads"], sh["head_dim"]
+    B, stride = len(rows), max(rows) + 2
+    rng, idx, W_ke, A_k, A_v, B_k, B_v, x, _ = _draw(sh, B * stride, B, 700 + len(name))
+    q = rng.standard_normal((B, T, n_h, d_h))
+    dims = dims_of(sh)
+    pos = np.tile(np.arange(stride), B)
+    ke64, ck64, cv64 = orc.slrd_append(x, pos, W_ke, A_k, A_v, idx, d_h, sh["rope_base"])
+    ked, cd = dev(ke64, dt), dev(np.concatenate([ck64, cv64], axis=1), dt)
+    qd, Bkd, Bvd = dev(q, dt), dev(B_k, dt), dev(B_v, dt)
+    q_pos = np.array([[max(n - T + t, 0) for t in range(T)] for n in rows])
+    kv_len = np.array([[max(n - T + t + 1, 0) for t in range(T)] for n in rows])
+    c_h = host64(cd).reshape(B, stride, -1)
+    ref = orc.slrd_multiquery_attn(host64(qd), q_pos, host64(ked).reshape(B, stride, n_h, -1), c_h[:, :, :d_ck],
+                                   c_h[:, :, d_ck:], kv_len, host64(Bkd), host64(Bvd), idx, d_h, sh["rope_base"])
+    for ns in splits:
+        out = torch.full((B, T, n_h, d_h), float("nan"), dtype=ekv.torch_dtype(dims), device=DEV)
+        nws = ekv.elitekv_slrd_multiquery_workspace_bytes(dims, d_ck, B, T, max(rows), ns)
+        assert nws > 0
+        ws = torch.full((nws,), 0xFF, dtype=torch.uint8, device=DEV)
+        ekv.elitekv_slrd_multiquery_attn(dims, d_ck, qd, i32(q_pos.reshape(-1)), i32(kv_len.reshape(-1)), max(rows),
+                                         stride, Bkd, Bvd, i32(idx), ked, cd, out, ws, n_splits=ns)
+        torch.cuda.synchronize()
+        o = host64(out)
+        assert np.all(np.isfinite(o))
+        assert orc.max_abs_rel(o, ref) <= TOL[dt], "n_splits=%d" % ns
+        assert np.all(o[kv_len == 0] == 0.0)
+
+
+def test_slrd_one_query_per_sequence_is_the_decode_call():
+    sh = shape(64, 32, 128, 8, 576, 960, "bf16")
+    rows, B, stride = [120, 77], 2, 125
+    rng, idx, _, _, _, B_k, B_v, _, q = _draw(sh, 1, B, 19)
+    dims, d_ck = dims_of(sh), sh["d_ck"]
+    ke64, c64 = synth.draw_cache_planes(rng, B * stride, 32, 8, 1536)
+    ked, cd, qd, Bkd, Bvd = (dev(a, "bf16") for a in (ke64, c64, q, B_k, B_v))
+    q_pos, seq = i32([r - 1 for r in rows]), i32(rows)
+    a = gpu_slrd_decode(dims, d_ck, qd, q_pos, seq, max(rows), stride, Bkd, Bvd, i32(idx), ked, cd)
+    out = torch.empty(B, 1, 32, 128, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(ekv.elitekv_slrd_multiquery_workspace_bytes(dims, d_ck, B, 1, max(rows)), dtype=torch.uint8,
+                     device=DEV)
+    ekv.elitekv_slrd_multiquery_attn(dims, d_ck, qd.reshape(B, 1, 32, 128), q_pos, seq, max(rows), stride, Bkd, Bvd,
+                                     i32(idx), ked, cd, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out.reshape(B, 32, 128), a)
+
+
 def test_slrd_end_to_end_and_repeatable():
     sh, S = shape(256, 32, 128, 8, 576, 960, "bf16"), 333
     _, idx, W_ke, A_k, A_v, B_k, B_v, x, q = _draw(sh, S, 1, 51)
