@@ -269,6 +269,23 @@ int elitekv_slrd_multiquery_attn(const elitekv_dims* dims, int32_t d_ck, const v
                                  int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
                                  void* hip_stream);
 
+/*
+ * Many queries per sequence of an S-LRD model: elitekv_prefill_attn with the keys
+ * [stored rotated elite dims | c^k B^k_S,h] and values c^v B^v_S,h of Section 3.2 rebuilt once per
+ * cached row (keys from the first d_ck columns of a latent row, values from the others), then ordinary
+ * attention (Section 2.1).  Arguments as elitekv_slrd_multiquery_attn, result the same.
+ * Runs this path under the conditions of elitekv_prefill_attn and, in addition, d_ck a multiple of 32
+ * and n_h (d_h - 2 r) a multiple of 128; every other call is handed to elitekv_slrd_multiquery_attn
+ * (and its limits apply).  Workspace: the _workspace_bytes function.
+ */
+size_t elitekv_slrd_prefill_attn_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t T,
+                                                 int64_t max_seq_len);
+int elitekv_slrd_prefill_attn(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                              const int32_t* kv_len, int64_t B, int64_t T, int64_t max_seq_len,
+                              int64_t batch_stride_rows, const void* B_k, const void* B_v, const int32_t* elite_idx,
+                              const void* ke_plane, const void* c_plane, int64_t plane_rows, void* out, void* ws,
+                              size_t ws_bytes, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * One decode step in one call: the B new tokens (one per sequence) are appended to the cache and
  * each sequence's query attends to its cached tokens and to its new token.  With

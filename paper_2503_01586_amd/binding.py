@@ -65,6 +65,8 @@ def _load():
         "elitekv_slrd_multiquery_workspace_bytes": (SZ, [DP, I32, I64, I64, I64, I32]),
         "elitekv_slrd_multiquery_attn": (C.c_int, [DP, I32, P, P, P, I64, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ,
                                                    I32, P]),
+        "elitekv_slrd_prefill_attn_workspace_bytes": (SZ, [DP, I32, I64, I64, I64]),
+        "elitekv_slrd_prefill_attn": (C.c_int, [DP, I32, P, P, P, I64, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, P]),
         "elitekv_decode_step_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_decode_step": (C.c_int, [DP, P, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, I64, P, P, SZ, I32,
                                           P]),
@@ -283,6 +285,23 @@ def elitekv_slrd_multiquery_attn(dims, d_ck, q, q_pos, kv_len, max_seq_len, batc
                                            _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
                                            _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
     _check(st, "elitekv_slrd_multiquery_attn")
+
+
+def elitekv_slrd_prefill_attn_workspace_bytes(dims, d_ck, B, T, max_seq_len) -> int:
+    return _lib.elitekv_slrd_prefill_attn_workspace_bytes(C.byref(dims), int(d_ck), int(B), int(T), int(max_seq_len))
+
+
+def elitekv_slrd_prefill_attn(dims, d_ck, q, q_pos, kv_len, max_seq_len, batch_stride_rows, B_k, B_v, elite_idx,
+                              ke_plane, c_plane, out, ws, stream=None, plane_rows=None):
+    """q [B, T, n_h, d_h]; q_pos, kv_len [B, T] (int32)."""
+    B, T = q.shape[0], q.shape[1]
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_slrd_prefill_attn(C.byref(dims), int(d_ck), _ptr(q), _ptr(q_pos), _ptr(kv_len), int(B), int(T),
+                                        int(max_seq_len), int(batch_stride_rows), _ptr(B_k), _ptr(B_v),
+                                        _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows), _ptr(out),
+                                        _ptr(ws), ws_bytes, _stream(stream))
+    _check(st, "elitekv_slrd_prefill_attn")
 
 
 def elitekv_decode_step_workspace_bytes(dims, B, max_seq_len, n_splits=0) -> int:

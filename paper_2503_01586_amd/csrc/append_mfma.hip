@@ -305,7 +305,7 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
     const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
     const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const bf16_t* __restrict__ W_dkv2, int d_ck,
     const int32_t* __restrict__ elite_idx, bf16_t* __restrict__ ke_plane, bf16_t* __restrict__ c_plane,
-    int64_t plane_rows, int d, int n_h, int d_h, int r, int d_c, RopeTable rope) {
+    int64_t plane_rows, int d, int n_h, int d_h, int r, int d_c, RopeTable rope, int64_t x_ld, int x_off2, int d2) {
   using L = GemmDmaLayout<WN, NS, WNW, CM>;
   extern __shared__ __attribute__((aligned(16))) char gsm[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -321,7 +321,11 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
   const int n0 = (seq % col_blocks) * L::COLS;
   const int64_t t0 = tblock * L::BN;
   if (t0 >= T) return;
-  const int nstages = d / kGdStage;
+  // a column block inside W_dkv2 may contract a different column slice of the input rows (d2 > 0; the host
+  // makes sure that no block straddles the two matrices then)
+  const bool second = d2 > 0 && n0 - NE >= d_ck;
+  const bf16_t* xs = second ? x + x_off2 : x;
+  const int nstages = (second ? d2 : d) / kGdStage;
 
   // ---- loader.  Wave w issues loads w*LPW .. w*LPW+LPW-1 of a stage; load index < WB is weight block
   // (kb = idx / CM, nb = idx % CM), the others are token blocks of 16 rows.
@@ -340,7 +344,7 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
     } else {
       const int tb = idx - L::WB, row = lane >> 2, pc = (lane & 3) ^ gd_swz4(row);
       const int64_t t = min(t0 + tb * 16 + row, T - 1);        // rows past the end repeat the last token
-      gsrc[u] = reinterpret_cast<const char*>(x + t * d + pc * 8);
+      gsrc[u] = reinterpret_cast<const char*>(xs + t * x_ld + pc * 8);
       gstep[u] = (int64_t)kGdStage * 2;
     }
   }
@@ -480,7 +484,8 @@ static hipError_t launch_gemm_dma(const AppendArgs& a, hipStream_t stream) {
   append_gemm_dma_kernel<WN, NS, WNW, CM><<<grid, 64 * CM * WNW, L::LDS_BYTES, stream>>>(
       (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
       (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
-      d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, rope_table(d.rope_base, d.head_dim));
+      d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, rope_table(d.rope_base, d.head_dim),
+      a.x_ld ? a.x_ld : (int64_t)d.d_model, a.x_off2, a.d2);
   return hipGetLastError();
 }
 
@@ -488,13 +493,20 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
   const int64_t col_blocks = (2 * d.r * d.n_heads + d.d_c) / kGmCols;
   // the widest token tile that still gives every compute unit work
+  const int split = 2 * d.r * d.n_heads + a.d_ck;              // first column of W_dkv2
+  if (a.d2 > 0 || a.x_ld > 0) {
+    // column slices of wider rows: only the direct-load kernels take them, with whole stages in both slices
+    // and no 128-column block across the two matrices
+    if (d.d_model % kGdStage || a.d2 % kGdStage || a.x_off2 % 8 || a.x_ld % 8 || (a.d2 > 0 && split % kGmCols))
+      return hipErrorInvalidValue;
+  }
   if (d.d_model % kGdStage == 0) {
     const int N = 2 * d.r * d.n_heads + d.d_c;
     // 256 x 256 tiles, one work-group per compute unit: a third fewer operand bytes per flop, 13 % faster
     // than 256 x 128 whenever its work-groups fill the 256 compute units evenly -- one full round, or
     // enough rounds that the ragged last one costs less than that (measured: slower at 260-320
     // work-groups and at 128, faster at 224-256 and from 360 on)
-    const int64_t wide = N % 256 == 0 ? (N / 256) * ((a.T + 255) / 256) : 0;
+    const int64_t wide = N % 256 == 0 && (a.d2 == 0 || split % 256 == 0) ? (N / 256) * ((a.T + 255) / 256) : 0;
     if (wide >= 352 || (wide >= 224 && wide <= 256)) return launch_gemm_dma<4, 4, 2, 4>(a, stream);
     if (col_blocks * ((a.T + 255) / 256) >= 512) return launch_gemm_dma<2, 6, 4, 2>(a, stream);
     if (col_blocks * ((a.T + 127) / 128) >= 256) return launch_gemm_dma<2, 4, 2, 2>(a, stream);

@@ -520,22 +520,29 @@ int elitekv_multiquery_attn(const elitekv_dims* dims, const void* q, const int32
 
 /* ---- many queries per sequence (prefill): K and V rebuilt once per cached row, then flash attention ---- */
 
-size_t elitekv_prefill_attn_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t T, int64_t max_seq_len) {
+static size_t prefill_ws_impl(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t T, int64_t max_seq_len) {
   if (check_dims(dims) || B < 0 || T < 1 || max_seq_len < 0) return 0;
-  if (prefill_flash_supported(*dims, T, max_seq_len)) return prefill_flash_workspace(*dims, B, T, max_seq_len);
-  return elitekv_multiquery_workspace_bytes(dims, B, T, max_seq_len, 0);
+  if (prefill_flash_supported(*dims, d_ck, T, max_seq_len)) return prefill_flash_workspace(*dims, B, T, max_seq_len);
+  return d_ck ? elitekv_slrd_multiquery_workspace_bytes(dims, d_ck, B, T, max_seq_len, 0)
+              : elitekv_multiquery_workspace_bytes(dims, B, T, max_seq_len, 0);
 }
 
-int elitekv_prefill_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos, const int32_t* kv_len,
-                         int64_t B, int64_t T, int64_t max_seq_len, int64_t batch_stride_rows, const void* W_uk,
-                         const void* W_uv, const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
-                         int64_t plane_rows, void* out, void* ws, size_t ws_bytes, void* hip_stream) {
+static int prefill_impl(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                        const int32_t* kv_len, int64_t B, int64_t T, int64_t max_seq_len, int64_t batch_stride_rows,
+                        const void* W_uk, const void* W_uv, const int32_t* elite_idx, const void* ke_plane,
+                        const void* c_plane, int64_t plane_rows, void* out, void* ws, size_t ws_bytes,
+                        void* hip_stream) {
   int st = check_dims(dims);
   if (st) return st;
   if (B < 0 || T < 1 || max_seq_len < 0 || batch_stride_rows < 0 || plane_rows < 0) return ELITEKV_EINVAL;
-  if (!prefill_flash_supported(*dims, T, max_seq_len))       // other shapes: every query as a decode query
+  if (!prefill_flash_supported(*dims, d_ck, T, max_seq_len)) {     // other shapes: every query as a decode query
+    if (d_ck)
+      return elitekv_slrd_multiquery_attn(dims, d_ck, q, q_pos, kv_len, B, T, max_seq_len, batch_stride_rows, W_uk,
+                                          W_uv, elite_idx, ke_plane, c_plane, plane_rows, out, ws, ws_bytes, 0,
+                                          hip_stream);
     return elitekv_multiquery_attn(dims, q, q_pos, kv_len, B, T, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
                                    ke_plane, c_plane, plane_rows, out, ws, ws_bytes, 0, hip_stream);
+  }
   if (B == 0) return ELITEKV_OK;
   if (B * T > (1LL << 24) || B * dims->n_heads > (1 << 20)) return ELITEKV_EUNSUPPORTED;
   if (!q || !q_pos || !kv_len || !W_uk || !W_uv || !elite_idx || !ke_plane || !c_plane || !out || !ws) return ELITEKV_ENULL;
@@ -543,9 +550,38 @@ int elitekv_prefill_attn(const elitekv_dims* dims, const void* q, const int32_t*
       !aligned16(out) || !aligned16(ws))
     return ELITEKV_EALIGN;
   if (ws_bytes < prefill_flash_workspace(*dims, B, T, max_seq_len)) return ELITEKV_EWORKSPACE;
-  const DecodeArgs a = decode_args(dims, 0, q, q_pos, kv_len, B * T, max_seq_len, batch_stride_rows, W_uk, W_uv,
+  const DecodeArgs a = decode_args(dims, d_ck, q, q_pos, kv_len, B * T, max_seq_len, batch_stride_rows, W_uk, W_uv,
                                    elite_idx, ke_plane, c_plane, plane_rows, out, ws, 7, (int32_t)T);
   return launch_prefill_flash(a, B, T, (hipStream_t)hip_stream) == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+size_t elitekv_prefill_attn_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t T, int64_t max_seq_len) {
+  return prefill_ws_impl(dims, 0, B, T, max_seq_len);
+}
+
+int elitekv_prefill_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos, const int32_t* kv_len,
+                         int64_t B, int64_t T, int64_t max_seq_len, int64_t batch_stride_rows, const void* W_uk,
+                         const void* W_uv, const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                         int64_t plane_rows, void* out, void* ws, size_t ws_bytes, void* hip_stream) {
+  return prefill_impl(dims, 0, q, q_pos, kv_len, B, T, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx, ke_plane,
+                      c_plane, plane_rows, out, ws, ws_bytes, hip_stream);
+}
+
+size_t elitekv_slrd_prefill_attn_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t T,
+                                                 int64_t max_seq_len) {
+  if (!dims || d_ck <= 0 || d_ck >= dims->d_c) return 0;
+  return prefill_ws_impl(dims, d_ck, B, T, max_seq_len);
+}
+
+int elitekv_slrd_prefill_attn(const elitekv_dims* dims, int32_t d_ck, const void* q, const int32_t* q_pos,
+                              const int32_t* kv_len, int64_t B, int64_t T, int64_t max_seq_len,
+                              int64_t batch_stride_rows, const void* B_k, const void* B_v, const int32_t* elite_idx,
+                              const void* ke_plane, const void* c_plane, int64_t plane_rows, void* out, void* ws,
+                              size_t ws_bytes, void* hip_stream) {
+  if (!dims) return ELITEKV_ENULL;
+  if (d_ck <= 0 || d_ck >= dims->d_c) return ELITEKV_EINVAL;
+  return prefill_impl(dims, d_ck, q, q_pos, kv_len, B, T, max_seq_len, batch_stride_rows, B_k, B_v, elite_idx,
+                      ke_plane, c_plane, plane_rows, out, ws, ws_bytes, hip_stream);
 }
 
 /* ---- separated low-rank decomposition (two latents per token, stored side by side) ---- */

@@ -101,6 +101,10 @@ struct AppendArgs {
   void* c_plane;
   int64_t plane_rows;
   char* ws;
+  // Matrix-core GEMM only (launch_append_gemm), for inputs that are column slices of wider rows:
+  int64_t x_ld = 0;     // elements between two rows of x; 0: dims.d_model
+  int32_t x_off2 = 0;   // the W_dkv2 columns contract x[:, x_off2 : x_off2 + d2] with W_dkv2 [d2, d_c - d_ck] ...
+  int32_t d2 = 0;       // ... 0: the same dims.d_model columns of x as the others
 };
 
 struct MhaArgs {
@@ -154,7 +158,7 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
 hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 // many queries per sequence: keys and values rebuilt from the latent once per cached row (with the append's
 // matrix-core GEMM), then flash attention; a.B = B * T query rows, a.seq_len = the visible rows of each
-bool prefill_flash_supported(const elitekv_dims& d, int64_t T, int64_t max_seq_len);
+bool prefill_flash_supported(const elitekv_dims& d, int d_ck, int64_t T, int64_t max_seq_len);
 size_t prefill_flash_workspace(const elitekv_dims& d, int64_t B, int64_t T, int64_t max_seq_len);
 hipError_t launch_prefill_flash(const DecodeArgs& a, int64_t B, int64_t T, hipStream_t stream);
 hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream);

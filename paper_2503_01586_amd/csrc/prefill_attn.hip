@@ -375,8 +375,12 @@ static elitekv_dims rebuild_dims(const elitekv_dims& d) {
 // cost on it at their measured rates.
 constexpr int kPfMinQueries = 48;
 
-bool prefill_flash_supported(const elitekv_dims& d, int64_t T, int64_t max_seq_len) {
+bool prefill_flash_supported(const elitekv_dims& d, int d_ck, int64_t T, int64_t max_seq_len) {
   if (d.dtype != ELITEKV_BF16 || d.head_dim != kPfDh) return false;
+  // separated latents: keys are rebuilt from the first d_ck columns of a latent row and values from the rest,
+  // each slice in whole contraction stages, and no 128-column block of the rebuilt row lies across the two
+  if (d_ck < 0 || d_ck >= d.d_c || d_ck % 32) return false;
+  if (d_ck > 0 && (d.n_heads * (d.head_dim - 2 * d.r)) % 128) return false;
   if (T < kPfMinQueries) return false;
   if (2 * d.r != 8 && 2 * d.r != 16) return false;
   if (d.d_c % 32 || T < 1 || max_seq_len <= 64 || max_seq_len > (1 << 30)) return false;
@@ -419,6 +423,9 @@ hipError_t launch_prefill_flash(const DecodeArgs& a, int64_t B, int64_t T, hipSt
     if (rows <= 0) continue;
     AppendArgs g;
     g.dims = gd; g.d_ck = (int32_t)NK; g.W_dkv = a.W_uk; g.W_dkv2 = a.W_uv; g.W_ke = nullptr;
+    if (a.d_ck > 0) {                                          // [c^k | c^v] rows: keys from c^k, values from c^v
+      g.dims.d_model = a.d_ck; g.x_ld = d.d_c; g.x_off2 = a.d_ck; g.d2 = d.d_c - a.d_ck;
+    }
     g.x = (const bf16_t*)a.c_plane + row0 * d.d_c; g.pos = nullptr; g.slot = nullptr; g.T = rows;   // rows written in place
     g.elite_idx = nullptr; g.ke_plane = nullptr; g.c_plane = kv + b * S * NKV; g.plane_rows = S; g.ws = nullptr;
     e = launch_append_gemm(g, stream);

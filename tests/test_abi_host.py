@@ -273,3 +273,24 @@ def test_block_step_argument_errors():
     assert blk(B=8) == ekv.EUNSUPPORTED
     assert blk(dims=_dims()) == ekv.EUNSUPPORTED                      # fp32
     assert ekv.elitekv_block_step_workspace_bytes(big, 8, 128) == 0
+
+
+def test_slrd_prefill_argument_errors():
+    big = ekv.make_dims(4096, 32, 128, 8, 1536, "bf16")
+    pf = lambda d_ck, **kw: lib.elitekv_slrd_prefill_attn(
+        C.byref(kw.get("dims", big)), d_ck, kw.get("q", FAKE), FAKE, FAKE, kw.get("B", 2), kw.get("T", 300),
+        kw.get("S", 512), 512, FAKE, kw.get("B_v", FAKE), FAKE, FAKE, FAKE, 1024, FAKE, FAKE, kw.get("wsb", 1 << 40), None)
+    assert pf(0) == ekv.EINVAL and pf(1536) == ekv.EINVAL
+    assert pf(576, T=0) == ekv.EINVAL and pf(576, B=-1) == ekv.EINVAL
+    assert pf(576, B=0) == ekv.OK
+    assert pf(576, q=None) == ekv.ENULL
+    assert pf(576, B_v=FAKE + 2) == ekv.EALIGN
+    need = ekv.elitekv_slrd_prefill_attn_workspace_bytes(big, 576, 2, 300, 512)
+    assert need == ekv.elitekv_prefill_attn_workspace_bytes(big, 2, 300, 512)             # the same rebuilt rows
+    assert pf(576, wsb=need - 1) == ekv.EWORKSPACE
+    assert ekv.elitekv_slrd_prefill_attn_workspace_bytes(big, 0, 2, 300, 512) == 0
+    # a d_ck that is not a multiple of 32, few queries, or 12.5 % at 40 heads (n_h (d_h - 2r) not a multiple of 128):
+    # the call is the several-queries call
+    for dims_, d_ck, T in [(big, 584, 300), (big, 576, 8), (ekv.make_dims(5120, 40, 128, 4, 960, "bf16"), 480, 300)]:
+        assert ekv.elitekv_slrd_prefill_attn_workspace_bytes(dims_, d_ck, 1, T, 512) == \
+            ekv.elitekv_slrd_multiquery_workspace_bytes(dims_, d_ck, 1, T, 512)

@@ -218,3 +218,48 @@ def test_full_size_prefill_attention(name, T):
             gots.append(o[0, t, h])
     err = orc.max_abs_rel(np.stack(gots), np.stack(refs))
     assert err <= TOL["bf16"], "max-abs-rel %g" % err
+
+
+def test_full_size_slrd_prefill_attention():
+    """elitekv_slrd_prefill_attn at the 7B shape with the paper's 25 % S-LRD split sizes (d_ck 576, d_cv 960),
+    one 2048-token prompt attending causally to its own rows (the 256 x 256 tile of the rebuild GEMM with a
+    different contraction slice per column block): planes from the library's own S-LRD append; sampled
+    (query, head) outputs one by one from the float64 oracle on exactly the planes the GPU reads."""
+    cfg = synth.CONFIGS["7b_25_b1_s32768"]
+    n_h, d_h, r, d_c, d, T = cfg.n_heads, cfg.head_dim, cfg.r, cfg.d_c, cfg.d_model, 2048
+    d_ck = 576
+    dims = dims_of(cfg)
+    rng = synth.rng_for(cfg.index, stream=17)
+    idx = synth.draw_elite_idx(rng, n_h, d_h, r)
+    W_ke, A_k, B_k, _ = synth.draw_weights(rng, d, n_h, d_h, r, d_ck)
+    _, A_v, _, B_v = synth.draw_weights(rng, d, n_h, d_h, r, d_c - d_ck)
+    Wked, Akd, Avd, Bkd, Bvd = (dev(a, "bf16") for a in (W_ke, A_k, A_v, B_k, B_v))
+    idxd = i32(idx)
+    xd = torch.from_numpy(rng.standard_normal((T, d), dtype=np.float32)).to(torch.bfloat16).to(DEV)
+    qd = torch.from_numpy(rng.standard_normal((1, T, n_h, d_h), dtype=np.float32)).to(torch.bfloat16).to(DEV)
+    ke = torch.zeros(T, n_h, 2 * r, dtype=torch.bfloat16, device=DEV)
+    c = torch.zeros(T, d_c, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(max(ekv.elitekv_slrd_append_workspace_bytes(dims, d_ck, T), 16), dtype=torch.uint8, device=DEV)
+    pos = torch.arange(T, dtype=torch.int32, device=DEV)
+    ekv.elitekv_slrd_append(dims, d_ck, xd, pos, torch.arange(T, dtype=torch.int64, device=DEV), Wked, Akd, Avd, idxd,
+                            ke, c, ws=ws)
+    out = torch.full((1, T, n_h, d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
+    pws = torch.full((ekv.elitekv_slrd_prefill_attn_workspace_bytes(dims, d_ck, 1, T, T),), 0xFF, dtype=torch.uint8,
+                     device=DEV)
+    ekv.elitekv_slrd_prefill_attn(dims, d_ck, qd, pos, pos + 1, T, T, Bkd, Bvd, idxd, ke, c, out, pws)
+    torch.cuda.synchronize()
+    o = host64(out)
+    assert np.all(np.isfinite(o))
+    heads_s = [0, n_h // 2 + 1, n_h - 1]
+    queries = sorted(set([0, 1, 63, 64, 127, 128, 129, T // 2 + 7, T - 129, T - 2, T - 1]))
+    ke64, c64, q64 = host64(ke), host64(c), host64(qd)
+    Bk64, Bv64 = host64(Bkd), host64(Bvd)
+    refs, gots = [], []
+    for t in queries:
+        ref = orc.slrd_decode_attn(q64[0, t:t + 1], [t], [ke64], [c64[:, :d_ck]], [c64[:, d_ck:]], [t + 1], Bk64, Bv64,
+                                   idx, d_h, cfg.rope_base, heads=heads_s)
+        for h in heads_s:
+            refs.append(ref[0, h])
+            gots.append(o[0, t, h])
+    err = orc.max_abs_rel(np.stack(gots), np.stack(refs))
+    assert err <= TOL["bf16"], "max-abs-rel %g" % err

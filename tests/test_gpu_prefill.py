@@ -161,3 +161,73 @@ def test_prefill_with_scores_that_keep_rising():
     ref = orc.multiquery_attn(host64(qd)[:, pick], q_pos[:, pick], host64(ked).reshape(1, S, n_h, -1),
                               c_r.reshape(1, S, -1), kv_len[:, pick], Wuk64, host64(Wuvd), idx, 128, sh["rope_base"])
     assert orc.max_abs_rel(o[:, pick], ref) <= TOL["bf16"]
+
+
+# ----------------------------------------------------------------------------------------------
+# Separated latents (Section 3.2, S-LRD): keys rebuilt from c^k, values from c^v
+# ----------------------------------------------------------------------------------------------
+from test_gpu_slrd import _draw as _draw_slrd, shape as slrd_shape   # noqa: E402
+
+SLRD_CASES = {
+    # name: (shape, cached rows per sequence, T, kind of visibility, sampled queries per sequence)
+    "7b_576_960_two_seqs_causal": (slrd_shape(64, 32, 128, 8, 576, 960, "bf16"), [300, 191], 150, "causal", 8),
+    "7b_768_768_random": (slrd_shape(64, 32, 128, 8, 768, 768, "bf16"), [333], 300, "random", 10),
+    "7b_192_1344_full_prefill": (slrd_shape(64, 32, 128, 8, 192, 1344, "bf16"), [200], 200, "causal", 8),
+    "7b_12pct_384_384": (slrd_shape(64, 32, 128, 4, 384, 384, "bf16"), [130, 257], 70, "causal", 6),
+    "13b_960_960": (slrd_shape(64, 40, 128, 8, 960, 960, "bf16"), [97], 97, "causal", 6),
+    "small_8_heads_160_96": (slrd_shape(64, 8, 128, 8, 160, 96, "bf16"), [700, 650, 720], 640, "causal", 6),
+    # d_ck not a multiple of 32: served query by query through the decode kernels
+    "7b_d_ck_72_handed_over": (slrd_shape(64, 32, 128, 8, 72, 56, "bf16"), [90], 50, "causal", 6),
+}
+
+
+@pytest.mark.parametrize("name", list(SLRD_CASES))
+def test_slrd_prefill_matches_oracle_and_the_absorbed_form(name):
+    sh, rows, T, kind, n_sample = SLRD_CASES[name]
+    dt, d_ck = sh["dtype"], sh["d_ck"]
+    B, stride, S = len(rows), max(rows) + 3, max(rows)
+    n_h, d_h = sh["n_heads"], sh["head_dim"]
+    rng, idx, W_ke, A_k, A_v, B_k, B_v, x, _ = _draw_slrd(sh, B * stride, B, 5200 + len(name))
+    q = rng.standard_normal((B, T, n_h, d_h))
+    dims = dims_of(sh)
+    pos = np.tile(np.arange(stride), B)
+    ke64, ck64, cv64 = orc.slrd_append(x, pos, W_ke, A_k, A_v, idx, d_h, sh["rope_base"])
+    c64 = np.concatenate([ck64, cv64], axis=1)
+    for b, n in enumerate(rows):                   # rows a sequence does not own yet: nothing may read them into a result
+        ke64[b * stride + n:(b + 1) * stride] = np.nan
+        c64[b * stride + n:(b + 1) * stride] = np.nan
+    ked, cd = dev(ke64, dt), dev(c64, dt)
+    qd, Bkd, Bvd = dev(q, dt), dev(B_k, dt), dev(B_v, dt)
+    if kind == "causal":
+        q_pos = np.array([[max(n - T + t, 0) for t in range(T)] for n in rows])
+        kv_len = np.array([[max(n - T + t + 1, 0) for t in range(T)] for n in rows])
+    else:
+        kv_len = np.stack([rng.integers(0, n + 1, size=T) for n in rows])
+        kv_len[:, ::17] = 0
+        kv_len[:, 5] = np.array(rows)
+        q_pos = np.maximum(kv_len - 1, 0)
+    out = torch.full((B, T, n_h, d_h), float("nan"), dtype=torch.bfloat16, device=DEV)
+    nws = ekv.elitekv_slrd_prefill_attn_workspace_bytes(dims, d_ck, B, T, S)
+    assert nws > 0
+    ws = torch.full((nws,), 0xFF, dtype=torch.uint8, device=DEV)
+    ekv.elitekv_slrd_prefill_attn(dims, d_ck, qd, i32(q_pos.reshape(-1)), i32(kv_len.reshape(-1)), S, stride, Bkd, Bvd,
+                                  i32(idx), ked, cd, out, ws)
+    torch.cuda.synchronize()
+    o = host64(out)
+    assert np.all(np.isfinite(o)), name
+    assert np.all(o[kv_len == 0] == 0.0)
+    # the oracle on sampled queries (first, last, block edges, random)
+    pick = sorted(set([0, T - 1, min(127, T - 1), min(128, T - 1)] + list(rng.choice(T, size=n_sample, replace=False))))
+    ke_h = np.nan_to_num(host64(ked)).reshape(B, stride, n_h, -1)
+    c_h = np.nan_to_num(host64(cd)).reshape(B, stride, -1)
+    ref = orc.slrd_multiquery_attn(host64(qd)[:, pick], q_pos[:, pick], ke_h, c_h[:, :, :d_ck], c_h[:, :, d_ck:],
+                                   kv_len[:, pick], host64(Bkd), host64(Bvd), idx, d_h, sh["rope_base"])
+    assert orc.max_abs_rel(o[:, pick], ref) <= TOL["bf16"]
+    # every query against the absorbed form (two bf16 computations, each within 2e-2 of the exact result)
+    out2 = torch.full_like(out, float("nan"))
+    ws2 = torch.empty(ekv.elitekv_slrd_multiquery_workspace_bytes(dims, d_ck, B, T, S), dtype=torch.uint8, device=DEV)
+    ekv.elitekv_slrd_multiquery_attn(dims, d_ck, qd, i32(q_pos.reshape(-1)), i32(kv_len.reshape(-1)), S, stride, Bkd,
+                                     Bvd, i32(idx), torch.nan_to_num(ked), torch.nan_to_num(cd), out2, ws2)
+    torch.cuda.synchronize()
+    o2 = host64(out2)
+    assert np.max(np.abs(o - o2)) <= 2 * TOL["bf16"] * np.max(np.abs(o2))
