@@ -416,10 +416,14 @@ hipError_t launch_prefill_flash(const DecodeArgs& a, int64_t B, int64_t T, hipSt
   bf16_t* kv = reinterpret_cast<bf16_t*>(a.ws);
 
   // K/V of every sequence's first S rows (rows past the end of the planes are left out)
+  // Sequences that lie back to back in the planes (stride == max_seq_len) are one GEMM over all their rows;
+  // otherwise one launch per sequence.
+  const bool packed = a.batch_stride_rows == S && B > 1;
   hipError_t e = hipSuccess;
-  for (int64_t b = 0; b < B; ++b) {
+  for (int64_t b = 0; b < (packed ? 1 : B); ++b) {
     const int64_t row0 = b * a.batch_stride_rows;
-    const int64_t rows = S < a.plane_rows - row0 ? S : a.plane_rows - row0;
+    const int64_t want = packed ? B * S : S;
+    const int64_t rows = want < a.plane_rows - row0 ? want : a.plane_rows - row0;
     if (rows <= 0) continue;
     AppendArgs g;
     g.dims = gd; g.d_ck = (int32_t)NK; g.W_dkv = a.W_uk; g.W_dkv2 = a.W_uv; g.W_ke = nullptr;
@@ -427,7 +431,7 @@ hipError_t launch_prefill_flash(const DecodeArgs& a, int64_t B, int64_t T, hipSt
       g.dims.d_model = a.d_ck; g.x_ld = d.d_c; g.x_off2 = a.d_ck; g.d2 = d.d_c - a.d_ck;
     }
     g.x = (const bf16_t*)a.c_plane + row0 * d.d_c; g.pos = nullptr; g.slot = nullptr; g.T = rows;   // rows written in place
-    g.elite_idx = nullptr; g.ke_plane = nullptr; g.c_plane = kv + b * S * NKV; g.plane_rows = S; g.ws = nullptr;
+    g.elite_idx = nullptr; g.ke_plane = nullptr; g.c_plane = kv + b * S * NKV; g.plane_rows = want; g.ws = nullptr;
     e = launch_append_gemm(g, stream);
     if (e != hipSuccess) return e;
   }

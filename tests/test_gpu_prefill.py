@@ -27,13 +27,16 @@ CASES = {
     "13b_full_prefill": (shape(64, 40, 128, 8, 1920, "bf16"), [97], 97, "causal", 6),
     # more work-groups than compute units, three sequences, five query blocks (an unpaired middle one)
     "many_work_groups": (shape(64, 32, 128, 8, 256, "bf16"), [700, 650, 720], 640, "causal", 5),
+    # the sequences lie back to back in the planes (stride == max_seq_len): one rebuild launch for all of them
+    "back_to_back": (shape(64, 8, 128, 8, 256, "bf16"), [300, 130, 257], 130, "causal", 8),
 }
+PAD = {"back_to_back": 0}        # plane rows between the longest sequence's end and the next sequence's start (default 3)
 
 
 def _run(name):
     sh, rows, T, kind, n_sample = CASES[name]
     dt = sh["dtype"]
-    B, stride, S = len(rows), max(rows) + 3, max(rows)
+    B, stride, S = len(rows), max(rows) + PAD.get(name, 3), max(rows)
     n_h, d_h = sh["n_heads"], sh["head_dim"]
     rng, idx, W_ke, W_dkv, W_uk, W_uv, x, _ = _draw(sh, B * stride, B, 4200 + len(name))
     q = rng.standard_normal((B, T, n_h, d_h))
@@ -82,7 +85,7 @@ def test_prefill_matches_oracle_on_sampled_queries(name):
 
 
 @pytest.mark.parametrize("name", ["small_two_seqs_causal", "small_three_blocks_random", "7b_full_prefill",
-                                  "many_work_groups"])
+                                  "many_work_groups", "back_to_back"])
 def test_prefill_agrees_with_the_absorbed_form_on_every_query(name):
     sh, rows, T, B, stride, rng, idx, qd, q_pos, kv_len, ked, cd, Wukd, Wuvd, dims, o, n_sample, S = _run(name)
     out2 = torch.full_like(torch.empty(B, T, sh["n_heads"], sh["head_dim"], dtype=torch.bfloat16, device=DEV), float("nan"))
@@ -177,6 +180,7 @@ SLRD_CASES = {
     "13b_960_960": (slrd_shape(64, 40, 128, 8, 960, 960, "bf16"), [97], 97, "causal", 6),
     "small_8_heads_160_96": (slrd_shape(64, 8, 128, 8, 160, 96, "bf16"), [700, 650, 720], 640, "causal", 6),
     # d_ck not a multiple of 32: served query by query through the decode kernels
+    "7b_576_960_back_to_back": (slrd_shape(64, 32, 128, 8, 576, 960, "bf16"), [200, 120], 100, "causal", 6),
     "7b_d_ck_72_handed_over": (slrd_shape(64, 32, 128, 8, 72, 56, "bf16"), [90], 50, "causal", 6),
 }
 
@@ -185,7 +189,7 @@ SLRD_CASES = {
 def test_slrd_prefill_matches_oracle_and_the_absorbed_form(name):
     sh, rows, T, kind, n_sample = SLRD_CASES[name]
     dt, d_ck = sh["dtype"], sh["d_ck"]
-    B, stride, S = len(rows), max(rows) + 3, max(rows)
+    B, stride, S = len(rows), max(rows) + (0 if name.endswith("back_to_back") else 3), max(rows)
     n_h, d_h = sh["n_heads"], sh["head_dim"]
     rng, idx, W_ke, A_k, A_v, B_k, B_v, x, _ = _draw_slrd(sh, B * stride, B, 5200 + len(name))
     q = rng.standard_normal((B, T, n_h, d_h))
