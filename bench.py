@@ -296,7 +296,19 @@ def comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream, 
         nbytes += c_p.numel() * c_p.element_size() + ke_p.numel() * ke_p.element_size()
     ev.record(e1, stream)
     torch.cuda.synchronize()
-    out["stream_read_GBs"] = round(nbytes / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9, 1)
+    out["stream_read_planes_GBs"] = round(nbytes / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9, 1)
+    # the same kernel over 1 GiB in one launch (no launch gaps, no ramp between planes): the ceiling
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    for i in range(2):
+        ekv.elitekv_stream_read(big, sink, stream=stream)
+    ev.record(e0, stream)
+    for i in range(10):
+        ekv.elitekv_stream_read(big, sink, stream=stream)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    out["stream_read_GBs"] = max(round(10 * big.numel() / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9, 1),
+                                 out["stream_read_planes_GBs"])
+    del big
     # a plain device-to-device copy of known size: the reference the HBM byte counters
     # (FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc) are scaled by
     src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
