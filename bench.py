@@ -254,9 +254,8 @@ def main():
         if not d_ck and B < 8:
             result["block_step"] = block_step(ekv, ev, cfg, dims, planes, x_d, pos_d, slot_d, seq_d, W_ke_d, W_dkv_d, W_uk_d,
                                               W_uv_d, idx_d, dev, dt, stream, cache_bytes, args)
-        if not d_ck:
-            result["prefill_attn"] = prefill_attn(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
-                                                  T=args.prefill_tokens)
+        result["prefill_attn"] = prefill_attn(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
+                                              T=args.prefill_tokens)
         result["ropelite_search"] = ropelite_search(ekv, ev, cfg, dev, stream)
         result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream,
                                                   T=args.prefill_tokens)
@@ -465,10 +464,17 @@ def prefill_attn(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, str
     pos = torch.arange(T, device=dev, dtype=torch.int32)
     kv = pos + 1
     out = torch.empty(1, T, n_h, d_h, dtype=dt, device=dev)
-    ws = torch.empty(ekv.elitekv_prefill_attn_workspace_bytes(dims, 1, T, T), dtype=torch.uint8, device=dev)
+    d_ck = cfg.d_ck                                   # > 0: separated latents (W_uk_d = B^k_S, W_uv_d = B^v_S)
+    nws = (ekv.elitekv_slrd_prefill_attn_workspace_bytes(dims, d_ck, 1, T, T) if d_ck
+           else ekv.elitekv_prefill_attn_workspace_bytes(dims, 1, T, T))
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev)
 
     def call():
-        ekv.elitekv_prefill_attn(dims, q, pos, kv, T, T, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out, ws, stream=stream)
+        if d_ck:
+            ekv.elitekv_slrd_prefill_attn(dims, d_ck, q, pos, kv, T, T, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out, ws,
+                                          stream=stream)
+        else:
+            ekv.elitekv_prefill_attn(dims, q, pos, kv, T, T, W_uk_d, W_uv_d, idx_d, ke_p, c_p, out, ws, stream=stream)
     for _ in range(3):
         call()
     e0, e1 = ev.create(), ev.create()
@@ -478,13 +484,15 @@ def prefill_attn(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, str
     ev.record(e1, stream)
     torch.cuda.synchronize()
     ms = ev.elapsed_ms(e0, e1) / iters
-    fl_rebuild = 2.0 * T * d_c * n_h * (2 * d_h - 2 * r)
+    fl_rebuild = (2.0 * T * n_h * (d_ck * (d_h - 2 * r) + (d_c - d_ck) * d_h) if d_ck
+                  else 2.0 * T * d_c * n_h * (2 * d_h - 2 * r))
     fl_attn = 4.0 * d_h * n_h * (T * (T + 1) / 2)
     tf = (fl_rebuild + fl_attn) / (ms * 1e-3) / 1e12
     return {"tokens": T, "ms": round(ms, 5), "TFLOPs": round(tf, 1), "bound": "mfma", "peak_TFLOPs": 2500.0,
             "frac": round(tf / 2500.0, 4), "rebuild_GFLOP": round(fl_rebuild / 1e9, 1),
             "attention_GFLOP": round(fl_attn / 1e9, 1),
-            "absorbed_form_GFLOP": round(n_h * (4.0 * d_c + 4 * r) * (T * (T + 1) / 2) / 1e9, 1),
+            "absorbed_form_GFLOP": round(n_h * (2.0 * (d_ck or d_c) + 2.0 * (d_c - d_ck if d_ck else d_c) + 4 * r)
+                                         * (T * (T + 1) / 2) / 1e9, 1),
             "query_tokens_per_s": round(T / (ms * 1e-3), 1)}
 
 
