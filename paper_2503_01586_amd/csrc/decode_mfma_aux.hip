@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
     const bf16_t* wb = W_uv + ((int64_t)(col0 + wave * RPI + rr) * n_h + head) * DH + jl * 8;
 #pragma unroll
     for (int i = 0; i < NWI; ++i)
-      wreg[i] = *reinterpret_cast<const uint4*>(wb + (int64_t)i * 4 * RPI * n_h * DH);
+      wreg[i] = ld16_stream(wb + (int64_t)i * 4 * RPI * n_h * DH);
   }
   // (2) first batch of split accumulators: group sg takes splits sg, sg + NG, ...
   const int cl = tid % LPR, sg = tid / LPR;

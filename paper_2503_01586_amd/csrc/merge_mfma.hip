@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void merge_up_mfma_kernel(
 #pragma unroll
   for (int i = 0; i < WPASS; ++i) {
     const int e = i * 256 + tid, k = e / CPR, c = e % CPR;
-    wld[i] = *reinterpret_cast<const uint4*>(W_uv + ((int64_t)(col0 + k) * n_h + head) * DH + c * 8);
+    wld[i] = ld16_stream(W_uv + ((int64_t)(col0 + k) * n_h + head) * DH + c * 8);
   }
   //      split accumulators: thread <-> (item g [+16], 16-byte piece cl); item = (row rl, slice sl);
   //      slice sl of SL takes the splits sl, sl + SL, ...
