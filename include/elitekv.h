@@ -399,8 +399,10 @@ int elitekv_mha_decode(const elitekv_dims* dims, const void* q, const int32_t* q
 
 /*
  * Streaming-read probe: reads `bytes` bytes at `src` (16-byte aligned, bytes % 16 == 0) once with
- * wide coalesced loads and folds them into sink[0..grid) so the reads cannot be elided.  Gives the
- * achievable HBM read rate to compare the decode kernel against.  sink: >= 4096 uint32.
+ * wide coalesced non-temporal loads (the kind the attention kernel uses for cache rows) and folds them
+ * into sink[0..grid) so the reads cannot be elided.  Gives the achievable HBM read rate to compare the
+ * decode kernel against; launches of a gigabyte show the ceiling, launches of a plane's size include the
+ * start-up of a launch.  sink: >= 4096 uint32.
  */
 int elitekv_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
 
