@@ -324,6 +324,20 @@ def comparators(ekv, ev, cfg, dims, planes, q_d, pos_d, seq_d, dev, dt, stream, 
     torch.cuda.synchronize()
     out["stream_read_GBs"] = max(round(10 * big.numel() / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9, 1),
                                  out["stream_read_planes_GBs"])
+    # what the cache hint and the load path are worth: plain / non-temporal loads, into registers / straight into LDS
+    kinds = {}
+    for mode, name in ((0, "registers_plain"), (1, "registers_nt"), (2, "to_lds_plain"), (3, "to_lds_nt")):
+        n_read = 0
+        for i in range(2):
+            n_read = ekv.elitekv_stream_read_mode(big, sink, mode, stream=stream)
+        ev.record(e0, stream)
+        for i in range(10):
+            ekv.elitekv_stream_read_mode(big, sink, mode, stream=stream)
+        ev.record(e1, stream)
+        torch.cuda.synchronize()
+        kinds[name] = round(10 * n_read / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9, 1)
+    out["stream_read_1GiB_by_load_kind_GBs"] = kinds
+    out["stream_read_GBs"] = max(out["stream_read_GBs"], *kinds.values())      # the ceiling: the best of them
     del big
     # a plain device-to-device copy of known size: the reference the HBM byte counters
     # (FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc) are scaled by

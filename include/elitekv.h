@@ -406,6 +406,17 @@ int elitekv_mha_decode(const elitekv_dims* dims, const void* q, const int32_t* q
  */
 int elitekv_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
 
+/*
+ * The same probe with the kind of load chosen by the caller, to show what the cache hint and the load
+ * path are worth on this machine.  mode bit 0: the loads carry the non-temporal bit; bit 1: direct
+ * global->LDS loads (the path the attention kernel's tiles take; 512 work-groups, every wave keeps 16 KiB in
+ * flight, nothing reads the LDS) instead of loads into registers.  The direct form reads whole units of
+ * 16 MiB only; *bytes_read (host pointer, may be NULL) receives the number of bytes the launch reads.
+ * EINVAL unless 0 <= mode <= 3; other errors as elitekv_stream_read (mode 1 is that call).
+ */
+int elitekv_stream_read_mode(const void* src, size_t bytes, uint32_t* sink, int32_t mode, size_t* bytes_read,
+                             void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

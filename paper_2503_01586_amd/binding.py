@@ -80,6 +80,7 @@ def _load():
         "elitekv_mha_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_mha_decode": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, I64, P, P, SZ, I32, P]),
         "elitekv_stream_read": (C.c_int, [P, SZ, P, P]),
+        "elitekv_stream_read_mode": (C.c_int, [P, SZ, P, I32, C.POINTER(SZ), P]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -391,6 +392,15 @@ def elitekv_stream_read(src, sink, nbytes=None, stream=None):
     nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
     st = _lib.elitekv_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream))
     _check(st, "elitekv_stream_read")
+
+
+def elitekv_stream_read_mode(src, sink, mode, nbytes=None, stream=None) -> int:
+    """Returns the number of bytes the launch reads."""
+    nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
+    n = C.c_size_t()
+    st = _lib.elitekv_stream_read_mode(_ptr(src), int(nbytes), _ptr(sink), int(mode), C.byref(n), _stream(stream))
+    _check(st, "elitekv_stream_read_mode")
+    return int(n.value)
 
 
 def raw():

@@ -193,9 +193,12 @@ hipError_t launch_mha_decode(const MhaArgs& a, hipStream_t stream) {
 constexpr int kStreamThreads = 256;
 constexpr int kStreamGrid = 2048;
 
+// NT: the loads carry the non-temporal bit
+template <bool NT>
 __global__ __launch_bounds__(kStreamThreads) void stream_read_kernel(const uint4* __restrict__ src,
                                                                      size_t n16, uint32_t* sink) {
   // every block streams one contiguous share, eight 16-byte loads per thread in flight
+  auto ld = [](const uint4* p) -> ck_u32x4 { return NT ? stream16(p) : *reinterpret_cast<const ck_u32x4*>(p); };
   uint32_t acc = 0;
   const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
   const size_t lo = per * blockIdx.x, hi = min(lo + per, n16);
@@ -203,12 +206,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_read_kernel(const uint4
   for (; i + 7 * kStreamThreads < hi; i += 8 * kStreamThreads) {
     ck_u32x4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = stream16(src + i + u * kStreamThreads);
+    for (int u = 0; u < 8; ++u) v[u] = ld(src + i + u * kStreamThreads);
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
   for (; i < hi; i += kStreamThreads) {
-    const ck_u32x4 a = stream16(src + i);
+    const ck_u32x4 a = ld(src + i);
     acc ^= a.x ^ a.y ^ a.z ^ a.w;
   }
 #pragma unroll
@@ -216,8 +219,56 @@ __global__ __launch_bounds__(kStreamThreads) void stream_read_kernel(const uint4
   if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
 }
 
-hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream) {
-  stream_read_kernel<<<kStreamGrid, kStreamThreads, 0, stream>>>((const uint4*)src, bytes / 16, sink);
+// The same stream through direct global->LDS loads (what the attention kernel's tiles come in by): every wave
+// keeps two groups of eight 1 KiB loads in flight in an LDS area of its own; nothing reads the LDS.  Whole
+// 8 KiB groups only: the last bytes % (grid * 4 waves * 8 KiB) bytes are left out (the caller accounts for them).
+constexpr int kStreamLdsGrid = 512;
+constexpr int kStreamLdsBytes = 4 * 16384;
+constexpr size_t kStreamLdsUnit = (size_t)kStreamLdsGrid * 4 * 8192;
+
+template <bool NT>
+__global__ __launch_bounds__(kStreamThreads) void stream_read_lds_kernel(const char* __restrict__ src, size_t groups,
+                                                                         uint32_t* sink) {
+  extern __shared__ __attribute__((aligned(16))) char ssm[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const char* p = src + ((size_t)blockIdx.x * 4 + wave) * groups * 8192 + lane * 16;
+  const uint32_t base = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ssm + wave * 16384);
+  for (size_t g = 0; g < groups; ++g) {
+    const uint32_t b = base + (uint32_t)(g & 1) * 8192;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (NT)
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off nt" : : "s"(b + u * 1024), "v"(p + u * 1024) : "memory", "m0");
+      else
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(b + u * 1024), "v"(p + u * 1024) : "memory", "m0");
+    }
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");         // the group before this one has landed
+    p += 8192;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) atomicXor(&sink[blockIdx.x], (uint32_t)(unsigned char)ssm[0]);
+}
+
+// mode bit 0: non-temporal loads; bit 1: direct global->LDS loads instead of loads into registers
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int mode, size_t* bytes_read,
+                              hipStream_t stream) {
+  if (mode & 2) {
+    const size_t groups = bytes / kStreamLdsUnit;            // 8 KiB groups per wave
+    if (bytes_read) *bytes_read = groups * kStreamLdsUnit;
+    if (groups == 0) return hipSuccess;
+    static LdsLimit lim0, lim1;
+    hipError_t e = (mode & 1) ? raise_lds_limit(lim1, reinterpret_cast<const void*>(&stream_read_lds_kernel<true>), kStreamLdsBytes)
+                              : raise_lds_limit(lim0, reinterpret_cast<const void*>(&stream_read_lds_kernel<false>), kStreamLdsBytes);
+    if (e != hipSuccess) return e;
+    if (mode & 1) stream_read_lds_kernel<true><<<kStreamLdsGrid, kStreamThreads, kStreamLdsBytes, stream>>>((const char*)src, groups, sink);
+    else stream_read_lds_kernel<false><<<kStreamLdsGrid, kStreamThreads, kStreamLdsBytes, stream>>>((const char*)src, groups, sink);
+    return hipGetLastError();
+  }
+  if (bytes_read) *bytes_read = bytes;
+  if (mode & 1) stream_read_kernel<true><<<kStreamGrid, kStreamThreads, 0, stream>>>((const uint4*)src, bytes / 16, sink);
+  else stream_read_kernel<false><<<kStreamGrid, kStreamThreads, 0, stream>>>((const uint4*)src, bytes / 16, sink);
   return hipGetLastError();
 }
 

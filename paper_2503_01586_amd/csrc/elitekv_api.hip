@@ -708,7 +708,18 @@ int elitekv_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip
   if (!src || !sink) return ELITEKV_ENULL;
   if (!aligned16(src) || (bytes & 15u)) return ELITEKV_EALIGN;
   if (bytes == 0) return ELITEKV_OK;
-  const hipError_t e = launch_stream_read(src, bytes, sink, (hipStream_t)hip_stream);
+  const hipError_t e = launch_stream_read(src, bytes, sink, 1, nullptr, (hipStream_t)hip_stream);
+  return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+int elitekv_stream_read_mode(const void* src, size_t bytes, uint32_t* sink, int32_t mode, size_t* bytes_read,
+                             void* hip_stream) {
+  if (!src || !sink) return ELITEKV_ENULL;
+  if (mode < 0 || mode > 3) return ELITEKV_EINVAL;
+  if (!aligned16(src) || (bytes & 15u)) return ELITEKV_EALIGN;
+  if (bytes_read) *bytes_read = 0;
+  if (bytes == 0) return ELITEKV_OK;
+  const hipError_t e = launch_stream_read(src, bytes, sink, mode, bytes_read, (hipStream_t)hip_stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
 }
 

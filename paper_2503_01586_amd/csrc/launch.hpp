@@ -166,6 +166,7 @@ size_t search_workspace_bytes(int64_t T, int n_h, int d_h);
 hipError_t launch_ropelite_search(const float* q, const float* k, const int32_t* pos, int64_t T, int n_h, int d_h,
                                   int r, double rope_base, int32_t* elite_out, float* dist_out, char* ws,
                                   hipStream_t stream);
-hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int mode, size_t* bytes_read,
+                              hipStream_t stream);
 
 }  // namespace ekv

@@ -149,6 +149,12 @@ def test_mha_and_stream_argument_errors():
     assert lib.elitekv_stream_read(None, 16, FAKE, None) == ekv.ENULL
     assert lib.elitekv_stream_read(FAKE, 24, FAKE, None) == ekv.EALIGN
     assert lib.elitekv_stream_read(FAKE, 0, FAKE, None) == ekv.OK
+    n = C.c_size_t(7)
+    assert lib.elitekv_stream_read_mode(FAKE, 32, FAKE, 4, C.byref(n), None) == ekv.EINVAL
+    assert lib.elitekv_stream_read_mode(FAKE, 32, FAKE, -1, None, None) == ekv.EINVAL
+    assert lib.elitekv_stream_read_mode(None, 32, FAKE, 0, None, None) == ekv.ENULL
+    assert lib.elitekv_stream_read_mode(FAKE, 24, FAKE, 3, None, None) == ekv.EALIGN
+    assert lib.elitekv_stream_read_mode(FAKE, 0, FAKE, 3, C.byref(n), None) == ekv.OK and n.value == 0
 
 
 def test_slrd_argument_errors():

@@ -272,3 +272,21 @@ def test_stream_read_probe_runs():
     want = int(np.bitwise_xor.reduce(np.arange(1 << 20, dtype=np.uint32)))
     got = int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)))
     assert got == want
+
+
+def test_stream_read_by_load_kind():
+    """Loads into registers (plain, non-temporal) fold every word read; the direct global->LDS forms read
+    whole 16 MiB units and report how many bytes that was."""
+    n_words = 9 << 20                                            # 36 MiB: two units and a remainder
+    src = torch.arange(n_words, dtype=torch.int32, device=DEV)
+    want = int(np.bitwise_xor.reduce(np.arange(n_words, dtype=np.uint32)))
+    for mode in (0, 1):
+        sink = torch.zeros(4096, dtype=torch.int32, device=DEV)
+        assert ekv.elitekv_stream_read_mode(src, sink, mode) == 4 * n_words
+        torch.cuda.synchronize()
+        assert int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))) == want
+    for mode in (2, 3):
+        sink = torch.zeros(4096, dtype=torch.int32, device=DEV)
+        assert ekv.elitekv_stream_read_mode(src, sink, mode) == 32 << 20
+        assert ekv.elitekv_stream_read_mode(src, sink, mode, nbytes=8 << 20) == 0     # less than one unit: no launch
+        torch.cuda.synchronize()
