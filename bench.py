@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
 # by the readings of a plain copy of known size (profiles/attn_mfma_<workload>.md); workloads that
 # have not been counted report null.
-TRAFFIC_BYTES = {"7b_25_b1_s32768": 160.5e6, "7b_25_b8_s4096": 166.1e6, "13b_25_b16_s8192": 727.3e6,
+TRAFFIC_BYTES = {"7b_25_b1_s32768": 160.5e6, "7b_25_b8_s4096": 166.1e6, "13b_25_b16_s8192": 711.4e6,
                  "7b_12_b64_s2048": 319.6e6, "7b_25_slrd_b1_s32768": 150.6e6, "7b_25_slrd_b8_s4096": 150.4e6}
 METRIC = "decode attn HBM GB/s (% of peak) + tokens/s, 7B shape 25% cache, 32K ctx"
 
