@@ -5,7 +5,8 @@ A step is one pass of the whole hot path over one batch of synthetic input:
   cache planes) followed by elitekv_decode_attn over the whole cached context.
 The default workload is the 7B shape at 25 % cache, batch 1, 32K context.  Inputs are resident
 in HBM before the timed region.  The timed steps cycle over several distinct copies of the
-cache planes (>= 1 GiB in total) so that the 256 MB Infinity Cache cannot serve the reads.
+cache planes (>= 1 GiB in total) and of the weights (>= 512 MB in total: a model's next layer brings its
+own) so that the 256 MB Infinity Cache cannot serve the reads.
 
 Prints one JSON line.
 """
