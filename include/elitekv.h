@@ -197,8 +197,9 @@ int elitekv_multiquery_attn(const elitekv_dims* dims, const void* q, const int32
  *   q [B, T, n_h, d_h]   q_pos [B * T]   kv_len [B * T]   out [B, T, n_h, d_h]   (device pointers)
  * bf16, head_dim 128, r in {4, 8}, d_c a multiple of 32, n_h (2 d_h - 2 r) a multiple of 128,
  * T >= 48 and max_seq_len > 64 run this path; every other call is handed to elitekv_multiquery_attn
- * (and its limits apply): with fewer queries per sequence the absorbed form is the cheaper order.  Rows of a sequence beyond the largest kv_len of its queries are never read by the
- * attention, but the first max_seq_len rows of the latent plane are read by the rebuild.
+ * (and its limits apply): with fewer queries per sequence the absorbed form is the cheaper order.
+ * Rows of a sequence beyond the largest kv_len of its queries are never read by the attention, but
+ * the first max_seq_len rows of the latent plane are read by the rebuild.
  * Workspace: the _workspace_bytes function (about B * max_seq_len * n_h * (2 d_h - 2 r) * 2 bytes).
  * Errors as elitekv_decode_attn; EUNSUPPORTED if B * T > 2^24.
  * ------------------------------------------------------------------------------------------- */
