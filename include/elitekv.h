@@ -40,7 +40,8 @@ enum elitekv_status {
   ELITEKV_EALIGN = -4,        /* a pointer or stride misses the 16-byte alignment the kernels need */
   ELITEKV_EWORKSPACE = -5,    /* workspace smaller than the matching *_workspace_bytes() */
   ELITEKV_EUNSUPPORTED = -6,  /* shape outside what the kernels cover (see each call) */
-  ELITEKV_EHIP = -7           /* the HIP runtime reported a launch error */
+  ELITEKV_EHIP = -7,          /* the HIP runtime reported a launch error */
+  ELITEKV_ESCRATCH = -8       /* elitekv_decode_attn_noalloc: the call needs more than the built-in scratch holds */
 };
 
 enum elitekv_dtype {
@@ -148,6 +149,29 @@ int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* 
                         const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
                         int64_t plane_rows, void* out, void* ws, size_t ws_bytes, int32_t n_splits,
                         void* hip_stream);
+
+/*
+ * elitekv_decode_attn for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (without ws / ws_bytes), same kernels and bit-for-bit the same result as elitekv_decode_attn; the
+ * intermediates live in a buffer of ELITEKV_NOALLOC_SCRATCH_BYTES that is part of the library's device
+ * image (one copy per GPU, held until the process ends).  The call allocates and frees nothing.
+ *   - ESCRATCH (nothing enqueued) when elitekv_decode_workspace_bytes(dims, B, max_seq_len, n_splits)
+ *     exceeds ELITEKV_NOALLOC_SCRATCH_BYTES; 32 MiB covers the 7B shape at 25 % cache, one sequence,
+ *     32768 cached tokens with the automatic split count.
+ *   - All calls on one GPU share that GPU's buffer: two calls whose kernels may overlap (different
+ *     streams, no ordering between them) race.  Calls on one stream are ordered and safe.  Nothing in
+ *     the buffer has to be cleared between calls.
+ *   - The buffer's address is looked up on the first call on each device (hipGetSymbolAddress); make
+ *     that first call outside a graph capture.
+ * Other errors as elitekv_decode_attn; EHIP also if the buffer's address cannot be obtained.
+ */
+#define ELITEKV_NOALLOC_SCRATCH_BYTES (32u << 20)
+int elitekv_decode_attn_noalloc(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                                const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                                int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                                const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                                int64_t plane_rows, void* out, int32_t n_splits, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
  * RoPElite search (Section 3.1, Algorithm 1): the greedy choice of every head's r elite chunks from

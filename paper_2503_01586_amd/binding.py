@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_PKG, "libelitekv.so")
 ELITEKV_FP32 = 0
 ELITEKV_BF16 = 1
 
-OK, EINVAL, EINDEX, ENULL, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, EINDEX, ENULL, EALIGN, EWORKSPACE, EUNSUPPORTED, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5, -6, -7, -8
+NOALLOC_SCRATCH_BYTES = 32 << 20   # ELITEKV_NOALLOC_SCRATCH_BYTES
 
 
 class elitekv_dims(C.Structure):
@@ -50,6 +51,7 @@ def _load():
         "elitekv_decode_auto_splits": (I32, [DP, I64, I64]),
         "elitekv_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_decode_attn": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32, P]),
+        "elitekv_decode_attn_noalloc": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, I32, P]),
         "elitekv_ropelite_search_workspace_bytes": (SZ, [I64, I32, I32, I32]),
         "elitekv_ropelite_search": (C.c_int, [P, P, P, I64, I32, I32, I32, C.c_double, P, P, P, SZ, P]),
         "elitekv_multiquery_workspace_bytes": (SZ, [DP, I64, I64, I64, I32]),
@@ -182,6 +184,17 @@ def elitekv_decode_attn(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows,
                                   _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
                                   _ptr(out), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
     _check(st, "elitekv_decode_attn")
+
+
+def elitekv_decode_attn_noalloc(dims, q, q_pos, seq_len, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+                                ke_plane, c_plane, out, n_splits=0, stream=None, B=None, plane_rows=None):
+    B = q.shape[0] if B is None else B
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    st = _lib.elitekv_decode_attn_noalloc(C.byref(dims), _ptr(q), _ptr(q_pos), _ptr(seq_len), int(B),
+                                          int(max_seq_len), int(batch_stride_rows), _ptr(W_uk), _ptr(W_uv),
+                                          _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane), int(plane_rows),
+                                          _ptr(out), int(n_splits), _stream(stream))
+    _check(st, "elitekv_decode_attn_noalloc")
 
 
 def elitekv_ropelite_search_workspace_bytes(T, n_heads, head_dim, r) -> int:

@@ -5,7 +5,24 @@
 
 #include "launch.hpp"
 
+// Built-in scratch of elitekv_decode_attn_noalloc: device memory that belongs to the library's code
+// object (every GPU the library runs on holds its own copy until the process ends).  In host code the
+// array's NAME is only a handle for hipGetSymbolAddress; kernels are given the looked-up address.
+static __device__ __align__(256) unsigned char scratch[ELITEKV_NOALLOC_SCRATCH_BYTES];
+
 namespace ekv {
+
+// Device address of `scratch` on the current device, looked up once per device; nullptr on error.
+static void* scratch_ptr() {
+  static std::atomic<void*> addr[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = addr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  addr[dev].store(p, std::memory_order_release);
+  return p;
+}
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
@@ -165,6 +182,7 @@ const char* elitekv_strerror(int status) {
     case ELITEKV_EWORKSPACE: return "workspace too small";
     case ELITEKV_EUNSUPPORTED: return "shape not covered by the kernels";
     case ELITEKV_EHIP: return "HIP launch error";
+    case ELITEKV_ESCRATCH: return "call needs more than the built-in scratch buffer holds";
     default: return "unknown status";
   }
 }
@@ -659,6 +677,23 @@ int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* 
                         void* hip_stream) {
   return decode_impl(dims, 0, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
                      ke_plane, c_plane, plane_rows, out, ws, ws_bytes, n_splits, hip_stream, 7);
+}
+
+int elitekv_decode_attn_noalloc(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
+                                const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                                int64_t batch_stride_rows, const void* W_uk, const void* W_uv,
+                                const int32_t* elite_idx, const void* ke_plane, const void* c_plane,
+                                int64_t plane_rows, void* out, int32_t n_splits, void* hip_stream) {
+  DecodePlan p;
+  const int st = plan_decode(dims, 0, B, max_seq_len, n_splits, &p);
+  if (st) return st;
+  if (p.total > (size_t)ELITEKV_NOALLOC_SCRATCH_BYTES) return ELITEKV_ESCRATCH;
+  void* ws = scratch_ptr();
+  if (!ws) return ELITEKV_EHIP;
+  // every kernel of the call writes the part of the scratch it later reads (empty splits included),
+  // so nothing needs clearing between calls
+  return decode_impl(dims, 0, q, q_pos, seq_len, B, max_seq_len, batch_stride_rows, W_uk, W_uv, elite_idx,
+                     ke_plane, c_plane, plane_rows, out, ws, ELITEKV_NOALLOC_SCRATCH_BYTES, n_splits, hip_stream, 7);
 }
 
 int elitekv_decode_attn_stages(const elitekv_dims* dims, const void* q, const int32_t* q_pos,

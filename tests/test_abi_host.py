@@ -300,3 +300,19 @@ def test_slrd_prefill_argument_errors():
     for dims_, d_ck, T in [(big, 584, 300), (big, 576, 8), (ekv.make_dims(5120, 40, 128, 4, 960, "bf16"), 480, 300)]:
         assert ekv.elitekv_slrd_prefill_attn_workspace_bytes(dims_, d_ck, 1, T, 512) == \
             ekv.elitekv_slrd_multiquery_workspace_bytes(dims_, d_ck, 1, T, 512)
+
+
+def test_noalloc_entry_point_rejects_oversized_calls_on_the_host():
+    """The scratch-size check comes before anything touches a device: a call whose workspace exceeds the
+    built-in buffer is refused with ESCRATCH (no GPU needed), and bad dims keep their own codes."""
+    import ctypes as C
+    dims = ekv.make_dims(4096, 32, 128, 8, 1536, "bf16")
+    assert ekv.elitekv_decode_workspace_bytes(dims, 1, 32768, 512) > ekv.NOALLOC_SCRATCH_BYTES
+    p = 4096   # never dereferenced
+    st = ekv.raw().elitekv_decode_attn_noalloc(C.byref(dims), p, p, p, 1, 32768, 32768, p, p, p, p, p, 32768, p, 512,
+                                               None)
+    assert st == ekv.ESCRATCH
+    assert "scratch" in ekv.elitekv_strerror(st)
+    bad = ekv.make_dims(4096, 32, 127, 8, 1536, "bf16")
+    st = ekv.raw().elitekv_decode_attn_noalloc(C.byref(bad), p, p, p, 1, 64, 64, p, p, p, p, p, 64, p, 0, None)
+    assert st == ekv.EINVAL
