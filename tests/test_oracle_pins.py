@@ -496,3 +496,51 @@ def test_planted_mistakes_are_caught(monkeypatch, mutation):
             return np.array([[int(t), int(t) + 4] for t in np.asarray(i).tolist()]).reshape(-1)
         monkeypatch.setattr(orc, "elite_dims", half)
     assert _some_pin_fails()
+
+
+def _metric_cases():
+    rows = []
+    for line in open(os.path.join(GOLDEN, "max_abs_rel_cases.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        got, ref, want = (part.split() for part in line.split(";"))
+        rows.append((np.array(got, dtype=float), np.array(ref, dtype=float), float(want[0])))
+    return rows
+
+
+def _metric_pin():
+    rows = _metric_cases()
+    assert len(rows) == 6
+    for got, ref, want in rows:
+        assert abs(orc.max_abs_rel(got, ref) - want) <= 1e-12 * max(want, 1.0), (got, ref, want)
+    # shape does not matter, one tensor = one number; an empty tensor has no error
+    assert abs(orc.max_abs_rel(np.array([[1.25, 2.0], [3.0, 11.0]]), np.array([[1.0, 2.0], [3.0, 10.0]])) - 0.1) < 1e-15
+    assert orc.max_abs_rel(np.zeros((0, 3)), np.zeros((0, 3))) == 0.0
+    # the metric of the parity gates is scale-free and not symmetric in its arguments
+    assert abs(orc.max_abs_rel(3.0 * np.array([1.5, -6.0]), 3.0 * np.array([1.0, -4.0])) - 0.5) < 1e-15
+    assert abs(orc.max_abs_rel(np.array([1.0, -4.0]), np.array([1.5, -6.0])) - 1.0 / 3.0) < 1e-15
+    # a NaN anywhere in the result must not pass a gate of the form  err <= tol
+    assert not (orc.max_abs_rel(np.array([1.0, np.nan]), np.array([1.0, 2.0])) <= 1.0)
+
+
+def test_max_abs_rel_hand_computed_cases():
+    """The metric every GPU parity gate uses, on hand-computed cases (tests/golden/max_abs_rel_cases.txt):
+    normalised by the largest |ref| (not |got|), absolute values on both the difference and the
+    normaliser, zero reference floored at 1e-30, empty tensors, NaN results."""
+    _metric_pin()
+
+
+@pytest.mark.parametrize("mutation", ["normalise_by_got", "no_abs_on_difference", "signed_normaliser", "mean_not_max",
+                                      "nan_ignored"])
+def test_planted_metric_mistakes_are_caught(monkeypatch, mutation):
+    bad = {
+        "normalise_by_got": lambda g, r: float(np.max(np.abs(np.asarray(g) - np.asarray(r)))) / max(float(np.max(np.abs(g))), 1e-30),
+        "no_abs_on_difference": lambda g, r: float(np.max(np.asarray(g) - np.asarray(r))) / max(float(np.max(np.abs(r))), 1e-30),
+        "signed_normaliser": lambda g, r: float(np.max(np.abs(np.asarray(g) - np.asarray(r)))) / max(float(np.max(r)), 1e-30),
+        "mean_not_max": lambda g, r: float(np.mean(np.abs(np.asarray(g) - np.asarray(r)))) / max(float(np.max(np.abs(r))), 1e-30),
+        "nan_ignored": lambda g, r: float(np.nanmax(np.abs(np.asarray(g) - np.asarray(r)))) / max(float(np.max(np.abs(r))), 1e-30),
+    }[mutation]
+    monkeypatch.setattr(orc, "max_abs_rel", lambda g, r: 0.0 if np.asarray(r).size == 0 else bad(g, r))
+    with pytest.raises(AssertionError):
+        _metric_pin()
