@@ -98,7 +98,7 @@ size_t elitekv_append_workspace_bytes(const elitekv_dims* dims, int64_t T);
  *   hip_stream a hipStream_t (NULL = the default stream)
  *
  * T == 0 is a successful no-op.  Errors: EINVAL, ENULL, EALIGN (pointers must be 16-byte aligned),
- * EWORKSPACE, EHIP.
+ * EWORKSPACE, EUNSUPPORTED (head_dim > 256), EHIP.
  */
 int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, const int64_t* slot,
                    int64_t T, const void* W_ke, const void* W_dkv, const int32_t* elite_idx,
@@ -141,7 +141,7 @@ size_t elitekv_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64
  *              beyond rounding.
  *
  * B == 0 is a successful no-op.  Errors: EINVAL, ENULL, EALIGN, EWORKSPACE, EUNSUPPORTED
- * (d_c > 4096, or n_splits > 1024), EHIP.
+ * (d_c > 4096, head_dim > 256, or n_splits > 1024), EHIP.
  */
 int elitekv_decode_attn(const elitekv_dims* dims, const void* q, const int32_t* q_pos,
                         const int32_t* seq_len, int64_t B, int64_t max_seq_len,

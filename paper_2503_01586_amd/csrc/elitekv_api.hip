@@ -239,6 +239,7 @@ static int append_check(const elitekv_dims* dims, int32_t d_ck, const void* x, c
   int st = check_dims(dims);
   if (st) return st;
   if (T < 0 || plane_rows < 0 || d_ck <= 0 || d_ck > dims->d_c) return ELITEKV_EINVAL;
+  if (dims->head_dim > 256) return ELITEKV_EUNSUPPORTED;     // the kernels' RoPE table holds 128 chunk frequencies
   if (T == 0) return ELITEKV_OK;
   if (!x || !pos || !slot || !W_dkv || !c_plane) return ELITEKV_ENULL;
   if (d_ck < dims->d_c && !W_dkv2) return ELITEKV_ENULL;

@@ -316,3 +316,19 @@ def test_noalloc_entry_point_rejects_oversized_calls_on_the_host():
     bad = ekv.make_dims(4096, 32, 127, 8, 1536, "bf16")
     st = ekv.raw().elitekv_decode_attn_noalloc(C.byref(bad), p, p, p, 1, 64, 64, p, p, p, p, p, 64, p, 0, None)
     assert st == ekv.EINVAL
+
+
+def test_append_rejects_head_dims_beyond_the_rope_table():
+    """head_dim > 256 would index past the 128 chunk frequencies the append kernels are given:
+    refused on the host (EUNSUPPORTED, the limit the decode path has), also through the S-LRD append
+    and the decode step."""
+    import ctypes as C
+    dims = ekv.make_dims(1024, 2, 512, 4, 128, "bf16")
+    p = 4096   # never dereferenced
+    lib = ekv.raw()
+    assert lib.elitekv_append(C.byref(dims), p, p, p, 3, p, p, p, p, p, 16, p, 1 << 20, None) == ekv.EUNSUPPORTED
+    assert lib.elitekv_slrd_append(C.byref(dims), 64, p, p, p, 3, p, p, p, p, p, p, 16, p, 1 << 20, None) == ekv.EUNSUPPORTED
+    assert lib.elitekv_decode_step(C.byref(dims), p, p, p, p, p, 1, 16, 16, p, p, p, p, p, p, p, 16, p, p, 1 << 20, 0,
+                                   None) == ekv.EUNSUPPORTED
+    ok = ekv.make_dims(1024, 2, 256, 4, 128, "bf16")
+    assert lib.elitekv_append(C.byref(ok), p, p, p, 0, p, p, p, p, p, 16, p, 1 << 20, None) == ekv.OK
