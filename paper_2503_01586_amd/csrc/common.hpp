@@ -43,6 +43,19 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Layout of the absorbed query in the workspace of the matrix-core decode path: element (b, h, k) of
+// q~ [B, n_h, d_q] is stored so that what one wave of the attention kernel loads with one instruction,
+// the MFMA operand of 16 heads x 32 latent columns (lane l: head 16*hh + l%16, columns 8*(l/16) .. +8),
+// is one contiguous KiB: blocks [b][head group of 32][column slice of qs][32-column step][head half],
+// inside a block lane-major, 8 columns per lane.  Head groups are padded to 32 heads (slots of heads
+// beyond n_h are never written or used).
+__host__ __device__ inline int64_t qt_packed_index(int b, int h, int k, int head_groups, int d_q, int qs) {
+  const int hg = h >> 5, hh = (h >> 4) & 1, i = h & 15;
+  const int w = k / qs, kk = k - w * qs;
+  const int64_t blk = ((((int64_t)b * head_groups + hg) * (d_q / qs) + w) * (qs / 32) + (kk >> 5)) * 2 + hh;
+  return (blk * 64 + ((kk >> 3) & 3) * 16 + i) * 8 + (kk & 7);
+}
+
 // Column n of the append's output Y = x [W_ke | W_dkv | W_dkv2]: which weight matrix holds it, at
 // which column, with which row stride.  NE = 2 r n_h elite columns, then d_ck columns of W_dkv,
 // then d_c - d_ck columns of W_dkv2 (separated latents; d_ck == d_c for the joint latent).

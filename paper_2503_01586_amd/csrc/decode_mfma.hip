@@ -28,6 +28,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
@@ -38,7 +39,7 @@ struct AttnMfmaParams {
   const bf16_t* ke_plane;
   const bf16_t* c_plane;
   const float* qe;        // [B, n_h, 2r]   rotated, scaled elite query
-  const bf16_t* qt;       // [B, n_h, d_c]  absorbed, scaled latent query
+  const bf16_t* qt;       // absorbed, scaled latent query q~ [B, n_h, d_q] in operand order (qt_packed_index)
   const int32_t* seq_len;
   float* part_m;          // [B, n_splits, HG*32]        split maxima (log2 domain)
   float* part_l;          // [B, n_splits, HG*32]        split sums
@@ -47,6 +48,7 @@ struct AttnMfmaParams {
   int batch, pair_map;    // pair_map: 1-D grid, the two head groups of an item share an XCD
   int q_per_seq;          // query rows per sequence (several queries share the cache rows of a sequence)
   int d_q, d_u;           // widths of the absorbed query and of the latent accumulators (d_c when joint)
+  int q_slice;            // column slice per wave (DC_W), as the query preparation laid qt out
   int64_t max_seq_len, batch_stride_rows, plane_rows;
   // Fused decode step: the newest token of every sequence (position seq_len - 1) is not read from the
   // planes.  Its cache row is still a set of partial sums (the append's contraction splits); the
@@ -61,6 +63,8 @@ struct AttnMfmaParams {
   int fr_ks;
   bf16_t* fr_ke_out;         // the planes, writable
   bf16_t* fr_c_out;
+  // arrival counters of the merge kernels that follow in the same call ([batch, n_h] ints): cleared here
+  int* chunk_counters;
 };
 
 // LDS layout of one wave's tile slice (16 tokens x DC_W latent columns, bf16): blocks of
@@ -198,9 +202,8 @@ __device__ __forceinline__ void new_token_role(const AttnMfmaParams& p, int hg, 
     const int head = hg * 32 + hh;
     if (head >= p.n_h) continue;                           // uniform over the wave
     float acc = 0.f;
-    const bf16_t* qrow = p.qt + ((int64_t)b * p.n_h + head) * p.d_q;
     for (int k = lane * 8; k < p.d_q; k += 512) {
-      const uint4 qv = *reinterpret_cast<const uint4*>(qrow + k);
+      const uint4 qv = *reinterpret_cast<const uint4*>(p.qt + qt_packed_index(b, head, k, p.head_groups, p.d_q, p.q_slice));
       const uint32_t qq[4] = {qv.x, qv.y, qv.z, qv.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -248,10 +251,18 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
-  const int nwk = SEP ? p.d_q / DC_W : NW;               // waves that compute scores
-  const bool do_s = !SEP || wave < nwk;                  // this wave's slice enters the scores
-  const bool do_v = !SEP || wave >= nwk;                 // this wave's slice is accumulated as values
-  const int vwave = SEP ? wave - nwk : wave;             // position of the slice among the value slices
+  // Which DC_W-column slice of the latent row this wave works on: rotated from work-group to
+  // work-group.  The work-groups of an XCD run in step and all fetch the same absorbed query from its
+  // L2; when they all ask for the same lines at the same moment the L2 serves them one after the
+  // other (a compute unit then gets a fifth of the rate of independent streams).  Rotated, eight
+  // groups of them ask for eight different parts of the query at any moment.  Partial scores are
+  // exchanged by slice index and summed in slice order, so the result does not depend on the rotation.
+  const int lin_wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const int cw = (wave + (lin_wg >> 3)) & (NW - 1);
+  const int nwk = SEP ? p.d_q / DC_W : NW;               // slices that enter the scores
+  const bool do_s = !SEP || cw < nwk;                    // this wave's slice enters the scores
+  const bool do_v = !SEP || cw >= nwk;                   // this wave's slice is accumulated as values
+  const int vwave = SEP ? cw - nwk : cw;                 // position of the slice among the value slices
   int split = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
   if (p.pair_map) {
     // Two head groups read the same latent rows.  Work-groups go to the eight XCDs round-robin by
@@ -266,17 +277,60 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
     split = item % per_row;
     b = item / per_row;
   }
+  if (split == 0 && hg == 0)
+    for (int i = tid; i < p.n_h; i += NW * 64) p.chunk_counters[(int64_t)b * p.n_h + i] = 0;
   if (split >= p.n_splits) {                             // only in a fused decode step
     new_token_role<NW * 64, TWO_R>(p, hg, b, smem);
     return;
   }
+  // ---- the query, requested before anything else
+  // This wave's slice of the absorbed query as the B operand of the 16x16x32 score MFMAs (lane l holds
+  // head hh*16 + l%16, latent columns 32*ks + 8*(l/16) .. +8) and the lane's head's rotated elite
+  // query.  A compute unit keeps only so many memory requests in flight and serves them in the order
+  // they were issued, so the 128 KB of query (quick: they come from the L2) must not queue up behind
+  // tile requests (slow: HBM) of waves that happen to run ahead: every wave asks for its query
+  // first, and no wave asks for a tile before all have (the barrier below).  The loads are issued
+  // from assembly, like the tile loads: a load the compiler knows of makes it wait, before the
+  // first use of the value, with a count that ignores the tile loads issued behind it, i.e. for all
+  // of them.  The registers are first read in compute(), after the loop's wait for the first tile,
+  // which these loads precede.  Heads beyond n_h (second head group of 40 heads) read the last
+  // head's query: their results are never stored.
+  const int head = hg * 32 + n;
+  const bool head_ok = head < p.n_h;
+  const int head_c = head_ok ? head : p.n_h - 1;
+  const int i16 = lane & 15, q16 = lane >> 4;
+  u32x4 Qb[KS][2];
+  float qe[TWO_R > 0 ? TWO_R : 1];
+  int32_t len_raw;                                       // seq_len[b] through the scalar cache: not behind the query
+  asm volatile("s_load_dword %0, %1, 0x0" : "=s"(len_raw) : "s"(p.seq_len + b) : "memory");
+  if (do_s) {
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int hq = min(hg * 32 + hh * 16 + i16, p.n_h - 1);
+      const bf16_t* qrow = p.qt + qt_packed_index(b, hq, cw * DC_W + 8 * q16, p.head_groups, p.d_q, DC_W);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)                        // one contiguous KiB per instruction
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(Qb[ks][hh]) : "v"(qrow + ks * 1024) : "memory");
+    }
+  }
+  if (TWO_R > 0) {
+    const float* qer = p.qe + ((int64_t)b * p.n_h + head_c) * TWO_R;
+    f32x4 qv[TWO_R > 0 ? TWO_R / 4 : 1];                  // (four floats in consecutive registers)
+#pragma unroll
+    for (int j = 0; j < TWO_R / 4; ++j) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qv[j]) : "v"(qer + 4 * j) : "memory");
+#pragma unroll
+    for (int j = 0; j < TWO_R; ++j) qe[j] = qv[j / 4][j % 4];
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(len_raw) : : "memory");
+  __builtin_amdgcn_s_barrier();                          // every wave's query requests are queued
+
   char* ctile0 = smem + wave * L::WTILE;                 // buffer 0; buffer 1 is TILE_BYTES further
   char* ketile0 = smem + L::KE_OFF + wave * L::KE_W;     // buffer 0; buffer 1 (if any) is KE_BYTES further
   float* x1 = reinterpret_cast<float*>(smem + L::X1_OFF);
   float* x2 = reinterpret_cast<float*>(smem + L::X2_OFF);
 
   const int64_t row0 = (int64_t)(b / p.q_per_seq) * p.batch_stride_rows;
-  int64_t len = p.seq_len[b];
+  int64_t len = len_raw;
   len = min(len, p.max_seq_len);
   len = min(len, p.plane_rows - row0);
   len = max(len, (int64_t)0);
@@ -299,36 +353,6 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
     return;
   }
 
-  const int head = hg * 32 + n;
-  const bool head_ok = head < p.n_h;
-  const int head_c = head_ok ? head : p.n_h - 1;
-
-  // this wave's slice of the absorbed query as the B operand of the 16x16x32 score MFMAs:
-  // lane l holds head hh*16 + l%16, latent columns 32*ks + 8*(l/16) .. +8
-  const int i16 = lane & 15, q16 = lane >> 4;
-  bf16x8 Qb[KS][2];
-  float qe[TWO_R > 0 ? TWO_R : 1];
-  auto load_query = [&]() {
-#pragma unroll
-  for (int hh = 0; hh < 2; ++hh) {
-    const int hq = hg * 32 + hh * 16 + i16;
-    const bool ok = hq < p.n_h;
-    const bf16_t* qrow = p.qt + ((int64_t)b * p.n_h + (ok ? hq : p.n_h - 1)) * p.d_q + (do_s ? wave : 0) * DC_W + 8 * q16;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      s16x8 v = (s16x8)(0);
-      if (do_s) v = *reinterpret_cast<const s16x8*>(qrow + 32 * ks);
-      if (!ok) v = (s16x8)(0);
-      Qb[ks][hh] = __builtin_bit_cast(bf16x8, v);
-    }
-  }
-  if (TWO_R > 0) {
-    const float* qer = p.qe + ((int64_t)b * p.n_h + head_c) * TWO_R;
-#pragma unroll
-    for (int j = 0; j < TWO_R; ++j) qe[j] = head_ok ? qer[j] : 0.f;
-  }
-  };
-
   f32x16 uacc[CT];
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) uacc[ct] = (f32x16)(0.f);
@@ -339,9 +363,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   // loader: lane l fills slot (row l/8, position l%8) of every block; it fetches the logical
   // chunk that the swizzle puts there
   const int ld_row = lane >> 3;
-  const char* cbase = reinterpret_cast<const char*>(p.c_plane) + (int64_t)wave * DC_W * 2 +
+  const char* cbase = reinterpret_cast<const char*>(p.c_plane) + (int64_t)cw * DC_W * 2 +
                       (((lane & 7) ^ tile_swz(ld_row)) << 4);
-  const char* hbase = reinterpret_cast<const char*>(p.c_plane) + ((int64_t)wave * DC_W + NCB * 64) * 2 +
+  const char* hbase = reinterpret_cast<const char*>(p.c_plane) + ((int64_t)cw * DC_W + NCB * 64) * 2 +
                       (((lane & 3) ^ half_swz(lane >> 2)) << 4);
   // elite-key loader: slot c = i*64 + lane of the wave's slice is (token c / KE_CPT, chunk c % KE_CPT)
   const char* kbase = reinterpret_cast<const char*>(p.ke_plane);
@@ -421,13 +445,13 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
       if (KS > 8 && ks % 4 == 0) asm volatile("" ::: "memory");   // wide slices: bound the operand look-ahead
       const int aoff = (L::HALF && ks == 2 * NCB) ? ah_off : (ks >> 1) * 1024 + ((ks & 1) ? a_c1 : a_c0);
       const bf16x8 a = *reinterpret_cast<const bf16x8*>(ctile + aoff);
-      sd[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Qb[ks][0], sd[0], 0, 0, 0);
-      sd[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Qb[ks][1], sd[1], 0, 0, 0);
+      sd[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, Qb[ks][0]), sd[0], 0, 0, 0);
+      sd[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, Qb[ks][1]), sd[1], 0, 0, 0);
     }
     }
-    // ---- stage 1: publish them as x1[wave][token][head]; lane holds tokens 4*q16 + v, head hh*16 + i16
+    // ---- stage 1: publish them as x1[slice][token][head]; lane holds tokens 4*q16 + v, head hh*16 + i16
     if (do_s) {
-      float* xw = x1 + (wave * kTile + 4 * q16) * L::X1_ROW + i16;
+      float* xw = x1 + (cw * kTile + 4 * q16) * L::X1_ROW + i16;
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
@@ -547,29 +571,34 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
     const int j = i ^ swp;
     return t0 + (int64_t)(j < n_my ? j : i) * t_step;
   };
-  const int64_t first = tile_at(0);
-  load_query();   // requested ahead of the tiles: behind a tile's worth of queued traffic it would return late
+  const int64_t first = tile_at(0), second = tile_at(1);
   issue_c(first, ctile0, NtEven{});
   issue_ke(first, ketile0, NtEven{});
+  if (second < t_end) {
+    // All work-groups start together.  Requests for the second tile go out once half of the first has
+    // arrived: the first tile is then complete (and being computed) after one tile's worth of bus time
+    // instead of two, while the bus still never runs dry.
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L::NLOAD / 2 + (TWO_R > 0 ? L::NKE : 0)) : "memory");
+    issue(second, ctile1, ketile1, NtOdd{});
+  }
   for (int i = 0; i < n_my; i += 2) {
-    const int64_t ta = tile_at(i), tb = tile_at(i + 1), tc = tile_at(i + 2);
-    if (tb < t_end) {
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // buffer 1 was last read one tile ago
-      issue(tb, ctile1, ketile1, NtOdd{});
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IN_FLIGHT) : "memory");
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
+    const int64_t ta = tile_at(i), tb = tile_at(i + 1), tc = tile_at(i + 2), td = tile_at(i + 3);
+    if (tb < t_end) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IN_FLIGHT) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     compute(ta, ctile0, ketile0, tb, NtOdd{});
     if (tb >= t_end) break;
     if (tc < t_end) {
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // buffer 0 was last read one tile ago
       issue(tc, ctile0, ketile0, NtEven{});
       asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IN_FLIGHT) : "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     compute(tb, ctile1, ketile1, tc, NtEven{});
+    if (td < t_end) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      issue(td, ctile1, ketile1, NtOdd{});
+    }
   }
 
   // ---- write this split's partial (m, l, U)
@@ -644,6 +673,7 @@ static void shape_of(int d_c, int* nw, int* dcw) {
 #undef X
 }
 static int slice_width(int d_c) { int nw, w; shape_of(d_c, &nw, &w); return w; }
+int decode_mfma_slice_width(int d_c) { return slice_width(d_c); }
 
 // work-groups of the attention kernel that fit one compute unit (see the launch bounds of the kernel)
 int decode_mfma_groups_per_cu(const elitekv_dims& d) {
@@ -678,10 +708,11 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.head_groups = p.head_groups; prm.max_seq_len = a.max_seq_len;
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
   prm.batch = (int)a.B; prm.pair_map = p.head_groups == 2 ? 1 : 0;
-  prm.d_q = p.d_q; prm.d_u = p.d_u; prm.q_per_seq = a.q_per_seq;
+  prm.d_q = p.d_q; prm.d_u = p.d_u; prm.q_per_seq = a.q_per_seq; prm.q_slice = slice_width(d.d_c);
   prm.n_part = p.n_part; prm.fresh = p.fresh;
   prm.fr_partial = nullptr; prm.fr_sincos = nullptr; prm.fr_slot = nullptr; prm.fr_ks = 0; prm.fr_stride = 0;
   prm.fr_ke_out = nullptr; prm.fr_c_out = nullptr;
+  prm.chunk_counters = (int*)(a.ws + p.off_cnt);
   if (p.fresh) {
     prm.fr_partial = (const float*)(a.ws + p.off_apart); prm.fr_sincos = (const float2*)(a.ws + p.off_sincos);
     prm.fr_slot = a.fr_slot; prm.fr_ks = p.fr_ks; prm.fr_stride = p.fr_stride;

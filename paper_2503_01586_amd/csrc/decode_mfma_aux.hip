@@ -4,8 +4,9 @@
 //   merge_up     : exact log-sum-exp merge of the sequence splits, normalisation, and the W_uv
 //                  up-projection of a chunk of latent columns (Section 3.2, B^v_J), one batch row
 //                  (the version for a batch is merge_mfma.hip)
-//   out_reduce   : sum of the up-projection partials over the latent chunks, cast to bf16
+//                  the last work-group of a head to finish adds the chunks' partials (chunk_sum.hpp)
 #include "common.hpp"
+#include "chunk_sum.hpp"
 #include "launch.hpp"
 #include "qprep_rows.hpp"
 #include "qprep_mfma.hpp"
@@ -23,6 +24,7 @@ QprepRowsParams make_qprep_rows_params(const DecodeArgs& a, const DecodePlan& p,
   QprepRowsParams P;
   P.q = (const bf16_t*)a.q; P.q_pos = a.q_pos; P.W_uk = (const bf16_t*)a.W_uk; P.elite_idx = a.elite_idx;
   P.qe = qe; P.qt = qt; P.sincos = p.fresh ? (float2*)(a.ws + p.off_sincos) : nullptr; P.B = (int)a.B; P.n_h = d.n_heads; P.d_h = d.head_dim; P.r = d.r; P.d_c = p.d_q;
+  P.q_slice = decode_mfma_slice_width(d.d_c); P.head_groups = p.head_groups;
   P.scale_log2e = kLog2e / sqrtf((float)d.head_dim);
   return P;
 }
@@ -92,7 +94,9 @@ hipError_t launch_qprep_rows(const DecodeArgs& a, const DecodePlan& p, float* qe
 //   * exact log-sum-exp merge of the sequence splits for this head (weights from m, l),
 //   * the merged, normalised latent of the chunk's columns,
 //   * its contribution to the up-projection  o[h, :] = ubar[h, :] W_uv[:, h, :]   (B^v_J),
-//   * written as a partial per chunk; out_reduce adds the chunk partials in a fixed order.
+//   * written as a partial per chunk; the last work-group of the head to arrive adds the chunk
+//     partials in chunk order and writes out[b, head, :] (chunk_sum.hpp); fuse_out == 0 leaves the
+//     partials for a caller that consumes them itself.
 // Partials: part_m / part_l [P, NHP], part_u [P, NHP, d_c] bf16 with P = b * n_splits + s.
 // All global loads that do not depend on earlier results (the W_uv rows, the first batch of
 // split accumulators) are requested at the top so that their latency overlaps the merge weights.
@@ -100,8 +104,8 @@ hipError_t launch_qprep_rows(const DecodeArgs& a, const DecodePlan& p, float* qe
 template <int CW, int DH>
 __global__ __launch_bounds__(256) void merge_up_kernel(
     const float* __restrict__ part_m, const float* __restrict__ part_l,
-    const bf16_t* __restrict__ part_u, const bf16_t* __restrict__ W_uv, float* __restrict__ opart,
-    int n_h, int nhp, int d_c, int n_splits) {
+    const bf16_t* __restrict__ part_u, const bf16_t* __restrict__ W_uv, float* opart,
+    bf16_t* __restrict__ out, int* chunk_counters, int fuse_out, int n_h, int nhp, int d_c, int n_splits) {
   constexpr int LPR = CW / 8;              // lanes that cover one split's row chunk (16 bytes each)
   constexpr int NG = 256 / LPR;            // split groups working in parallel
   constexpr int LPW = DH / 8;              // lanes that cover one W_uv row
@@ -231,37 +235,16 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   }
   __syncthreads();
   float* op = opart + (((int64_t)b * n_h + head) * n_chunks + chunk) * DH;
-  if (tid < DH) op[tid] = (wred[tid] + wred[DH + tid]) + (wred[2 * DH + tid] + wred[3 * DH + tid]);
-
-}
-
-// out[b, h, j] = sum over the latent chunks of the up-projection partials, in a fixed order.
-// (A separate launch rather than a last-arrival epilogue: device-scope fences inside merge_up
-// write back and invalidate the whole L2 of the XCD for every work-group.)
-__global__ __launch_bounds__(256) void out_reduce_kernel(const float* __restrict__ opart,
-                                                         bf16_t* __restrict__ out, int d_h,
-                                                         int n_chunks, int64_t total) {
-  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [B * n_h, d_h]
-  if (e >= total) return;
-  const int64_t bh = e / d_h;
-  const int j = (int)(e % d_h);
-  const float* p = opart + bh * n_chunks * d_h + j;
-  float a = 0.f;
-#pragma unroll 8
-  for (int c = 0; c < n_chunks; ++c) a += p[(int64_t)c * d_h];
-  st(out, e, a);
+  if (tid < DH)
+    store_partial_device_scope(op + tid, (wred[tid] + wred[DH + tid]) + (wred[2 * DH + tid] + wred[3 * DH + tid]));
+  if (fuse_out)
+    sum_chunks_by_last_arrival<DH>(opart, out, chunk_counters + (int64_t)b * n_h + head, n_h, n_chunks, head, b, 1,
+                                   reinterpret_cast<int*>(red));
 }
 
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
-  if (p.merge_batch) {
-    hipError_t e = launch_merge_mfma(a, p, stream);
-    if (e != hipSuccess || a.no_out_reduce) return e;
-    const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
-    out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
-        (const float*)(a.ws + p.off_opart), (bf16_t*)a.out, d.head_dim, p.d_u / 128, total);
-    return hipGetLastError();
-  }
+  if (p.merge_batch) return launch_merge_mfma(a, p, stream);
   const float* pm = (const float*)(a.ws + p.off_m);
   const float* pl = (const float*)(a.ws + p.off_l);
   const bf16_t* pu = (const bf16_t*)(a.ws + p.off_u);
@@ -272,17 +255,14 @@ hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t
 #define EKV_MU(CW, DH)                                                                              \
   do {                                                                                              \
     const size_t sm = sizeof(float) * ((size_t)p.n_part + 256 + (size_t)(256 / (CW / 8)) * CW + CW); \
-    merge_up_kernel<CW, DH><<<grid, 256, sm, stream>>>(pm, pl, pu, (const bf16_t*)a.W_uv, opart, d.n_heads, \
-                                                       nhp, p.d_u, p.n_part);                            \
+    merge_up_kernel<CW, DH><<<grid, 256, sm, stream>>>(pm, pl, pu, (const bf16_t*)a.W_uv, opart,    \
+                                                       (bf16_t*)a.out, (int*)(a.ws + p.off_cnt),    \
+                                                       a.no_out_reduce ? 0 : 1, d.n_heads, nhp,     \
+                                                       p.d_u, p.n_part);                            \
   } while (0)
   if (cw == 192) { if (d.head_dim == 128) EKV_MU(192, 128); else EKV_MU(192, 64); }
   else { if (d.head_dim == 128) EKV_MU(64, 128); else EKV_MU(64, 64); }
 #undef EKV_MU
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || a.no_out_reduce) return e;
-  const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
-  out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(opart, (bf16_t*)a.out, d.head_dim,
-                                                                        p.d_u / cw, total);
   return hipGetLastError();
 }
 

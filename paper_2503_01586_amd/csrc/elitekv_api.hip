@@ -108,7 +108,7 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     chunk = (chunk + 31) / 32 * 32;
     p->chunk = (int32_t)chunk;
     const size_t np = Bz * (size_t)p->n_part * p->head_groups;
-    p->off_qt = off; off = align_up(off + Bz * nh * dq * 2, 256);
+    p->off_qt = off; off = align_up(off + Bz * (size_t)p->head_groups * 32 * dq * 2, 256);   // head groups padded to 32
     p->off_m = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_l = off;  off = align_up(off + np * 32 * sizeof(float), 256);
     p->off_u = off;  off = align_up(off + np * 32 * du * 2, 256);
@@ -116,6 +116,8 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     p->up_cw = p->merge_batch ? 128 : (p->d_u % 192 == 0) ? 192 : 64;
     p->off_opart = off;
     off = align_up(off + Bz * nh * (size_t)(p->d_u / p->up_cw) * d->head_dim * sizeof(float), 256);
+    p->off_cnt = off;
+    off = align_up(off + Bz * nh * sizeof(int32_t), 256);
     if (p->fresh) {
       p->off_apart = off;
       off = align_up(off + (size_t)p->fr_ks * Bz * (size_t)p->fr_stride * sizeof(float), 256);

@@ -46,6 +46,7 @@ struct DecodePlan {
   size_t off_l;         // split sums                       fp32 [B, n_splits, n_h_pad]
   size_t off_u;         // split latent accumulators        fp32 [B, n_splits, ...]
   size_t off_opart;     // up-projection partials           fp32
+  size_t off_cnt;       // MFMA path: arrival counters of the merge kernels' chunk groups   int32 [B, n_h]
   // fused decode step (fresh = 1): the newest token of every sequence reaches the attention as one more
   // split, built from the append's contraction-split sums inside the attention kernel
   int32_t fresh;
@@ -134,6 +135,7 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_decode_generic(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 bool decode_mfma_supported(const elitekv_dims& d, int d_ck);
 int decode_mfma_groups_per_cu(const elitekv_dims& d);
+int decode_mfma_slice_width(int d_c);     // latent columns per wave of the attention kernel for rows of d_c columns; 0 = none
 struct bf16_t;
 hipError_t launch_qprep_rows(const DecodeArgs& a, const DecodePlan& p, float* qe, bf16_t* qt,
                              hipStream_t stream);

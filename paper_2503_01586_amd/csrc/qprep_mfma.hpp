@@ -104,15 +104,15 @@ __device__ __forceinline__ void qprep_mfma_body(const QprepRowsParams& P, const 
       // D[k, b]: this lane holds batch row bt + n32 and latent columns k0 + 8*g4 + 4*hi + {0..3}
       const int b = b0 + bt + n32;
       if (b < B) {
-        bf16_t* orow = qt + ((int64_t)b * n_h + h) * d_c + k0 + 4 * hi;
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
+          bf16_t* orow = qt + qt_packed_index(b, h, k0 + 4 * hi + 8 * g4, P.head_groups, d_c, P.q_slice);   // four columns of one lane slot
           uint2 pk;
           pk.x = (uint32_t)f32_to_bf16_bits(acc[4 * g4] * scale_log2e) |
                  ((uint32_t)f32_to_bf16_bits(acc[4 * g4 + 1] * scale_log2e) << 16);
           pk.y = (uint32_t)f32_to_bf16_bits(acc[4 * g4 + 2] * scale_log2e) |
                  ((uint32_t)f32_to_bf16_bits(acc[4 * g4 + 3] * scale_log2e) << 16);
-          *reinterpret_cast<uint2*>(orow + 8 * g4) = pk;
+          *reinterpret_cast<uint2*>(orow) = pk;
         }
       }
     }

@@ -29,6 +29,7 @@ struct QprepRowsParams {
   bf16_t* qt;
   float2* sincos;         // optional [B][n_h * r]: (sin, cos) of every rotated chunk, for the key of the same position
   int B, n_h, d_h, r, d_c;
+  int q_slice, head_groups;   // layout of qt (qt_packed_index): the attention kernel's column slice per wave, groups of 32 heads
   float scale_log2e;
 };
 
@@ -184,7 +185,7 @@ __device__ __forceinline__ void qprep_rows_body(const QprepRowsParams& P, const 
   }
 #pragma unroll
   for (int bt = 0; bt < BT; ++bt)
-    if (bt < bt_n) st(qt, ((int64_t)(b0 + bt) * n_h + h) * d_c + k, acc[bt] * scale_log2e);
+    if (bt < bt_n) st(qt, qt_packed_index(b0 + bt, h, k, P.head_groups, d_c, P.q_slice), acc[bt] * scale_log2e);
 }
 
 }  // namespace ekv
