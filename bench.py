@@ -24,12 +24,27 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled
-# by the readings of a plain copy of known size (profiles/attn_mfma_<workload>.md); workloads that
-# have not been counted report null.
-TRAFFIC_BYTES = {"7b_25_b1_s32768": 160.5e6, "7b_25_b8_s4096": 166.1e6, "13b_25_b16_s8192": 711.4e6,
-                 "7b_12_b64_s2048": 319.6e6, "7b_25_slrd_b1_s32768": 150.6e6, "7b_25_slrd_b8_s4096": 150.4e6}
+FP32_VALU_PEAK_TFLOPS = 157.3       # 256 compute units x 4 SIMDs x 64 lanes x 2 flops at 2.4 GHz
 METRIC = "decode attn HBM GB/s (% of peak) + tokens/s, 7B shape 25% cache, 32K ctx"
+
+
+def counted_traffic(workload):
+    """HBM bytes per launch of the dominant kernel as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each
+    scaled by what the same counter reads for a plain copy of known size): read from the committed summary of
+    that workload, profiles/attn_mfma_<workload>.md, which carries one line
+        traffic_bytes_per_launch: <integer>
+    Returns (bytes or None, "file name @ first 12 hex digits of its sha1" or None): no summary, no number."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", "attn_mfma_%s.md" % workload)
+    try:
+        text = open(path, "rb").read()
+    except OSError:
+        return None, None
+    m = re.search(rb"^traffic_bytes_per_launch:\s*(\d+)\s*$", text, re.M)
+    if not m:
+        return None, None
+    return int(m.group(1)), "profiles/%s @ %s" % (os.path.basename(path), hashlib.sha1(text).hexdigest()[:12])
 
 
 class HipEvents:
@@ -209,6 +224,26 @@ def main():
     ev.record(e1, stream)
     torch.cuda.synchronize()
     ms_two_calls = ev.elapsed_ms(e0, e1) / args.steps
+    # elitekv_decode_attn alone (query preparation, split attention, merge + up-projection), the call the
+    # north star prices, over the same rotating plane and weight copies
+    def attn_call(i):
+        ke_p, c_p = planes[i % n_copies]
+        _, _, _, Wuk, Wuv = wsets[i % n_wcopies]
+        if d_ck:
+            ekv.elitekv_slrd_decode_attn(dims, d_ck, q_d, pos_d, seq_d, S, S, Wuk, Wuv, idx_d, ke_p, c_p, out_d, ws_d,
+                                         n_splits=args.splits, stream=stream)
+        else:
+            ekv.elitekv_decode_attn(dims, q_d, pos_d, seq_d, S, S, Wuk, Wuv, idx_d, ke_p, c_p, out_d, ws_d,
+                                    n_splits=args.splits, stream=stream)
+    for i in range(args.warmup):
+        attn_call(i)
+    torch.cuda.synchronize()
+    ev.record(e0, stream)
+    for i in range(args.steps):
+        attn_call(i)
+    ev.record(e1, stream)
+    torch.cuda.synchronize()
+    ms_attn_call = ev.elapsed_ms(e0, e1) / args.steps
 
     # dominant kernel (the split attention kernel): K launches of that stage alone, back to back on
     # the stream over the same rotating plane copies, between ONE pair of HIP events (an event pair
@@ -239,6 +274,7 @@ def main():
 
     value_gbs = cache_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = cache_bytes / (k_avg_ms * 1e-3) / 1e9
+    traffic, traffic_src = counted_traffic(cfg.name)
     result = {
         "metric": METRIC, "value": round(value_gbs, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
@@ -254,10 +290,12 @@ def main():
         "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
         "ms_per_step_median": round(reps[len(reps) // 2], 5), "ms_per_step_min": round(reps[0], 5),
         "ms_per_step_two_calls": round(ms_two_calls, 5),
+        "ms_decode_attn_call": round(ms_attn_call, 5),
+        "decode_attn_call_GBs": round(cache_bytes / (ms_attn_call * 1e-3) / 1e9, 2),
         "ms_per_step_one_weight_set": round(ms_same_weights, 5),
         "roofline": {"bound": "hbm", "kernel": "split attention kernel of elitekv_decode_attn",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES.get(cfg.name),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_src,
                      "algorithmic_bytes_per_launch": cache_bytes, "avg_launch_ms": round(k_avg_ms, 5),
                      "median_launch_ms": round(k_runs[len(k_runs) // 2], 5), "min_launch_ms": round(k_runs[0], 5),
                      "launches_timed": 5 * args.steps},
@@ -479,7 +517,13 @@ def ropelite_search(ekv, ev, cfg, dev, stream, T=512, iters=3):
     torch.cuda.synchronize()
     ms = ev.elapsed_ms(e0, e1) / iters
     evals = T * (T + 1) / 2 * n_h * r * (d_h // 2)      # (causal pair, chunk) evaluations over all rounds
-    return {"tokens": T, "rounds": r, "ms_per_layer": round(ms, 4), "G_pair_chunk_evals_per_s": round(evals / ms / 1e6, 1)}
+    # Algorithm 1 per round, causal pair and chunk: the rotated and the plain 2-D dot product, their scaled
+    # difference (8 flops), its share of the residual (1), and |residual - difference| added to the chunk's
+    # distance (3): 12 fp32 vector flops, no contraction with a shared operand -- bounded by the vector ALUs
+    tf = 12.0 * evals / (ms * 1e-3) / 1e12
+    return {"tokens": T, "rounds": r, "ms_per_layer": round(ms, 4), "G_pair_chunk_evals_per_s": round(evals / ms / 1e6, 1),
+            "bound": "alu", "flops_per_pair_chunk_round": 12, "TFLOPs": round(tf, 2), "peak_TFLOPs": FP32_VALU_PEAK_TFLOPS,
+            "frac": round(tf / FP32_VALU_PEAK_TFLOPS, 4)}
 
 
 def prefill_attn(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream, T=2048, iters=20):

@@ -630,7 +630,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
     const int idx = i * 64 + lane;
     const int row = idx / CPRW, ch = idx % CPRW;
     const uint4 v = *reinterpret_cast<const uint4*>(tt + row * TSTR + ch * 16);
-    if (do_v && hg * 32 + row < p.n_h) *reinterpret_cast<uint4*>(ubase + (int64_t)row * p.d_u * 2 + ch * 16) = v;
+    // non-temporal: the 25 MB of partials of a launch are on their way to memory while other work-groups still
+    // stream, instead of leaving the eight L2s in one burst when the kernel ends
+    if (do_v && hg * 32 + row < p.n_h)
+      __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(ubase + (int64_t)row * p.d_u * 2 + ch * 16));
   }
 }
 

@@ -63,3 +63,22 @@ def gpu_decode(dims, q, q_pos, seq_len, max_seq, stride, W_uk, W_uv, idx, ke, c,
                             n_splits=n_splits)
     torch.cuda.synchronize()
     return out
+
+
+def parity_report(name, got, ref, tol, per_row_axes=None):
+    """The parity gate of one output tensor plus what the benchmark definition asks to be logged next to it:
+    returns max|got - ref| / max|ref| over the tensor (the gated metric, oracle.max_abs_rel) and prints
+    the largest ELEMENT-WISE relative error among the elements with |ref| > 1e-3 max|ref|, and the worst
+    max-abs-rel of any single row (leading axes = rows, e.g. one (batch row, head) output vector each), so
+    that a row of small magnitude cannot hide behind a large one in the same tensor."""
+    from oracle import elitekv_oracle as orc
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    err = orc.max_abs_rel(got, ref)
+    big = np.abs(ref) > 1e-3 * np.max(np.abs(ref)) if ref.size else np.zeros(ref.shape, dtype=bool)
+    elem = float(np.max(np.abs(got - ref)[big] / np.abs(ref)[big])) if big.any() else 0.0
+    rows_g, rows_r = got.reshape(-1, got.shape[-1]), ref.reshape(-1, ref.shape[-1])
+    row_err = max((orc.max_abs_rel(g, r) for g, r in zip(rows_g, rows_r)), default=0.0)
+    print("parity %-44s max-abs-rel %.3e (bound %.0e)  worst row %.3e  max element-wise rel (|ref| > 1e-3 max) %.3e"
+          % (name, err, tol, row_err, elem), flush=True)
+    return err, row_err
