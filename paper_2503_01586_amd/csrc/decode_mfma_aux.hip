@@ -242,9 +242,34 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
                                    reinterpret_cast<int*>(red));
 }
 
+// out[b, h, j] = sum over the latent chunks of the up-projection partials, in chunk order: the launch that
+// follows the batched merge.  (There a last-arrival sum inside the merge, as the single-row merge has it, was
+// measured 1 to 3 us slower than this launch: one work-group then adds up to 32 rows x d_h x chunks values behind
+// a chain of store acknowledgement, counter and device-scope loads.)
+__global__ __launch_bounds__(256) void out_reduce_kernel(const float* __restrict__ opart,
+                                                         bf16_t* __restrict__ out, int d_h,
+                                                         int n_chunks, int64_t total) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [B * n_h, d_h]
+  if (e >= total) return;
+  const int64_t bh = e / d_h;
+  const int j = (int)(e % d_h);
+  const float* p = opart + bh * n_chunks * d_h + j;
+  float a = 0.f;
+#pragma unroll 8
+  for (int c = 0; c < n_chunks; ++c) a += p[(int64_t)c * d_h];
+  st(out, e, a);
+}
+
 hipError_t launch_merge_up(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
-  if (p.merge_batch) return launch_merge_mfma(a, p, stream);
+  if (p.merge_batch) {
+    hipError_t e = launch_merge_mfma(a, p, stream);
+    if (e != hipSuccess || a.no_out_reduce) return e;
+    const int64_t total = (int64_t)a.B * d.n_heads * d.head_dim;
+    out_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(
+        (const float*)(a.ws + p.off_opart), (bf16_t*)a.out, d.head_dim, p.d_u / 128, total);
+    return hipGetLastError();
+  }
   const float* pm = (const float*)(a.ws + p.off_m);
   const float* pl = (const float*)(a.ws + p.off_l);
   const bf16_t* pu = (const bf16_t*)(a.ws + p.off_u);

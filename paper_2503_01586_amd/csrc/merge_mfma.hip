@@ -11,10 +11,8 @@
 //      tile of the head's d_h outputs per wave, K = the chunk's 128 columns in eight steps; ubar goes
 //      in as bf16 high part + bf16 remainder (two MFMAs per step: 16 mantissa bits), W_uv is read
 //      transposed from LDS (ds_read_b64_tr_b16);
-//   5. the chunk's partial outputs go to opart; the last work-group of a (row tile, head) to arrive
-//      adds the chunks in chunk order and writes the output rows (chunk_sum.hpp).
+//   5. the chunk's partial outputs go to opart; out_reduce adds the chunks in a fixed order.
 #include "common.hpp"
-#include "chunk_sum.hpp"
 #include "launch.hpp"
 
 namespace ekv {
@@ -47,8 +45,8 @@ struct MergeMfmaLayout {
 template <int DH>
 __global__ __launch_bounds__(256) void merge_up_mfma_kernel(
     const float* __restrict__ part_m, const float* __restrict__ part_l, const bf16_t* __restrict__ part_u,
-    const bf16_t* __restrict__ W_uv, float* opart, bf16_t* __restrict__ out, int* chunk_counters, int fuse_out,
-    int B, int n_h, int nhp, int d_u, int n_splits, int rows_per_wg) {
+    const bf16_t* __restrict__ W_uv, float* __restrict__ opart, int B, int n_h, int nhp, int d_u, int n_splits,
+    int rows_per_wg) {
   using L = MergeMfmaLayout<DH>;
   constexpr int WROW = L::WROW, UROW = L::UROW;
   extern __shared__ __attribute__((aligned(16))) char msm2[];
@@ -246,14 +244,9 @@ __global__ __launch_bounds__(256) void merge_up_mfma_kernel(
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int rl = 8 * g4 + 4 * hi + v;
-        if (rl < rows)
-          store_partial_device_scope(opart + (((int64_t)(b0 + rl) * n_h + head) * n_chunks + chunk) * DH + j,
-                                     acc[4 * g4 + v]);
+        if (rl < rows) opart[(((int64_t)(b0 + rl) * n_h + head) * n_chunks + chunk) * DH + j] = acc[4 * g4 + v];
       }
   }
-  if (fuse_out)
-    sum_chunks_by_last_arrival<DH>(opart, out, chunk_counters + (int64_t)blockIdx.z * n_h + head, n_h, n_chunks, head,
-                                   b0, rows, reinterpret_cast<int*>(invl));
 }
 
 bool merge_mfma_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits) {
@@ -276,8 +269,8 @@ static hipError_t launch_merge_mfma_dh(const DecodeArgs& a, const DecodePlan& p,
   const dim3 grid(p.d_u / kMmCols, d.n_heads, (unsigned)((a.B + rows - 1) / rows));
   merge_up_mfma_kernel<DH><<<grid, 256, sm, stream>>>(
       (const float*)(a.ws + p.off_m), (const float*)(a.ws + p.off_l), (const bf16_t*)(a.ws + p.off_u),
-      (const bf16_t*)a.W_uv, (float*)(a.ws + p.off_opart), (bf16_t*)a.out, (int*)(a.ws + p.off_cnt),
-      a.no_out_reduce ? 0 : 1, (int)a.B, d.n_heads, p.head_groups * 32, p.d_u, p.n_part, rows);
+      (const bf16_t*)a.W_uv, (float*)(a.ws + p.off_opart), (int)a.B, d.n_heads, p.head_groups * 32, p.d_u,
+      p.n_part, rows);
   return hipGetLastError();
 }
 

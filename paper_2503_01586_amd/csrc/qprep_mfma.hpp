@@ -101,19 +101,23 @@ __device__ __forceinline__ void qprep_mfma_body(const QprepRowsParams& P, const 
         const qp_bf16x8 bop = *reinterpret_cast<const qp_bf16x8*>(brow + ks * 16);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ks], bop, acc, 0, 0, 0);
       }
-      // D[k, b]: this lane holds batch row bt + n32 and latent columns k0 + 8*g4 + 4*hi + {0..3}
+      // D[k, b]: this lane holds batch row bt + n32 and latent columns k0 + 8*g4 + 4*hi + {0..3}.  The two
+      // lanes of a batch row (hi = 0, 1) hold the two halves of each 8-column lane slot of the operand
+      // layout (qt_packed_index): the upper half is fetched from lane + 32 and the slot stored as 16 bytes.
       const int b = b0 + bt + n32;
-      if (b < B) {
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          bf16_t* orow = qt + qt_packed_index(b, h, k0 + 4 * hi + 8 * g4, P.head_groups, d_c, P.q_slice);   // four columns of one lane slot
-          uint2 pk;
-          pk.x = (uint32_t)f32_to_bf16_bits(acc[4 * g4] * scale_log2e) |
-                 ((uint32_t)f32_to_bf16_bits(acc[4 * g4 + 1] * scale_log2e) << 16);
-          pk.y = (uint32_t)f32_to_bf16_bits(acc[4 * g4 + 2] * scale_log2e) |
-                 ((uint32_t)f32_to_bf16_bits(acc[4 * g4 + 3] * scale_log2e) << 16);
-          *reinterpret_cast<uint2*>(orow) = pk;
-        }
+      for (int g4 = 0; g4 < 4; ++g4) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16_bits(acc[4 * g4] * scale_log2e) |
+               ((uint32_t)f32_to_bf16_bits(acc[4 * g4 + 1] * scale_log2e) << 16);
+        pk.y = (uint32_t)f32_to_bf16_bits(acc[4 * g4 + 2] * scale_log2e) |
+               ((uint32_t)f32_to_bf16_bits(acc[4 * g4 + 3] * scale_log2e) << 16);
+        uint4 slot;
+        slot.x = pk.x; slot.y = pk.y;
+        slot.z = __shfl_xor(pk.x, 32, kWave);
+        slot.w = __shfl_xor(pk.y, 32, kWave);
+        if (b < B && hi == 0)
+          *reinterpret_cast<uint4*>(qt + qt_packed_index(b, h, k0 + 8 * g4, P.head_groups, d_c, P.q_slice)) = slot;
       }
     }
   }
