@@ -105,6 +105,17 @@ int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, 
                    void* ke_plane, void* c_plane, int64_t plane_rows, void* ws, size_t ws_bytes,
                    void* hip_stream);
 
+/* Which kernels the decode entry points (elitekv_decode_attn, _decode_step, _multiquery_attn and their slrd_
+ * forms; Sections 3.1, 3.2 and 5 as cited there) run for a shape: ELITEKV_PATH_MATRIX_CORE, the tuned bf16 MFMA
+ * kernels (bf16; d_h 64 or 128; r = 4, 8 or 16 elite chunks per head; (d_h - 2r) a multiple of 8; d_c a
+ * multiple of 128 up to 2048, or 1920; r = 16 only up to d_c 1792, the widest row whose tiles fit the LDS next to
+ * 2 r = 32 elite values per head; separated latents: d_ck and d_c - d_ck whole wave slices / 64-column chunks),
+ * or ELITEKV_PATH_GENERIC, the untuned fp32 vector kernels that cover every other shape (all fp32 shapes,
+ * other r or d_c).  Results are the same to rounding; only the speed differs, so a caller that cares asks here.
+ * d_ck = 0: joint latent; d_ck > 0: separated latents.  Host only.  Negative status on bad dims. */
+enum elitekv_path { ELITEKV_PATH_GENERIC = 0, ELITEKV_PATH_MATRIX_CORE = 1 };
+int elitekv_decode_path(const elitekv_dims* dims, int32_t d_ck);
+
 /* Number of sequence splits elitekv_decode_attn uses when n_splits == 0 ("auto") for this shape.
  * Returns <= 0 on bad dims. */
 int32_t elitekv_decode_auto_splits(const elitekv_dims* dims, int64_t B, int64_t max_seq_len);

@@ -48,6 +48,7 @@ def _load():
         "elitekv_validate_elite_idx": (C.c_int, [DP, P]),
         "elitekv_append_workspace_bytes": (SZ, [DP, I64]),
         "elitekv_append": (C.c_int, [DP, P, P, P, I64, P, P, P, P, P, I64, P, SZ, P]),
+        "elitekv_decode_path": (C.c_int, [DP, I32]),
         "elitekv_decode_auto_splits": (I32, [DP, I64, I64]),
         "elitekv_decode_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_decode_attn": (C.c_int, [DP, P, P, P, I64, I64, I64, P, P, P, P, P, I64, P, P, SZ, I32, P]),
@@ -164,6 +165,17 @@ def elitekv_append(dims, x, pos, slot, W_ke, W_dkv, elite_idx, ke_plane, c_plane
                              _ptr(W_dkv), _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane),
                              int(plane_rows), _ptr(ws), ws_bytes, _stream(stream))
     _check(st, "elitekv_append")
+
+
+PATH_GENERIC, PATH_MATRIX_CORE = 0, 1
+
+
+def elitekv_decode_path(dims, d_ck=0) -> int:
+    """PATH_MATRIX_CORE or PATH_GENERIC (which kernels the decode entry points run for this shape)."""
+    st = _lib.elitekv_decode_path(C.byref(dims), int(d_ck))
+    if st < 0:
+        raise EliteKVError(st, "elitekv_decode_path")
+    return st
 
 
 def elitekv_decode_auto_splits(dims, B, max_seq_len) -> int:

@@ -109,7 +109,7 @@ struct AttnMfmaLayout {
   static constexpr int X1_OFF = KE_OFF + KE_BUFS * KE_BYTES;
   static constexpr int X2_OFF = X1_OFF + X1_PAD;
   static constexpr int LDS_BYTES = X2_OFF + X2;
-  static_assert(LDS_BYTES <= kLdsMax, "exceeds the 160 KiB of LDS of a gfx950 compute unit");
+  static constexpr bool kFits = LDS_BYTES <= kLdsMax;       // else: not compiled (the shape runs the generic kernels)
 };
 
 __device__ __forceinline__ int tile_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
@@ -654,9 +654,21 @@ static hipError_t launch_attn_as(const AttnMfmaParams& prm, int64_t B, hipStream
 
 template <int NW, int DC_W, int TWO_R, bool SEP>
 static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t stream) {
-  // head-group pairs share their rows through the L2; every other launch reads a row once
-  return prm.pair_map ? launch_attn_as<NW, DC_W, TWO_R, SEP, 2>(prm, B, stream)
-                      : launch_attn_as<NW, DC_W, TWO_R, SEP, 1>(prm, B, stream);
+  if constexpr (AttnMfmaLayout<NW, DC_W, TWO_R>::kFits) {
+    // head-group pairs share their rows through the L2; every other launch reads a row once
+    return prm.pair_map ? launch_attn_as<NW, DC_W, TWO_R, SEP, 2>(prm, B, stream)
+                        : launch_attn_as<NW, DC_W, TWO_R, SEP, 1>(prm, B, stream);
+  } else {
+    return hipErrorInvalidValue;                            // decode_mfma_supported() keeps such shapes away
+  }
+}
+
+// does the tile set of (waves, slice width) hold its LDS layout with elite rows of 2r values?
+template <int NW, int DC_W>
+static bool layout_fits(int two_r) {
+  return two_r == 8 ? AttnMfmaLayout<NW, DC_W, 8>::kFits
+       : two_r == 16 ? AttnMfmaLayout<NW, DC_W, 16>::kFits
+       : two_r == 32 ? AttnMfmaLayout<NW, DC_W, 32>::kFits : false;
 }
 
 // wave slice of the compiled instantiation for a latent row of d_c columns; 0 = none
@@ -689,9 +701,14 @@ bool decode_mfma_supported(const elitekv_dims& d, int d_ck) {
   if (d.dtype != ELITEKV_BF16) return false;
   if ((d.head_dim != 128 && d.head_dim != 64) || (d.head_dim - 2 * d.r) % 8) return false;
   const int two_r = 2 * d.r;
-  if (two_r != 8 && two_r != 16) return false;
+  if (two_r != 8 && two_r != 16 && two_r != 32) return false;     // r = 4, 8, 16 elite chunks per head
   const int w = slice_width(d.d_c);
   if (w == 0) return false;
+  bool fits = false;                                      // 2r = 32 with the widest rows does not fit the LDS
+#define X(DC, NWV, DCW) if (d.d_c == DC) fits = layout_fits<NWV, DCW>(two_r);
+  EKV_ATTN_SHAPES(X)
+#undef X
+  if (!fits) return false;
   if (d_ck > 0 && w > 256) return false;    // the one-wave-per-SIMD instantiations are compiled for the joint latent only
   // separated latents: whole wave slices on either side of the boundary
   // (and the value part a whole number of the merge kernels' 64-column chunks)
@@ -733,11 +750,13 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
 #define X(DC, NWV, DCW)                                                                                \
   if (d.d_c == DC) {                                                                                   \
     if constexpr (DCW <= 256) {                                                                        \
-      if (sep) e = two_r == 16 ? launch_attn<NWV, DCW, 16, true>(prm, a.B, stream)                     \
+      if (sep) e = two_r == 32 ? launch_attn<NWV, DCW, 32, true>(prm, a.B, stream)                     \
+                 : two_r == 16 ? launch_attn<NWV, DCW, 16, true>(prm, a.B, stream)                     \
                                : launch_attn<NWV, DCW, 8, true>(prm, a.B, stream);                     \
     }                                                                                                  \
-    if (!sep) e = two_r == 16 ? launch_attn<NWV, DCW, 16, false>(prm, a.B, stream)                     \
-                              : launch_attn<NWV, DCW, 8, false>(prm, a.B, stream);                     \
+    if (!sep) e = two_r == 32 ? launch_attn<NWV, DCW, 32, false>(prm, a.B, stream)                     \
+                  : two_r == 16 ? launch_attn<NWV, DCW, 16, false>(prm, a.B, stream)                   \
+                                : launch_attn<NWV, DCW, 8, false>(prm, a.B, stream);                   \
   }
   EKV_ATTN_SHAPES(X)
 #undef X

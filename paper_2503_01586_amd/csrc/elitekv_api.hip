@@ -298,6 +298,13 @@ int elitekv_append(const elitekv_dims* dims, const void* x, const int32_t* pos, 
                      plane_rows, ws, ws_bytes, hip_stream);
 }
 
+int elitekv_decode_path(const elitekv_dims* dims, int32_t d_ck) {
+  DecodePlan p;
+  const int st = plan_decode(dims, d_ck, 1, 16, 0, &p);
+  if (st) return st;
+  return p.mfma ? ELITEKV_PATH_MATRIX_CORE : ELITEKV_PATH_GENERIC;
+}
+
 int32_t elitekv_decode_auto_splits(const elitekv_dims* dims, int64_t B, int64_t max_seq_len) {
   DecodePlan p;
   if (plan_decode(dims, 0, B, max_seq_len, 0, &p)) return 0;

@@ -42,6 +42,9 @@ APPEND_CASES = {
     "bf16_13b_200_tokens": (shape(5120, 40, 128, 8, 1920, "bf16"), 200, 8191),
     "bf16_12pct_odd_hidden_130": (shape(1000, 32, 128, 4, 768, "bf16"), 130, 2047),
     "bf16_half_block_boundary_200": (shape(1024, 24, 64, 4, 320, "bf16"), 200, 999),   # 2 r n_h = 192
+    "bf16_r16_one_token": (shape(4096, 32, 128, 16, 1792, "bf16"), 1, 32767),
+    "bf16_r16_batch_16": (shape(4096, 32, 128, 16, 1792, "bf16"), 16, 4095),
+    "bf16_r16_300_tokens": (shape(4096, 32, 128, 16, 1792, "bf16"), 300, 8191),
 }
 
 
@@ -120,6 +123,12 @@ DECODE_CASES = {
 for _dc in (128, 384, 512, 640, 896, 1024, 1152, 1280, 1408, 1664, 1792, 2048):
     DECODE_CASES["bf16_latent_%d" % _dc] = (shape(64, 32, 128, 8 if _dc % 256 else 4, _dc, "bf16"), [150, 33, 16],
                                             [0, 3])
+# r = 16 elite chunks per head (Table 2's RoPElite setting; 34.4 % of the full cache at the 7B shape with d_c 1792)
+DECODE_CASES["bf16_r16_latent_1792"] = (shape(64, 32, 128, 16, 1792, "bf16"), [300, 1, 257, 16], [0, 1, 4])
+DECODE_CASES["bf16_r16_latent_1024_batch_9"] = (shape(64, 32, 128, 16, 1024, "bf16"),
+                                                [0, 1, 15, 16, 17, 250, 33, 48, 100], [0, 3])
+DECODE_CASES["bf16_r16_latent_1536_40_heads"] = (shape(64, 40, 128, 16, 1536, "bf16"), [97, 160], [0, 2])
+DECODE_CASES["bf16_r16_small_heads"] = (shape(64, 8, 64, 16, 256, "bf16"), [70, 33], [0, 2])
 DECODE_CASES["bf16_latent_2048_40_heads"] = (shape(64, 40, 128, 8, 2048, "bf16"), [97, 160], [0, 2])
 DECODE_CASES["bf16_latent_1024_batch_9"] = (shape(64, 32, 128, 8, 1024, "bf16"), [0, 1, 15, 16, 17, 250, 33, 48, 100],
                                             [0, 3])

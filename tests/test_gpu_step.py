@@ -37,6 +37,9 @@ STEP_CASES = {
     "bf16_small_heads_two_waves": (shape(512, 8, 64, 4, 128, "bf16"), [77, 16]),          # d_c = 128: two-wave attention
     "bf16_forty_heads_r4": (shape(1024, 40, 128, 4, 256, "bf16"), [40, 41, 1]),             # two head groups, 2r = 8
     "bf16_head_dim_64_five_sequences": (shape(768, 16, 64, 8, 512, "bf16"), [9, 100, 33, 64, 2]),
+    "bf16_r16_one_sequence": (shape(4096, 32, 128, 16, 1792, "bf16"), [301]),                 # 2r = 32 elite values per head
+    "bf16_r16_three_sequences": (shape(4096, 32, 128, 16, 1024, "bf16"), [1, 64, 97]),
+    "bf16_r16_twelve_sequences": (shape(4096, 32, 128, 16, 1792, "bf16"), [7 + 13 * i for i in range(12)]),
     "fp32_tiny_three_sequences": (synth.CONFIGS["tiny_fp32"].as_dict(), [129, 5, 60]),
 }
 
