@@ -509,7 +509,12 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
     const int64_t wide = N % 256 == 0 && (a.d2 == 0 || split % 256 == 0) ? (N / 256) * ((a.T + 255) / 256) : 0;
     if (wide >= 352 || (wide >= 224 && wide <= 256)) return launch_gemm_dma<4, 4, 2, 4>(a, stream);
     if (col_blocks * ((a.T + 255) / 256) >= 512) return launch_gemm_dma<2, 6, 4, 2>(a, stream);
-    if (col_blocks * ((a.T + 127) / 128) >= 256) return launch_gemm_dma<2, 4, 2, 2>(a, stream);
+    // 128 x 128 tiles: with about one work-group per compute unit eight waves (two per SIMD, 32 tokens x 64
+    // columns each) hide a little more of the stage latency than four (595 against 549 TFLOP/s at 2048 tokens
+    // x 2048 columns); with more rounds the four-wave form and its larger share of the tile per wave is kept
+    const int64_t wgs128 = col_blocks * ((a.T + 127) / 128);
+    if (wgs128 >= 256 && wgs128 <= 384) return launch_gemm_dma<1, 6, 4, 2>(a, stream);
+    if (wgs128 >= 256) return launch_gemm_dma<2, 4, 2, 2>(a, stream);
     return launch_gemm_dma<1, 6, 2, 2>(a, stream);
   }
   if (col_blocks * ((a.T + 255) / 256) >= 1024) return launch_gemm_wn<4>(a, stream);

@@ -42,6 +42,7 @@ APPEND_CASES = {
     "bf16_13b_200_tokens": (shape(5120, 40, 128, 8, 1920, "bf16"), 200, 8191),
     "bf16_12pct_odd_hidden_130": (shape(1000, 32, 128, 4, 768, "bf16"), 130, 2047),
     "bf16_half_block_boundary_200": (shape(1024, 24, 64, 4, 320, "bf16"), 200, 999),   # 2 r n_h = 192
+    "bf16_7b_2100_tokens": (shape(4096, 32, 128, 8, 1536, "bf16"), 2100, 32767),   # about one 128 x 128 tile per compute unit
     "bf16_r16_one_token": (shape(4096, 32, 128, 16, 1792, "bf16"), 1, 32767),
     "bf16_r16_batch_16": (shape(4096, 32, 128, 16, 1792, "bf16"), 16, 4095),
     "bf16_r16_300_tokens": (shape(4096, 32, 128, 16, 1792, "bf16"), 300, 8191),
