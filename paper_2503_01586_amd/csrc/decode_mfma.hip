@@ -50,10 +50,11 @@ struct AttnMfmaParams {
   int d_q, d_u;           // widths of the absorbed query and of the latent accumulators (d_c when joint)
   int q_slice;            // column slice per wave (DC_W), as the query preparation laid qt out
   int64_t max_seq_len, batch_stride_rows, plane_rows;
-  // Fused decode step: the newest token of every sequence (position seq_len - 1) is not read from the
-  // planes.  Its cache row is still a set of partial sums (the append's contraction splits); the
-  // extra work-groups with split index n_splits add them up, store the row and hand the token to
-  // the merge as one more split.  n_part = partials per batch row (n_splits, or n_splits + 1 here).
+  // Fused decode step: the cache row of the newest token of every sequence (position seq_len - 1) is
+  // still a set of partial sums (the append's contraction splits) when the launch begins.  The
+  // work-group whose tiles include that position adds them up and stores the row before it requests
+  // its first tile (both head groups of a 40-head shape do, each for itself); every other tile of the
+  // launch lies below that position.  n_part = partials per batch row (= n_splits).
   int n_part;
   int fresh;              // 1: fused decode step
   const float* fr_partial;   // [fr_ks][batch][fr_stride] sums of the append's contraction splits (a cache row first)
@@ -150,21 +151,17 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 // log2-domain slack before the running maximum is raised: probabilities stay below 2^8
 constexpr float kRescaleSlack = 8.f;
 
-// The newest token of sequence b in a fused decode step, for head group hg (NT threads).
-//   1. its cache row = the sum of the append's contraction splits (in split order, as append_finish
-//      adds them), the elite pairs rotated with the (sin, cos) the query preparation left behind
-//      (same position, same chunks), rounded to bf16; head group 0 stores it at slot[b];
-//   2. its score against every head of the group, from the row AS STORED (what a later step reads):
-//      s_h = qe[h] . ke_row[h] + qt[h] . c_row[0 : d_q]           (log2 domain, query pre-scaled)
-//   3. one more split for the merge: m = s_h, l = 1, U = c_row[d_c - d_u : d_c].
-// A sequence with no attended token at all (seq_len <= 0) gets an empty split (l = 0).
+// The newest token of sequence b in a fused decode step (NT threads): its cache row = the sum of the
+// append's contraction splits (in split order, as append_finish adds them), the elite pairs rotated
+// with the (sin, cos) the query preparation left behind (same position, same chunks), rounded to the
+// cache type and stored at slot[b].  Run by the work-group(s) that own the tile the token lies in,
+// before they request anything from the planes: the tile loads then bring the row in like any other.
 template <int NT, int TWO_R>
-__device__ __forceinline__ void new_token_role(const AttnMfmaParams& p, int hg, int b, char* smem) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+__device__ __forceinline__ void store_new_token_row(const AttnMfmaParams& p, int b) {
+  const int tid = threadIdx.x;
   const int NE = p.n_h * TWO_R, N = NE + p.d_c;
-  float* row = reinterpret_cast<float*>(smem);             // [N] the row as stored
   const int64_t slot = p.fr_slot[b];
-  const bool store = hg == 0 && slot >= 0 && slot < p.plane_rows;
+  if (slot < 0 || slot >= p.plane_rows) return;            // a token without a row is not stored
   for (int pr = tid; pr < N / 2; pr += NT) {
     const int n = 2 * pr;
     float a0 = 0.f, a1 = 0.f;
@@ -184,49 +181,8 @@ __device__ __forceinline__ void new_token_role(const AttnMfmaParams& p, int hg, 
       a0 = o0; a1 = o1;
     }
     const uint32_t pk = pack_bf16x2(a0, a1);
-    row[n] = __uint_as_float(pk << 16);
-    row[n + 1] = __uint_as_float(pk & 0xffff0000u);
-    if (store) {
-      if (n < NE) *reinterpret_cast<uint32_t*>(p.fr_ke_out + slot * NE + n) = pk;
-      else *reinterpret_cast<uint32_t*>(p.fr_c_out + slot * (int64_t)p.d_c + (n - NE)) = pk;
-    }
-  }
-  __syncthreads();
-  int64_t len = p.seq_len[b];                              // clamped as the tile work-groups clamp it
-  len = min(len, p.max_seq_len);
-  len = min(len, p.plane_rows - (int64_t)(b / p.q_per_seq) * p.batch_stride_rows);
-  const bool attended = len > 0;
-  const int64_t pbase = ((int64_t)b * p.n_part + p.n_splits) * (p.head_groups * 32) + hg * 32;
-  const float* crow = row + NE;
-  for (int hh = wave; hh < 32; hh += NT / 64) {
-    const int head = hg * 32 + hh;
-    if (head >= p.n_h) continue;                           // uniform over the wave
-    float acc = 0.f;
-    for (int k = lane * 8; k < p.d_q; k += 512) {
-      const uint4 qv = *reinterpret_cast<const uint4*>(p.qt + qt_packed_index(b, head, k, p.head_groups, p.d_q, p.q_slice));
-      const uint32_t qq[4] = {qv.x, qv.y, qv.z, qv.w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        acc = fmaf(__uint_as_float(qq[i] << 16), crow[k + 2 * i], acc);
-        acc = fmaf(__uint_as_float(qq[i] & 0xffff0000u), crow[k + 2 * i + 1], acc);
-      }
-    }
-    if (lane < TWO_R) acc = fmaf(p.qe[((int64_t)b * p.n_h + head) * TWO_R + lane], row[head * TWO_R + lane], acc);
-    acc = wave_sum(acc);
-    if (lane == 0) {
-      p.part_m[pbase + hh] = attended ? acc : -INFINITY;
-      p.part_l[pbase + hh] = attended ? 1.f : 0.f;
-    }
-    bf16_t* urow = p.part_u + (pbase + hh) * (int64_t)p.d_u;
-    const float* vrow = crow + (p.d_c - p.d_u);
-    for (int k = lane * 8; k < p.d_u; k += 512) {
-      uint4 o = make_uint4(0, 0, 0, 0);
-      if (attended) {
-        o.x = pack_bf16x2(vrow[k], vrow[k + 1]);     o.y = pack_bf16x2(vrow[k + 2], vrow[k + 3]);
-        o.z = pack_bf16x2(vrow[k + 4], vrow[k + 5]); o.w = pack_bf16x2(vrow[k + 6], vrow[k + 7]);
-      }
-      *reinterpret_cast<uint4*>(urow + k) = o;
-    }
+    if (n < NE) *reinterpret_cast<uint32_t*>(p.fr_ke_out + slot * NE + n) = pk;
+    else *reinterpret_cast<uint32_t*>(p.fr_c_out + slot * (int64_t)p.d_c + (n - NE)) = pk;
   }
 }
 
@@ -271,7 +227,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
     // that XCD's L2 instead of fetching it from HBM again.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int item = (slot >> 1) * 8 + xcd;
-    const int per_row = p.n_splits + p.fresh;            // the new-token work-groups are items too
+    const int per_row = p.n_splits;
     if (item >= per_row * p.batch) return;
     hg = slot & 1;
     split = item % per_row;
@@ -279,10 +235,6 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   }
   if (split == 0 && hg == 0)
     for (int i = tid; i < p.n_h; i += NW * 64) p.chunk_counters[(int64_t)b * p.n_h + i] = 0;
-  if (split >= p.n_splits) {                             // only in a fused decode step
-    new_token_role<NW * 64, TWO_R>(p, hg, b, smem);
-    return;
-  }
   // ---- the query, requested before anything else
   // This wave's slice of the absorbed query as the B operand of the 16x16x32 score MFMAs (lane l holds
   // head hh*16 + l%16, latent columns 32*ks + 8*(l/16) .. +8) and the lane's head's rotated elite
@@ -303,38 +255,52 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   float qe[TWO_R > 0 ? TWO_R : 1];
   int32_t len_raw;                                       // seq_len[b] through the scalar cache: not behind the query
   asm volatile("s_load_dword %0, %1, 0x0" : "=s"(len_raw) : "s"(p.seq_len + b) : "memory");
-  if (do_s) {
+  auto load_query = [&]() {
+    if (do_s) {
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      const int hq = min(hg * 32 + hh * 16 + i16, p.n_h - 1);
-      const bf16_t* qrow = p.qt + qt_packed_index(b, hq, cw * DC_W + 8 * q16, p.head_groups, p.d_q, DC_W);
+      for (int hh = 0; hh < 2; ++hh) {
+        const int hq = min(hg * 32 + hh * 16 + i16, p.n_h - 1);
+        const bf16_t* qrow = p.qt + qt_packed_index(b, hq, cw * DC_W + 8 * q16, p.head_groups, p.d_q, DC_W);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)                        // one contiguous KiB per instruction
-        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(Qb[ks][hh]) : "v"(qrow + ks * 1024) : "memory");
+        for (int ks = 0; ks < KS; ++ks)                      // one contiguous KiB per instruction
+          asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(Qb[ks][hh]) : "v"(qrow + ks * 1024) : "memory");
+      }
     }
-  }
-  if (TWO_R > 0) {
-    const float* qer = p.qe + ((int64_t)b * p.n_h + head_c) * TWO_R;
-    f32x4 qv[TWO_R > 0 ? TWO_R / 4 : 1];                  // (four floats in consecutive registers)
+    if (TWO_R > 0) {
+      const float* qer = p.qe + ((int64_t)b * p.n_h + head_c) * TWO_R;
+      f32x4 qv[TWO_R > 0 ? TWO_R / 4 : 1];                // (four floats in consecutive registers)
 #pragma unroll
-    for (int j = 0; j < TWO_R / 4; ++j) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qv[j]) : "v"(qer + 4 * j) : "memory");
+      for (int j = 0; j < TWO_R / 4; ++j) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qv[j]) : "v"(qer + 4 * j) : "memory");
 #pragma unroll
-    for (int j = 0; j < TWO_R; ++j) qe[j] = qv[j / 4][j % 4];
-  }
+      for (int j = 0; j < TWO_R; ++j) qe[j] = qv[j / 4][j % 4];
+    }
+  };
+  if (!p.fresh) load_query();
   asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(len_raw) : : "memory");
-  __builtin_amdgcn_s_barrier();                          // every wave's query requests are queued
+  const int64_t row0 = (int64_t)(b / p.q_per_seq) * p.batch_stride_rows;
+  int64_t len = len_raw;
+  len = min(len, p.max_seq_len);
+  len = min(len, p.plane_rows - row0);
+  len = max(len, (int64_t)0);
+  if (p.fresh) {
+    // Fused decode step: the work-group whose tiles include the newest token's position (both head groups
+    // of it, each for itself) finishes that token's cache row and stores it, and waits for the stores,
+    // before any wave of it requests a tile; with nothing attended the row is still stored, by one group.
+    // This comes before the query loads: nothing may touch their registers until they have landed.
+    const bool own = len > 0 ? split == (int)(((len - 1) / kTile) % p.n_splits) : (split == 0 && hg == 0);
+    if (own) {
+      store_new_token_row<NW * 64, TWO_R>(p, b);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    load_query();
+  }
+  __builtin_amdgcn_s_barrier();                          // every wave's query requests are queued (and a new row is stored)
 
   char* ctile0 = smem + wave * L::WTILE;                 // buffer 0; buffer 1 is TILE_BYTES further
   char* ketile0 = smem + L::KE_OFF + wave * L::KE_W;     // buffer 0; buffer 1 (if any) is KE_BYTES further
   float* x1 = reinterpret_cast<float*>(smem + L::X1_OFF);
   float* x2 = reinterpret_cast<float*>(smem + L::X2_OFF);
 
-  const int64_t row0 = (int64_t)(b / p.q_per_seq) * p.batch_stride_rows;
-  int64_t len = len_raw;
-  len = min(len, p.max_seq_len);
-  len = min(len, p.plane_rows - row0);
-  len = max(len, (int64_t)0);
-  if (p.fresh) len = max(len - 1, (int64_t)0);           // the newest token comes from the new-token role
   // Split s takes the 16-token tiles s, s + n_splits, s + 2 n_splits, ...: at any moment the
   // work-groups of a batch row read one contiguous window of the planes that moves through the
   // sequence (DRAM-page friendly); the softmax does not care about token order.
@@ -645,7 +611,7 @@ static hipError_t launch_attn_as(const AttnMfmaParams& prm, int64_t B, hipStream
   const hipError_t le = raise_lds_limit(
       lds_limit, reinterpret_cast<const void*>(&attn_mfma_kernel<NW, DC_W, TWO_R, SEP, SMODE>), L::LDS_BYTES);
   if (le != hipSuccess) return le;
-  const int per_row = prm.n_splits + prm.fresh;     // + the new-token work-group of a fused decode step
+  const int per_row = prm.n_splits;
   const dim3 grid = prm.pair_map ? dim3((unsigned)((per_row * B + 7) / 8 * 16), 1, 1)
                                  : dim3(per_row, prm.head_groups, (unsigned)B);
   attn_mfma_kernel<NW, DC_W, TWO_R, SEP, SMODE><<<grid, NW * 64, L::LDS_BYTES, stream>>>(prm);

@@ -98,12 +98,10 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
       const int64_t cap = (seq + 15) / 16;
       if (ns > cap) ns = cap;
       if (ns > kMaxSplits) ns = kMaxSplits;
-      if (p->fresh && ns > 1) --ns;            // the new-token work-group takes a compute unit of its own
       if (ns < 1) ns = 1;
     }
-    if (p->fresh && ns + 1 > kMaxSplits) return ELITEKV_EUNSUPPORTED;
     p->n_splits = (int32_t)ns;
-    p->n_part = (int32_t)ns + p->fresh;
+    p->n_part = (int32_t)ns;
     int64_t chunk = (seq + ns - 1) / ns;
     chunk = (chunk + 31) / 32 * 32;
     p->chunk = (int32_t)chunk;

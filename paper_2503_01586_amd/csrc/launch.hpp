@@ -47,10 +47,11 @@ struct DecodePlan {
   size_t off_u;         // split latent accumulators        fp32 [B, n_splits, ...]
   size_t off_opart;     // up-projection partials           fp32
   size_t off_cnt;       // MFMA path: arrival counters of the merge kernels' chunk groups   int32 [B, n_h]
-  // fused decode step (fresh = 1): the newest token of every sequence reaches the attention as one more
-  // split, built from the append's contraction-split sums inside the attention kernel
+  // fused decode step (fresh = 1): the cache row of the newest token of every sequence is finished (summed,
+  // rotated, stored) inside the attention kernel, by the work-group whose tiles include its position,
+  // from the append's contraction-split sums
   int32_t fresh;
-  int32_t n_part;       // partials per batch row: n_splits + fresh
+  int32_t n_part;       // partials per batch row (= n_splits)
   int32_t fr_ks;        // contraction splits of the step's append
   int32_t fr_kc;        // ... rows of the weight matrices per split (a multiple of 32)
   size_t off_apart;     // the append's split sums           fp32 [fr_ks, B, fr_stride]
