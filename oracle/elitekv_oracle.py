@@ -268,6 +268,32 @@ def slrd_decode_attn(q, q_pos, ke, c_k, c_v, seq_len, B_k, B_v, elite_idx, head_
     return out
 
 
+def slrd_attention_block_step(x, pos, ke_old, ck_old, cv_old, W_q, W_ke, A_k, A_v, B_k, B_v, W_o, elite_idx,
+                              head_dim: int, rope_base: float):
+    """One decode step of the attention block of an S-LRD model (Section 2.1 for the projections
+    q_t = x_t W^q and [o_0 .. o_{n_h-1}] W^o, Section 3.2 "Separated Low-Rank Decomposition" for what is
+    cached and attended): the step's tokens are appended first and are the last tokens attended to.
+
+    x [B, d]; pos [B]; ke_old[b] [S_b, n_h, 2r], ck_old[b] [S_b, d_ck], cv_old[b] [S_b, d_cv] (lists; S_b may
+    be 0); W_q [d, n_h, d_h]; W_o [n_h, d_h, d]; the other weights as in slrd_append / slrd_decode_attn.
+    Returns (y [B, d], ke_new [B, n_h, 2r], ck_new [B, d_ck], cv_new [B, d_cv]), float64.
+    """
+    x = np.asarray(x, dtype=F64)
+    W_q = np.asarray(W_q, dtype=F64)
+    W_o = np.asarray(W_o, dtype=F64)
+    B = x.shape[0]
+    q = np.einsum("bd,dhj->bhj", x, W_q)                                  # q_t = x_t W^q, head by head
+    ke_new, ck_new, cv_new = slrd_append(x, pos, W_ke, A_k, A_v, elite_idx, head_dim, rope_base)
+    cat = lambda old, new, b: np.concatenate([np.asarray(old[b], dtype=F64), new[b:b + 1]], axis=0)
+    ke_all = [cat(ke_old, ke_new, b) for b in range(B)]
+    ck_all = [cat(ck_old, ck_new, b) for b in range(B)]
+    cv_all = [cat(cv_old, cv_new, b) for b in range(B)]
+    seq = [ke_all[b].shape[0] for b in range(B)]
+    o = slrd_decode_attn(q, pos, ke_all, ck_all, cv_all, seq, B_k, B_v, elite_idx, head_dim, rope_base)
+    y = np.einsum("bhj,hjd->bd", o, W_o)                                  # [o_0, ..., o_{n_h-1}] W^o
+    return y, ke_new, ck_new, cv_new
+
+
 # ----------------------------------------------------------------------------------------------
 # Several queries per sequence (a prefill chunk, or the verification of drafted tokens): every
 # query is one more instance of the decode attention above, over the rows of its own sequence that
