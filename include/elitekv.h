@@ -337,9 +337,9 @@ int elitekv_slrd_prefill_attn(const elitekv_dims* dims, int32_t d_ck, const void
  *   its fresh row or from whatever row seq_len[b] - 1 of the plane holds.  seq_len[b] <= 0:
  *   nothing is attended, out[b] is 0, and the token is still stored at slot[b] if that is in range.
  *   For fewer than eight sequences (bf16 shapes of the matrix-core path) the step is four launches:
- *   the first pass of the append together with the query preparation; the attention, whose extra
- *   work-groups add up the append's partial sums, rotate and store the new rows and pass the new
- *   token on as one more split; the merge with the up-projection; the final reduction.  With 8 to
+ *   the first pass of the append together with the query preparation; the attention, in which the
+ *   work-group that owns the tile of a sequence's newest position first adds up the append's partial
+ *   sums, rotates and stores the new row; the merge with the up-projection (and the final reduction).  With 8 to
  *   64 sequences the first pass of the append and the query preparation share a launch as well
  *   (five launches instead of six).  Other shapes run the two entry points' kernels one after
  *   the other.
@@ -369,13 +369,15 @@ int elitekv_decode_step(const elitekv_dims* dims, const void* x, const void* q, 
  *   W_o   [n_h, d_h, d_model]      dims->dtype
  *   y     [B, d_model]             written, dims->dtype
  *   the other arguments as in elitekv_decode_step; ws: elitekv_block_step_workspace_bytes bytes.
- * Seven launches: the first pass of the append and of x W_q in one weight-streaming launch; the sum
- * of the query's contraction splits; the query preparation; the attention with its new-token
- * work-groups; the merge with the up-projection; out W_o read straight from the merge's
- * column-chunk partials; the sum of its contraction splits.
- * EUNSUPPORTED unless the shape takes the fused path of elitekv_decode_step (bf16, matrix-core
- * shapes, fewer than eight sequences, joint latent) and d_model and n_h d_h are multiples of 64;
- * other errors as there.
+ * Fewer than eight sequences (bf16 shapes of the matrix-core path): seven launches -- the first pass of
+ * the append and of x W_q in one weight-streaming launch; the sum of the query's contraction splits; the
+ * query preparation; the attention, which also finishes and stores the new rows; the merge with the
+ * up-projection; out W_o read straight from the merge's column-chunk partials; the sum of its
+ * contraction splits.  Eight to 64 sequences, and bf16 shapes outside the matrix-core path: the composed
+ * form -- q = x W_q and y = out W_o as weight-streaming launches of their own around the kernels of
+ * elitekv_decode_step, q and out (rounded to dims->dtype) staying in the workspace.
+ * EUNSUPPORTED unless bf16, B <= 64 and d_model and n_h d_h are multiples of 64; other errors as
+ * elitekv_decode_step.
  * ------------------------------------------------------------------------------------------- */
 size_t elitekv_block_step_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len,
                                           int32_t n_splits);
@@ -384,6 +386,20 @@ int elitekv_block_step(const elitekv_dims* dims, const void* x, const int32_t* p
                        const void* W_q, const void* W_ke, const void* W_dkv, const void* W_uk, const void* W_uv,
                        const void* W_o, const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows,
                        void* y, void* ws, size_t ws_bytes, int32_t n_splits, void* hip_stream);
+
+/* The whole attention block of a decode step of an S-LRD model (Section 2.1 projections around Section 3.2's
+ * separated decomposition): elitekv_block_step with the cache rows, keys and values of elitekv_slrd_append /
+ * elitekv_slrd_decode_attn (A_k [d_model, d_ck], A_v [d_model, d_c - d_ck], B_k [d_ck, n_h, d_h - 2r],
+ * B_v [d_c - d_ck, n_h, d_h]; a latent row is [c^k | c^v]).  Always the composed form (see elitekv_block_step).
+ * EINVAL unless 0 < d_ck < dims->d_c; EUNSUPPORTED unless bf16, B <= 64, d_model and n_h d_h multiples of 64. */
+size_t elitekv_slrd_block_step_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t max_seq_len,
+                                               int32_t n_splits);
+int elitekv_slrd_block_step(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                            const int64_t* slot, const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                            int64_t batch_stride_rows, const void* W_q, const void* W_ke, const void* A_k,
+                            const void* A_v, const void* B_k, const void* B_v, const void* W_o,
+                            const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows, void* y,
+                            void* ws, size_t ws_bytes, int32_t n_splits, void* hip_stream);
 
 /* The same step for separated latents: elitekv_slrd_append followed by elitekv_slrd_decode_attn. */
 size_t elitekv_slrd_decode_step_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B,

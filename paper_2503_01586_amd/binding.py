@@ -75,6 +75,9 @@ def _load():
                                           P]),
         "elitekv_block_step_workspace_bytes": (SZ, [DP, I64, I64, I32]),
         "elitekv_block_step": (C.c_int, [DP, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, P, P, I64, P, P, SZ, I32, P]),
+        "elitekv_slrd_block_step_workspace_bytes": (SZ, [DP, I32, I64, I64, I32]),
+        "elitekv_slrd_block_step": (C.c_int, [DP, I32, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, P, P, P, I64, P, P,
+                                              SZ, I32, P]),
         "elitekv_slrd_decode_step_workspace_bytes": (SZ, [DP, I32, I64, I64, I32]),
         "elitekv_slrd_decode_step": (C.c_int, [DP, I32, P, P, P, P, P, I64, I64, I64, P, P, P, P, P, P, P, P, I64, P,
                                                P, SZ, I32, P]),
@@ -360,6 +363,24 @@ def elitekv_block_step(dims, x, pos, slot, seq_len, max_seq_len, batch_stride_ro
                                  _ptr(W_uk), _ptr(W_uv), _ptr(W_o), _ptr(elite_idx), _ptr(ke_plane), _ptr(c_plane),
                                  int(plane_rows), _ptr(y), _ptr(ws), ws_bytes, int(n_splits), _stream(stream))
     _check(st, "elitekv_block_step")
+
+
+def elitekv_slrd_block_step_workspace_bytes(dims, d_ck, B, max_seq_len, n_splits=0) -> int:
+    return _lib.elitekv_slrd_block_step_workspace_bytes(C.byref(dims), int(d_ck), int(B), int(max_seq_len), int(n_splits))
+
+
+def elitekv_slrd_block_step(dims, d_ck, x, pos, slot, seq_len, max_seq_len, batch_stride_rows, W_q, W_ke, A_k, A_v, B_k,
+                            B_v, W_o, elite_idx, ke_plane, c_plane, y, ws, n_splits=0, stream=None, B=None,
+                            plane_rows=None):
+    B = x.shape[0] if B is None else B
+    plane_rows = c_plane.shape[0] if plane_rows is None else plane_rows
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    st = _lib.elitekv_slrd_block_step(C.byref(dims), int(d_ck), _ptr(x), _ptr(pos), _ptr(slot), _ptr(seq_len), int(B),
+                                      int(max_seq_len), int(batch_stride_rows), _ptr(W_q), _ptr(W_ke), _ptr(A_k),
+                                      _ptr(A_v), _ptr(B_k), _ptr(B_v), _ptr(W_o), _ptr(elite_idx), _ptr(ke_plane),
+                                      _ptr(c_plane), int(plane_rows), _ptr(y), _ptr(ws), ws_bytes, int(n_splits),
+                                      _stream(stream))
+    _check(st, "elitekv_slrd_block_step")
 
 
 def elitekv_slrd_decode_step_workspace_bytes(dims, d_ck, B, max_seq_len, n_splits=0) -> int:

@@ -96,9 +96,30 @@ hipError_t launch_append_small(const AppendArgs& a, hipStream_t stream) {
   return launch_append_finish(a, partial, ks, stream);
 }
 
+// out[t, n] = sum over the contraction splits of partial[s][t][n], rounded to the storage type
+__global__ __launch_bounds__(256) void dense_finish_kernel(const float* __restrict__ partial, bf16_t* __restrict__ out,
+                                                           int ksplit, int64_t total) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [T, N]
+  if (e >= total) return;
+  float a = 0.f;
+  for (int s0 = 0; s0 < ksplit; s0 += 8) {                      // eight independent loads in flight; split order kept
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (s0 + u < ksplit) ? partial[(int64_t)(s0 + u) * total + e] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a += v[u];
+  }
+  st(out, e, a);
+}
+
 hipError_t launch_append_finish(const AppendArgs& a, const float* partial, int ksplit, hipStream_t stream) {
   const elitekv_dims& d = a.dims;
   const int N = 2 * d.r * d.n_heads + d.d_c;
+  if (a.dense_out) {
+    const int64_t total = a.T * (int64_t)N;
+    dense_finish_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(partial, (bf16_t*)a.dense_out, ksplit, total);
+    return hipGetLastError();
+  }
   append_finish_kernel<<<dim3((unsigned)a.T, (N + 255) / 256), 256, 0, stream>>>(
       partial, a.pos, a.slot, a.T, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
       d.n_heads, d.head_dim, d.r, d.d_c, ksplit, rope_table(d.rope_base, d.head_dim));

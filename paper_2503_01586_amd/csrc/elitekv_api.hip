@@ -437,10 +437,92 @@ int elitekv_decode_step(const elitekv_dims* dims, const void* x, const void* q, 
 
 /* ---- whole attention block of a decode step ---- */
 
+// Plain projection out = in W of up to 64 rows (in [T, d_in], W [d_in, N], out [T, N], all bf16) through the
+// weight-streaming append kernels (r = 0: no elite columns, no rotation; the latent columns are the output).
+static elitekv_dims projection_dims(const elitekv_dims* dims, int d_in, int N) {
+  elitekv_dims pd = *dims;
+  pd.d_model = d_in; pd.n_heads = 1; pd.head_dim = 2; pd.r = 0; pd.d_c = N;
+  return pd;
+}
+static bool projection_supported(const elitekv_dims* dims, int64_t T, int d_in, int N) {
+  const elitekv_dims pd = projection_dims(dims, d_in, N);
+  return T >= 1 && T <= 64 && (append_skinny_supported(pd, T, N) || append_small_supported(pd, T, N));
+}
+static size_t projection_ws_bytes(const elitekv_dims* dims, int64_t T, int d_in, int N) {
+  const elitekv_dims pd = projection_dims(dims, d_in, N);
+  return append_ws_bytes(&pd, N, T);
+}
+static hipError_t launch_projection(const elitekv_dims* dims, const void* in, const void* W, int64_t T, int d_in, int N,
+                                    void* out, void* ws, hipStream_t stream) {
+  const elitekv_dims pd = projection_dims(dims, d_in, N);
+  AppendArgs a = append_args(&pd, N, in, nullptr, nullptr, T, nullptr, W, nullptr, nullptr, nullptr, nullptr, 0, ws);
+  a.dense_out = out;
+  return append_skinny_supported(pd, T, N) ? launch_append_skinny(a, stream) : launch_append_small(a, stream);
+}
+
+// The composed form of the block step, for what the fused form does not cover (eight sequences and more, separated
+// latents): q = x W_q, the decode step, y = out W_o as launches of their own, q and out staying in the workspace.
+// Workspace: [decode-step workspace | q bf16 [B, n_h d_h] | out bf16 [B, n_h d_h] | projection partial sums].
+struct BlockLayout { size_t step, off_q, off_o, off_proj, total; };
+static bool block_composed_layout(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t max_seq_len,
+                                  int32_t n_splits, BlockLayout* L) {
+  if (check_dims(dims) || dims->dtype != ELITEKV_BF16 || B < 1 || B > 64) return false;
+  const int hd = dims->n_heads * dims->head_dim;
+  if (!projection_supported(dims, B, dims->d_model, hd) || !projection_supported(dims, B, hd, dims->d_model)) return false;
+  L->step = step_ws_bytes(dims, d_ck, B, max_seq_len, n_splits);
+  if (L->step == 0) return false;
+  size_t off = align_up(L->step, 256);
+  L->off_q = off; off = align_up(off + (size_t)B * hd * 2, 256);
+  L->off_o = off; off = align_up(off + (size_t)B * hd * 2, 256);
+  L->off_proj = off;
+  const size_t pq = projection_ws_bytes(dims, B, dims->d_model, hd), po = projection_ws_bytes(dims, B, hd, dims->d_model);
+  L->total = align_up(off + (pq > po ? pq : po), 256);
+  return true;
+}
+
+static int block_composed_impl(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                               const int64_t* slot, const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                               int64_t batch_stride_rows, const void* W_q, const void* W_ke, const void* W_dkv,
+                               const void* W_dkv2, const void* W_uk, const void* W_uv, const void* W_o,
+                               const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows, void* y,
+                               void* ws, size_t ws_bytes, int32_t n_splits, void* hip_stream) {
+  BlockLayout L;
+  if (!block_composed_layout(dims, d_ck, B, max_seq_len, n_splits, &L)) return ELITEKV_EUNSUPPORTED;
+  if (!x || !W_q || !W_o || !y || !ws) return ELITEKV_ENULL;
+  if (!aligned16(x) || !aligned16(W_q) || !aligned16(W_o) || !aligned16(y) || !aligned16(ws)) return ELITEKV_EALIGN;
+  if (ws_bytes < L.total) return ELITEKV_EWORKSPACE;
+  char* w = (char*)ws;
+  const int hd = dims->n_heads * dims->head_dim;
+  const hipStream_t stream = (hipStream_t)hip_stream;
+  // the step's own argument checks come first (nothing is enqueued on an error): a dry plan + check
+  {
+    DecodePlan p;
+    int st = plan_decode(dims, d_ck, B, max_seq_len, n_splits, &p, true);
+    if (st) return st;
+    const int32_t a_ck = d_ck > 0 ? d_ck : dims->d_c;
+    st = append_check(dims, a_ck, x, pos, slot, B, W_ke, W_dkv, W_dkv2, elite_idx, ke_plane, c_plane, plane_rows, ws,
+                      ws_bytes, 0);
+    if (st) return st;
+    st = decode_check(dims, p, x, pos, seq_len, B, batch_stride_rows, W_uk, W_uv, elite_idx, ke_plane, c_plane,
+                      plane_rows, y, ws, ws_bytes);
+    if (st) return st;
+  }
+  if (launch_projection(dims, x, W_q, B, dims->d_model, hd, w + L.off_q, w + L.off_proj, stream) != hipSuccess)
+    return ELITEKV_EHIP;
+  const int st = step_impl(dims, d_ck, x, w + L.off_q, pos, slot, seq_len, B, max_seq_len, batch_stride_rows, W_ke, W_dkv,
+                           W_dkv2, W_uk, W_uv, elite_idx, ke_plane, c_plane, plane_rows, w + L.off_o, ws, L.step, n_splits,
+                           hip_stream);
+  if (st) return st;
+  if (launch_projection(dims, w + L.off_o, W_o, B, hd, dims->d_model, y, w + L.off_proj, stream) != hipSuccess)
+    return ELITEKV_EHIP;
+  return ELITEKV_OK;
+}
+
 size_t elitekv_block_step_workspace_bytes(const elitekv_dims* dims, int64_t B, int64_t max_seq_len, int32_t n_splits) {
   DecodePlan p;
-  if (plan_decode(dims, 0, B, max_seq_len, n_splits, &p, true, true)) return 0;
-  return p.total;
+  if (plan_decode(dims, 0, B, max_seq_len, n_splits, &p, true, true) == ELITEKV_OK) return p.total;
+  BlockLayout L;
+  return block_composed_layout(dims, 0, B, max_seq_len, n_splits, &L) ? L.total : 0;
 }
 
 int elitekv_block_step(const elitekv_dims* dims, const void* x, const int32_t* pos, const int64_t* slot,
@@ -452,6 +534,10 @@ int elitekv_block_step(const elitekv_dims* dims, const void* x, const int32_t* p
   if (B == 0) return check_dims(dims);                       // nothing to do
   DecodePlan p;
   int st = plan_decode(dims, 0, B, max_seq_len, n_splits, &p, true, true);
+  if (st == ELITEKV_EUNSUPPORTED)                            // eight sequences and more, ...: the composed form
+    return block_composed_impl(dims, 0, x, pos, slot, seq_len, B, max_seq_len, batch_stride_rows, W_q, W_ke, W_dkv,
+                               nullptr, W_uk, W_uv, W_o, elite_idx, ke_plane, c_plane, plane_rows, y, ws, ws_bytes,
+                               n_splits, hip_stream);
   if (st) return st;
   st = append_check(dims, dims->d_c, x, pos, slot, B, W_ke, W_dkv, nullptr, elite_idx, ke_plane, c_plane, plane_rows,
                     ws, ws_bytes, 0);
@@ -470,13 +556,36 @@ int elitekv_block_step(const elitekv_dims* dims, const void* x, const int32_t* p
   a.fr_slot = slot; a.fr_ke_out = ke_plane; a.fr_c_out = c_plane;
   a.no_out_reduce = 1;
   // (1) first pass of the append and of x W_q  (2) the query's contraction splits summed, rounded
-  // (3) q-prep  (4) attention, whose new-token work-groups finish the append  (5) merge +
+  // (3) q-prep  (4) attention, which also finishes and stores the new rows  (5) merge +
   // up-projection, chunk partials kept  (6) out W_o from the chunk partials  (7) sum of its splits
   hipError_t e = launch_block_front(ap, W_q, a, p, stream);
   if (e == hipSuccess) e = launch_qprep_rows(a, p, (float*)(a.ws + p.off_qe), (bf16_t*)(a.ws + p.off_qt), stream);
   if (e == hipSuccess) e = launch_decode_mfma(a, p, stream);
   if (e == hipSuccess) e = launch_oproj(a, p, W_o, y, stream);
   return e == hipSuccess ? ELITEKV_OK : ELITEKV_EHIP;
+}
+
+size_t elitekv_slrd_block_step_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B, int64_t max_seq_len,
+                                               int32_t n_splits) {
+  BlockLayout L;
+  if (!dims || d_ck <= 0 || d_ck >= dims->d_c) return 0;
+  return block_composed_layout(dims, d_ck, B, max_seq_len, n_splits, &L) ? L.total : 0;
+}
+
+int elitekv_slrd_block_step(const elitekv_dims* dims, int32_t d_ck, const void* x, const int32_t* pos,
+                            const int64_t* slot, const int32_t* seq_len, int64_t B, int64_t max_seq_len,
+                            int64_t batch_stride_rows, const void* W_q, const void* W_ke, const void* A_k,
+                            const void* A_v, const void* B_k, const void* B_v, const void* W_o,
+                            const int32_t* elite_idx, void* ke_plane, void* c_plane, int64_t plane_rows, void* y,
+                            void* ws, size_t ws_bytes, int32_t n_splits, void* hip_stream) {
+  if (!dims) return ELITEKV_ENULL;
+  int st = check_dims(dims);
+  if (st) return st;
+  if (d_ck <= 0 || d_ck >= dims->d_c || B < 0) return ELITEKV_EINVAL;
+  if (B == 0) return ELITEKV_OK;
+  return block_composed_impl(dims, d_ck, x, pos, slot, seq_len, B, max_seq_len, batch_stride_rows, W_q, W_ke, A_k, A_v,
+                             B_k, B_v, W_o, elite_idx, ke_plane, c_plane, plane_rows, y, ws, ws_bytes, n_splits,
+                             hip_stream);
 }
 
 size_t elitekv_slrd_decode_step_workspace_bytes(const elitekv_dims* dims, int32_t d_ck, int64_t B,

@@ -107,6 +107,10 @@ struct AppendArgs {
   int64_t x_ld = 0;     // elements between two rows of x; 0: dims.d_model
   int32_t x_off2 = 0;   // the W_dkv2 columns contract x[:, x_off2 : x_off2 + d2] with W_dkv2 [d2, d_c - d_ck] ...
   int32_t d2 = 0;       // ... 0: the same dims.d_model columns of x as the others
+  // Plain projection (the q and output projections of the whole-block step, Section 2.1): with dense_out set the
+  // T <= 64 append kernels run with r = 0 and leave x W_dkv as dense rows [T, d_c] of the storage type there;
+  // no rotation, no planes, pos / slot / elite_idx unused.
+  void* dense_out = nullptr;
 };
 
 struct MhaArgs {

@@ -275,10 +275,24 @@ def test_block_step_argument_errors():
     assert blk(W_o=FAKE + 8) == ekv.EALIGN
     need = ekv.elitekv_block_step_workspace_bytes(big, 1, 128)
     assert need > 0 and blk(wsb=need - 1) == ekv.EWORKSPACE
-    # shapes outside the fused path of the decode step are not covered
-    assert blk(B=8) == ekv.EUNSUPPORTED
+    # eight to 64 sequences take the composed form (projections around the decode step): same validation
+    need8 = ekv.elitekv_block_step_workspace_bytes(big, 8, 128)
+    assert need8 > ekv.elitekv_decode_step_workspace_bytes(big, 8, 128)
+    assert blk(B=8, x=None) == ekv.ENULL and blk(B=8, W_o=None) == ekv.ENULL
+    assert blk(B=8, W_q=FAKE + 8) == ekv.EALIGN
+    assert blk(B=8, wsb=need8 - 1) == ekv.EWORKSPACE
+    assert blk(B=65) == ekv.EUNSUPPORTED and ekv.elitekv_block_step_workspace_bytes(big, 65, 128) == 0
     assert blk(dims=_dims()) == ekv.EUNSUPPORTED                      # fp32
-    assert ekv.elitekv_block_step_workspace_bytes(big, 8, 128) == 0
+    # separated latents
+    sblk = lambda d_ck, **kw: lib.elitekv_slrd_block_step(
+        C.byref(big), d_ck, kw.get("x", FAKE), FAKE, FAKE, FAKE, kw.get("B", 2), 128, 128, FAKE, FAKE, FAKE,
+        kw.get("A_v", FAKE), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 256, FAKE, FAKE, kw.get("wsb", 1 << 30), 0, None)
+    assert sblk(0) == ekv.EINVAL and sblk(1536) == ekv.EINVAL
+    assert sblk(576, B=0) == ekv.OK
+    assert sblk(576, x=None) == ekv.ENULL and sblk(576, A_v=None) == ekv.ENULL
+    needs = ekv.elitekv_slrd_block_step_workspace_bytes(big, 576, 2, 128)
+    assert needs > 0 and sblk(576, wsb=needs - 1) == ekv.EWORKSPACE
+    assert ekv.elitekv_slrd_block_step_workspace_bytes(big, 0, 2, 128) == 0
 
 
 def test_slrd_prefill_argument_errors():
