@@ -300,7 +300,10 @@ struct GemmDmaLayout {
   static_assert(NS >= 3 && NS <= 12 && (NS - 2) * LPW <= 63, "ring depth outside what the load counter can express");
 };
 
-template <int WN, int NS, int WNW, int CM>
+// SPB = stages consumed per barrier (1 or 2).  With 2 the work-group synchronises once per 64 contraction rows:
+// half as many barriers and load waits, the operands of the second stage of a pair read while the first is
+// multiplied, NS - 2 stages in flight behind the pair.
+template <int WN, int NS, int WNW, int CM, int SPB>
 __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
     const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
     const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const bf16_t* __restrict__ W_dkv2, int d_ck,
@@ -427,20 +430,40 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[ks][i], o.b[ks][j], acc[i][j], 0, 0, 0);
   };
 
+  if constexpr (SPB == 1) {
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < nstages) issue();
-  // Ring pipeline: stages s+1 .. s+NS-2 stay in flight while stage s is consumed.  (A version skewed
-  // by one stage -- the operands of stage s+1 read into a second register set while stage s is
-  // multiplied -- hides the LDS latency and the barrier but keeps one stage less in flight; it
-  // measured 5 % slower with eight waves and 20 % slower with four.)
-  for (int s = 0; s < nstages; ++s) {
-    wait_loads(min(nstages - 1 - s, NS - 2));                   // this wave's loads of stage s have landed
-    __syncthreads();             // every wave's part of stage s is in LDS; everyone is done with stage s-1
-    if (s + NS - 1 < nstages) issue();                          // into the buffer stage s-1 occupied
-    StageOps ops;
-    read_ops(ops);
-    multiply(ops);
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < nstages) issue();
+    // Ring pipeline: stages s+1 .. s+NS-2 stay in flight while stage s is consumed.  (A version skewed
+    // by one stage -- the operands of stage s+1 read into a second register set while stage s is
+    // multiplied -- hides the LDS latency and the barrier but keeps one stage less in flight; it
+    // measured 5 % slower with eight waves and 20 % slower with four.)
+    for (int s = 0; s < nstages; ++s) {
+      wait_loads(min(nstages - 1 - s, NS - 2));                   // this wave's loads of stage s have landed
+      __syncthreads();             // every wave's part of stage s is in LDS; everyone is done with stage s-1
+      if (s + NS - 1 < nstages) issue();                          // into the buffer stage s-1 occupied
+      StageOps ops;
+      read_ops(ops);
+      multiply(ops);
+    }
+  } else {
+    static_assert(SPB == 2 && NS >= 4, "pairs of stages need a ring of at least four");
+#pragma unroll
+    for (int s = 0; s < NS - 2; ++s)
+      if (s < nstages) issue();
+    // Stages s and s+1 are consumed behind one barrier; before it NS-4 later stages may still be in flight,
+    // after it the two buffers of stages s-2 and s-1 are refilled (NS-2 stages in flight behind the pair).
+    for (int s = 0; s < nstages; s += 2) {
+      wait_loads(max(min(nstages, s + NS - 2) - (s + 2), 0));     // this wave's loads of stages s, s+1 have landed
+      __syncthreads();
+      if (s + NS - 2 < nstages) issue();
+      if (s + NS - 1 < nstages) issue();
+      StageOps o0, o1;
+      read_ops(o0);
+      if (s + 1 < nstages) read_ops(o1);
+      multiply(o0);
+      if (s + 1 < nstages) multiply(o1);
+    }
   }
 
   gemm_epilogue<WN>(acc, n0, t0, wm, wn, n32, hi, T, pos, slot, elite_idx, ke_plane, c_plane, plane_rows, n_h, d_h,
@@ -470,18 +493,18 @@ static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <int WN, int NS, int WNW, int CM>
+template <int WN, int NS, int WNW, int CM, int SPB = 1>
 static hipError_t launch_gemm_dma(const AppendArgs& a, hipStream_t stream) {
   using L = GemmDmaLayout<WN, NS, WNW, CM>;
   const elitekv_dims& d = a.dims;
   const int N = 2 * d.r * d.n_heads + d.d_c;
   static LdsLimit lds_limit;
-  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW, CM>),
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW, CM, SPB>),
                                         L::LDS_BYTES);
   if (le != hipSuccess) return le;
   const int64_t tblocks = (a.T + L::BN - 1) / L::BN;
   const dim3 grid((unsigned)((tblocks + 7) / 8 * 8 * (N / L::COLS)));   // token blocks padded to whole rounds of 8 XCDs
-  append_gemm_dma_kernel<WN, NS, WNW, CM><<<grid, 64 * CM * WNW, L::LDS_BYTES, stream>>>(
+  append_gemm_dma_kernel<WN, NS, WNW, CM, SPB><<<grid, 64 * CM * WNW, L::LDS_BYTES, stream>>>(
       (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
       (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
       d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, rope_table(d.rope_base, d.head_dim),
@@ -513,9 +536,9 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
     // columns each) hide a little more of the stage latency than four (595 against 549 TFLOP/s at 2048 tokens
     // x 2048 columns); with more rounds the four-wave form and its larger share of the tile per wave is kept
     const int64_t wgs128 = col_blocks * ((a.T + 127) / 128);
-    if (wgs128 >= 256 && wgs128 <= 384) return launch_gemm_dma<1, 6, 4, 2>(a, stream);
+    if (wgs128 >= 256 && wgs128 <= 384) return launch_gemm_dma<1, 6, 4, 2, 2>(a, stream);
     if (wgs128 >= 256) return launch_gemm_dma<2, 4, 2, 2>(a, stream);
-    return launch_gemm_dma<1, 6, 2, 2>(a, stream);
+    return launch_gemm_dma<1, 6, 2, 2, 2>(a, stream);
   }
   if (col_blocks * ((a.T + 255) / 256) >= 1024) return launch_gemm_wn<4>(a, stream);
   return launch_gemm_wn<1>(a, stream);

@@ -204,6 +204,14 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   // the middle of the current tile, before the latent loads of the tile after)
   constexpr int IN_FLIGHT = KE2 ? L::NLOAD + (TWO_R > 0 ? L::NKE : 0) : L::NLOAD;
 
+  // Every kernel argument the start-up uses is fetched now, in one round trip of the scalar cache (left to
+  // itself the compiler fetches them block by block where they are first used: three trips of about 0.4 us
+  // each, one after the other, before the first load of the launch can go out).
+  asm volatile("" ::"s"(p.ke_plane), "s"(p.c_plane), "s"(p.qe), "s"(p.qt), "s"(p.seq_len), "s"(p.n_h), "s"(p.d_c),
+               "s"(p.n_splits), "s"(p.head_groups), "s"(p.batch), "s"(p.pair_map), "s"(p.q_per_seq), "s"(p.d_q),
+               "s"(p.max_seq_len), "s"(p.batch_stride_rows), "s"(p.plane_rows), "s"(p.fresh), "s"(p.chunk_counters),
+               "s"(p.n_part), "s"(p.fr_partial), "s"(p.fr_stride), "s"(p.fr_sincos), "s"(p.fr_slot), "s"(p.fr_ks),
+               "s"(p.fr_ke_out), "s"(p.fr_c_out), "s"(gridDim.x), "s"(gridDim.y));
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
@@ -235,17 +243,17 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   }
   if (split == 0 && hg == 0)
     for (int i = tid; i < p.n_h; i += NW * 64) p.chunk_counters[(int64_t)b * p.n_h + i] = 0;
-  // ---- the query, requested before anything else
+  // ---- the query
   // This wave's slice of the absorbed query as the B operand of the 16x16x32 score MFMAs (lane l holds
   // head hh*16 + l%16, latent columns 32*ks + 8*(l/16) .. +8) and the lane's head's rotated elite
   // query.  A compute unit keeps only so many memory requests in flight and serves them in the order
-  // they were issued, so the 128 KB of query (quick: they come from the L2) must not queue up behind
-  // tile requests (slow: HBM) of waves that happen to run ahead: every wave asks for its query
-  // first, and no wave asks for a tile before all have (the barrier below).  The loads are issued
+  // they were issued, so the 128 KB of query (quick: they come from the L2) are requested right behind
+  // the first tile (slow: HBM; see the start-up below) and ahead of the second: they land with the first
+  // tile and never queue up behind later ones.  The loads are issued
   // from assembly, like the tile loads: a load the compiler knows of makes it wait, before the
   // first use of the value, with a count that ignores the tile loads issued behind it, i.e. for all
-  // of them.  The registers are first read in compute(), after the loop's wait for the first tile,
-  // which these loads precede.  Heads beyond n_h (second head group of 40 heads) read the last
+  // of them.  The registers are first read in compute(), after the loop's wait for the first tile.
+  // Heads beyond n_h (second head group of 40 heads) read the last
   // head's query: their results are never stored.
   const int head = hg * 32 + n;
   const bool head_ok = head < p.n_h;
@@ -253,7 +261,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   const int i16 = lane & 15, q16 = lane >> 4;
   u32x4 Qb[KS][2];
   float qe[TWO_R > 0 ? TWO_R : 1];
-  int32_t len_raw;                                       // seq_len[b] through the scalar cache: not behind the query
+  int32_t len_raw;                                       // seq_len[b] through the scalar cache: not behind the vector loads
   asm volatile("s_load_dword %0, %1, 0x0" : "=s"(len_raw) : "s"(p.seq_len + b) : "memory");
   auto load_query = [&]() {
     if (do_s) {
@@ -275,26 +283,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
       for (int j = 0; j < TWO_R; ++j) qe[j] = qv[j / 4][j % 4];
     }
   };
-  if (!p.fresh) load_query();
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(len_raw) : : "memory");
   const int64_t row0 = (int64_t)(b / p.q_per_seq) * p.batch_stride_rows;
-  int64_t len = len_raw;
-  len = min(len, p.max_seq_len);
-  len = min(len, p.plane_rows - row0);
-  len = max(len, (int64_t)0);
-  if (p.fresh) {
-    // Fused decode step: the work-group whose tiles include the newest token's position (both head groups
-    // of it, each for itself) finishes that token's cache row and stores it, and waits for the stores,
-    // before any wave of it requests a tile; with nothing attended the row is still stored, by one group.
-    // This comes before the query loads: nothing may touch their registers until they have landed.
-    const bool own = len > 0 ? split == (int)(((len - 1) / kTile) % p.n_splits) : (split == 0 && hg == 0);
-    if (own) {
-      store_new_token_row<NW * 64, TWO_R>(p, b);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    load_query();
-  }
-  __builtin_amdgcn_s_barrier();                          // every wave's query requests are queued (and a new row is stored)
 
   char* ctile0 = smem + wave * L::WTILE;                 // buffer 0; buffer 1 is TILE_BYTES further
   char* ketile0 = smem + L::KE_OFF + wave * L::KE_W;     // buffer 0; buffer 1 (if any) is KE_BYTES further
@@ -305,19 +294,12 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   // work-groups of a batch row read one contiguous window of the planes that moves through the
   // sequence (DRAM-page friendly); the softmax does not care about token order.
   const int64_t t0 = (int64_t)split * kTile;
-  const int64_t t_end = len;
   const int64_t t_step = (int64_t)p.n_splits * kTile;
   const int64_t pidx = ((int64_t)b * p.n_part + split) * (p.head_groups * 32) + hg * 32;
-
-  if (t0 >= t_end) {   // empty split: weight 0 in the merge (l == 0), accumulator rows zeroed
-    if (wave == 0 && g == 0) {
-      p.part_m[pidx + n] = -INFINITY;
-      p.part_l[pidx + n] = 0.f;
-    }
-    uint4* z = reinterpret_cast<uint4*>(p.part_u + pidx * (int64_t)p.d_u);
-    for (int i = tid; i < 4 * p.d_u; i += NW * 64) z[i] = make_uint4(0, 0, 0, 0);
-    return;
-  }
+  // Rows the tile loads may touch: until seq_len[b] has arrived, the bound the host knows (the planes'
+  // extent); afterwards the sequence's length.
+  const int64_t t_cap = min(p.max_seq_len, p.plane_rows - row0);
+  int64_t t_end = t_cap;
 
   f32x16 uacc[CT];
 #pragma unroll
@@ -526,25 +508,81 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   // two tiles per trip so that buffer and register-set indices are compile-time
   char* ctile1 = ctile0 + L::TILE_BYTES;
   char* ketile1 = KE2 ? ketile0 + L::KE_BYTES : ketile0;
+  // The second work-group of a head-group pair swaps neighbouring tiles (see tile_at below).
+  const int swp = (p.pair_map && hg) ? 1 : 0;
+
+  // ---- start-up.  seq_len[b] takes a trip to memory (about 1.5 us after a launch); the first tile does not wait
+  // for it.  Its rows are requested at once, on the assumption that the tile lies wholly inside the sequence:
+  // the rows are inside the planes whatever seq_len says (t_cap), and when the assumption holds -- every split
+  // but the one at the sequence's end -- these are exactly the loads the tile needs.  The query follows (it comes
+  // from the L2 and is first read together with the tile).  A work-group whose first tile turns out to be cut by
+  // the sequence's end, to hold the newest token's row (fused step), or not to exist, lets the loads land,
+  // discards them and starts over with the length known.
+  const int64_t spec_t = t0 + swp * t_step;
+  const bool spec = spec_t + kTile <= t_cap;
+  if (spec) {
+    issue_c(spec_t, ctile0, NtEven{});
+    issue_ke(spec_t, ketile0, NtEven{});
+  }
+  if (!p.fresh) load_query();
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(len_raw) : : "memory");
+  {
+    int64_t len = len_raw;
+    len = min(len, t_cap);
+    t_end = max(len, (int64_t)0);
+  }
+  // rows the speculative loads may have covered: all below the sequence's end, and below the newest token's row,
+  // which is still being put together when a fused step begins
+  const bool spec_ok = spec && spec_t + kTile <= t_end - (p.fresh ? 1 : 0);
+  if (spec && !spec_ok) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (p.fresh) {
+    // Fused decode step: the work-group whose tiles include the newest token's position (both head groups
+    // of it, each for itself) finishes that token's cache row and stores it, and waits for the stores,
+    // before any wave of it requests that tile; with nothing attended the row is still stored, by one group.
+    // This comes before the query loads: nothing may touch their registers until they have landed.
+    const bool own = t_end > 0 ? split == (int)(((t_end - 1) / kTile) % p.n_splits) : (split == 0 && hg == 0);
+    if (own) {
+      store_new_token_row<NW * 64, TWO_R>(p, b);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    load_query();
+  }
+  __builtin_amdgcn_s_barrier();                          // a new row is stored before any wave asks for its tile
+
+  if (t0 >= t_end) {   // empty split: weight 0 in the merge (l == 0), accumulator rows zeroed
+    if (wave == 0 && g == 0) {
+      p.part_m[pidx + n] = -INFINITY;
+      p.part_l[pidx + n] = 0.f;
+    }
+    uint4* z = reinterpret_cast<uint4*>(p.part_u + pidx * (int64_t)p.d_u);
+    for (int i = tid; i < 4 * p.d_u; i += NW * 64) z[i] = make_uint4(0, 0, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the query loads (and the stores) are done with the registers
+    return;
+  }
+
   // The i-th tile this work-group processes.  The second work-group of a head-group pair swaps
   // neighbouring tiles: at any moment the two fetch DIFFERENT rows from HBM, and each finds the
   // tile its partner fetched one step earlier in the XCD's L2 (twice as many independent streams
   // as when both ask for the same rows at the same time).
   const int n_my = (int)((t_end - t0 + t_step - 1) / t_step);
-  const int swp = (p.pair_map && hg) ? 1 : 0;
   auto tile_at = [&](int i) -> int64_t {     // t_end stands for "no such tile"
     if (i >= n_my) return t_end;
     const int j = i ^ swp;
     return t0 + (int64_t)(j < n_my ? j : i) * t_step;
   };
   const int64_t first = tile_at(0), second = tile_at(1);
-  issue_c(first, ctile0, NtEven{});
-  issue_ke(first, ketile0, NtEven{});
+  // query loads of a wave that stand behind the speculative tile loads in the order of return
+  constexpr int NQ = 2 * KS + TWO_R / 4;
+  if (!spec_ok) {
+    issue_c(first, ctile0, NtEven{});
+    issue_ke(first, ketile0, NtEven{});
+  }
   if (second < t_end) {
     // All work-groups start together.  Requests for the second tile go out once half of the first has
     // arrived: the first tile is then complete (and being computed) after one tile's worth of bus time
     // instead of two, while the bus still never runs dry.
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L::NLOAD / 2 + (TWO_R > 0 ? L::NKE : 0)) : "memory");
+    if (spec_ok) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L::NLOAD / 2 + (TWO_R > 0 ? L::NKE : 0) + NQ) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(L::NLOAD / 2 + (TWO_R > 0 ? L::NKE : 0)) : "memory");
     issue(second, ctile1, ketile1, NtOdd{});
   }
   for (int i = 0; i < n_my; i += 2) {
@@ -598,8 +636,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
     const uint4 v = *reinterpret_cast<const uint4*>(tt + row * TSTR + ch * 16);
     // non-temporal: the 25 MB of partials of a launch are on their way to memory while other work-groups still
     // stream, instead of leaving the eight L2s in one burst when the kernel ends
-    if (do_v && hg * 32 + row < p.n_h)
+    if (do_v && hg * 32 + row < p.n_h) {
       __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(ubase + (int64_t)row * p.d_u * 2 + ch * 16));
+    }
   }
 }
 

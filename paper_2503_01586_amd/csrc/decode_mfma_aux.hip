@@ -112,6 +112,9 @@ __global__ __launch_bounds__(256) void merge_up_kernel(
   constexpr int RPI = 64 / LPW;            // W_uv rows per wave instruction
   constexpr int NWI = CW / (4 * RPI);      // W_uv rows per thread
   constexpr int UB = 28;                   // split accumulators requested per batch
+  // all arguments in one round trip of the scalar cache (else: three, one after the other, before the first load)
+  asm volatile("" ::"s"(part_m), "s"(part_l), "s"(part_u), "s"(W_uv), "s"(opart), "s"(out), "s"(chunk_counters),
+               "s"(fuse_out), "s"(n_h), "s"(nhp), "s"(d_c), "s"(n_splits), "s"(gridDim.x));
   extern __shared__ __attribute__((aligned(16))) float msm[];
   float* wsp = msm;                        // [n_splits] merge weights of this head
   float* red = wsp + n_splits;             // [256] scratch
