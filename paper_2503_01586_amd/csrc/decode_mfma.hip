@@ -110,7 +110,12 @@ struct AttnMfmaLayout {
   static constexpr int X1_OFF = KE_OFF + KE_BUFS * KE_BYTES;
   static constexpr int X2_OFF = X1_OFF + X1_PAD;
   static constexpr int LDS_BYTES = X2_OFF + X2;
-  static constexpr bool kFits = LDS_BYTES <= kLdsMax;       // else: not compiled (the shape runs the generic kernels)
+  // else: not compiled (the shape runs the generic kernels); 64 elite values per head beside a 128-column latent
+  // (more elite than latent columns, two waves with eight tokens each to finalise) is not a shape worth a kernel
+  static constexpr bool kFits = LDS_BYTES <= kLdsMax && !(TWO_R == 64 && NW == 2);
+  // four waves with slices of up to 192 columns leave room for a second work-group on the compute unit (then at most
+  // 256 registers per lane) -- unless the elite rows are so wide that the LDS holds one work-group only
+  static constexpr int kGroupsPerCu = (NW == 4 && DC_W <= 192 && 2 * LDS_BYTES <= kLdsMax) ? 2 : 1;
 };
 
 __device__ __forceinline__ int tile_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
@@ -189,15 +194,19 @@ __device__ __forceinline__ void store_new_token_row(const AttnMfmaParams& p, int
 // SEP = separated latents (Section 3.2, S-LRD): a cache row is [c^k (d_q columns) | c^v (d_u columns)];
 // the waves whose slice lies in c^k only compute scores, the waves whose slice lies in c^v only
 // accumulate values (d_q is a multiple of DC_W).  SEP = false is the joint latent: every wave does both.
-// (Four-wave instantiations with slices of up to 192 columns use at most 75 KB of LDS: they are
-// compiled for two work-groups per compute unit, i.e. at most 256 registers per lane.)
+// (Four-wave instantiations with slices of up to 192 columns that use at most 80 KB of LDS are
+// compiled for two work-groups per compute unit, i.e. at most 256 registers per lane: kGroupsPerCu.)
 // SMODE: which loads of cache rows are marked non-temporal (see dma16): 1 = all (nobody else reads the rows),
 // 2 = those of the odd steps only (head-group pairs: at odd steps a work-group is the second and last reader of its tile).
 template <int NW, int DC_W, int TWO_R, bool SEP, int SMODE>
-__global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void attn_mfma_kernel(const AttnMfmaParams p) {
+__global__ __launch_bounds__(NW * 64, (AttnMfmaLayout<NW, DC_W, TWO_R>::kGroupsPerCu)) void attn_mfma_kernel(const AttnMfmaParams p) {
   using L = AttnMfmaLayout<NW, DC_W, TWO_R>;
   constexpr int KS = L::KS, CT = L::CT, NCB = L::NCB, EPL = L::EPL, TPW = L::TPW;
   constexpr int KCH = TWO_R / 8;                 // 16-byte chunks of one head's elite key
+  // One wave per SIMD (512 registers per lane, half of them accumulation registers): the accumulators are pinned to
+  // the AGPRs by hand.  Left to the compiler, such a kernel keeps the accumulators in VGPRs and parks the absorbed
+  // query in AGPRs instead -- copying its registers right after the loads below were issued, before they have landed.
+  constexpr bool ACC_AGPR = NW == 4 && L::kGroupsPerCu == 1;
   constexpr bool KE2 = L::KE_BUFS == 2 || TWO_R == 0;
   // direct-to-LDS loads that may still be in flight when a tile is consumed: with two elite-key
   // buffers the whole next tile, with one only its latent part (its elite keys are requested in
@@ -260,27 +269,31 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
   const int head_c = head_ok ? head : p.n_h - 1;
   const int i16 = lane & 15, q16 = lane >> 4;
   u32x4 Qb[KS][2];
-  float qe[TWO_R > 0 ? TWO_R : 1];
+  // the lane's head's rotated elite query, four floats per register quad; the quads are read in place (element by
+  // element) and never copied: a copy made before the loads below have landed would take stale registers with it
+  // and leave the loaded values to land in registers the compiler has already given to something else
+  f32x4 qv[TWO_R > 0 ? TWO_R / 4 : 1];
   int32_t len_raw;                                       // seq_len[b] through the scalar cache: not behind the vector loads
-  asm volatile("s_load_dword %0, %1, 0x0" : "=s"(len_raw) : "s"(p.seq_len + b) : "memory");
+  asm volatile("s_load_dword %0, %1, 0x0" : "=s"(len_raw) : "s"(p.seq_len + __builtin_amdgcn_readfirstlane(b)) : "memory");
   auto load_query = [&]() {
-    if (do_s) {
+    {
+      // every wave loads a slice, also the waves of a separated latent that only accumulate values (they read slice 0
+      // and never use it): a load under a condition would reach the loop through a merge of two register versions,
+      // which the compiler may realise as copies made right behind the loads, before they have landed
+      const int cq = do_s ? cw : 0;
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
         const int hq = min(hg * 32 + hh * 16 + i16, p.n_h - 1);
-        const bf16_t* qrow = p.qt + qt_packed_index(b, hq, cw * DC_W + 8 * q16, p.head_groups, p.d_q, DC_W);
+        const bf16_t* qrow = p.qt + qt_packed_index(b, hq, cq * DC_W + 8 * q16, p.head_groups, p.d_q, DC_W);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)                      // one contiguous KiB per instruction
           asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(Qb[ks][hh]) : "v"(qrow + ks * 1024) : "memory");
       }
     }
-    if (TWO_R > 0) {
+    if constexpr (TWO_R > 0) {
       const float* qer = p.qe + ((int64_t)b * p.n_h + head_c) * TWO_R;
-      f32x4 qv[TWO_R > 0 ? TWO_R / 4 : 1];                // (four floats in consecutive registers)
 #pragma unroll
       for (int j = 0; j < TWO_R / 4; ++j) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(qv[j]) : "v"(qer + 4 * j) : "memory");
-#pragma unroll
-      for (int j = 0; j < TWO_R; ++j) qe[j] = qv[j / 4][j % 4];
     }
   };
   const int64_t row0 = (int64_t)(b / p.q_per_seq) * p.batch_stride_rows;
@@ -417,8 +430,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
           const uint32_t w[4] = {kv.x, kv.y, kv.z, kv.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            d = fmaf(qe[8 * c + 2 * i], __uint_as_float(w[i] << 16), d);
-            d = fmaf(qe[8 * c + 2 * i + 1], __uint_as_float(w[i] & 0xffff0000u), d);
+            d = fmaf(qv[2 * c + i / 2][2 * (i % 2)], __uint_as_float(w[i] << 16), d);
+            d = fmaf(qv[2 * c + i / 2][2 * (i % 2) + 1], __uint_as_float(w[i] & 0xffff0000u), d);
           }
         }
       }
@@ -468,8 +481,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && DC_W <= 192) ? 2 : 1) void att
     l_run = l_run * alpha + psum;
     m_run = m_new;
     if (__any(alpha != 1.f)) {
-      if (CT > 8) {
-        // Wide slices keep their many accumulator tiles in the accumulation registers (AGPRs).
+      if (ACC_AGPR) {
+        // One wave per SIMD: the accumulator tiles are kept in the accumulation registers (AGPRs).
         // Rescaling them as ordinary vector arithmetic would make the compiler hold every tile in
         // VGPRs across the whole loop; the explicit moves pin them to AGPRs instead.
 #pragma unroll
@@ -673,7 +686,8 @@ template <int NW, int DC_W>
 static bool layout_fits(int two_r) {
   return two_r == 8 ? AttnMfmaLayout<NW, DC_W, 8>::kFits
        : two_r == 16 ? AttnMfmaLayout<NW, DC_W, 16>::kFits
-       : two_r == 32 ? AttnMfmaLayout<NW, DC_W, 32>::kFits : false;
+       : two_r == 32 ? AttnMfmaLayout<NW, DC_W, 32>::kFits
+       : two_r == 64 ? AttnMfmaLayout<NW, DC_W, 64>::kFits : false;
 }
 
 // wave slice of the compiled instantiation for a latent row of d_c columns; 0 = none
@@ -697,24 +711,35 @@ int decode_mfma_slice_width(int d_c) { return slice_width(d_c); }
 
 // work-groups of the attention kernel that fit one compute unit (see the launch bounds of the kernel)
 int decode_mfma_groups_per_cu(const elitekv_dims& d) {
-  int nw, w;
-  shape_of(d.d_c, &nw, &w);
-  return (nw == 4 && w <= 192) ? 2 : 1;
+  int g = 1;
+  const int two_r = 2 * d.r;
+#define X(DC, NWV, DCW)                                                                         \
+  if (d.d_c == DC)                                                                              \
+    g = two_r == 8 ? AttnMfmaLayout<NWV, DCW, 8>::kGroupsPerCu                                  \
+      : two_r == 16 ? AttnMfmaLayout<NWV, DCW, 16>::kGroupsPerCu                                \
+      : two_r == 32 ? AttnMfmaLayout<NWV, DCW, 32>::kGroupsPerCu                                \
+      : two_r == 64 ? AttnMfmaLayout<NWV, DCW, 64>::kGroupsPerCu : 1;
+  EKV_ATTN_SHAPES(X)
+#undef X
+  return g;
 }
 
 bool decode_mfma_supported(const elitekv_dims& d, int d_ck) {
   if (d.dtype != ELITEKV_BF16) return false;
   if ((d.head_dim != 128 && d.head_dim != 64) || (d.head_dim - 2 * d.r) % 8) return false;
   const int two_r = 2 * d.r;
-  if (two_r != 8 && two_r != 16 && two_r != 32) return false;     // r = 4, 8, 16 elite chunks per head
+  if (two_r != 8 && two_r != 16 && two_r != 32 && two_r != 64) return false;   // r = 4, 8, 16, 32 elite chunks per head
   const int w = slice_width(d.d_c);
   if (w == 0) return false;
-  bool fits = false;                                      // 2r = 32 with the widest rows does not fit the LDS
+  bool fits = false;                                      // 2r = 32 and 64 with the widest rows do not fit the LDS
 #define X(DC, NWV, DCW) if (d.d_c == DC) fits = layout_fits<NWV, DCW>(two_r);
   EKV_ATTN_SHAPES(X)
 #undef X
   if (!fits) return false;
   if (d_ck > 0 && w > 256) return false;    // the one-wave-per-SIMD instantiations are compiled for the joint latent only
+  // separated latents with 64 elite values per head, or 32 beside 224-column slices: the compiled code parks query
+  // registers in AGPRs right behind their loads (before they have landed), so these shapes take the generic kernels
+  if (d_ck > 0 && (two_r == 64 || (two_r == 32 && w == 224))) return false;
   // separated latents: whole wave slices on either side of the boundary
   // (and the value part a whole number of the merge kernels' 64-column chunks)
   return d_ck == 0 || (d_ck > 0 && d_ck < d.d_c && d_ck % w == 0 && (d.d_c - d_ck) % 64 == 0);
@@ -759,7 +784,8 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
                  : two_r == 16 ? launch_attn<NWV, DCW, 16, true>(prm, a.B, stream)                     \
                                : launch_attn<NWV, DCW, 8, true>(prm, a.B, stream);                     \
     }                                                                                                  \
-    if (!sep) e = two_r == 32 ? launch_attn<NWV, DCW, 32, false>(prm, a.B, stream)                     \
+    if (!sep) e = two_r == 64 ? launch_attn<NWV, DCW, 64, false>(prm, a.B, stream)                     \
+                  : two_r == 32 ? launch_attn<NWV, DCW, 32, false>(prm, a.B, stream)                   \
                   : two_r == 16 ? launch_attn<NWV, DCW, 16, false>(prm, a.B, stream)                   \
                                 : launch_attn<NWV, DCW, 8, false>(prm, a.B, stream);                   \
   }

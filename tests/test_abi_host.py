@@ -349,9 +349,9 @@ def test_append_rejects_head_dims_beyond_the_rope_table():
 
 
 def test_decode_path_query_names_the_kernels_a_shape_runs():
-    """elitekv_decode_path: the paper's RoPElite settings r = 4, 8, 16 at hardware-friendly latent widths take
+    """elitekv_decode_path: the paper's RoPElite settings r = 4, 8, 16, 32 at hardware-friendly latent widths take
     the matrix-core kernels; fp32, other r, other widths and r = 16 with rows too wide for the LDS take the
-    generic ones -- visibly, not silently."""
+    generic ones -- visibly, not silently (r = 32: up to d_c 1152)."""
     mk = lambda r, d_c, dt="bf16", n_h=32, d_h=128: ekv.make_dims(4096, n_h, d_h, r, d_c, dt)
     MC, GEN = ekv.PATH_MATRIX_CORE, ekv.PATH_GENERIC
     assert ekv.elitekv_decode_path(mk(8, 1536)) == MC
@@ -360,7 +360,10 @@ def test_decode_path_query_names_the_kernels_a_shape_runs():
     assert ekv.elitekv_decode_path(mk(16, 1024)) == MC
     assert ekv.elitekv_decode_path(mk(8, 1920, n_h=40)) == MC
     assert ekv.elitekv_decode_path(mk(16, 2048)) == GEN         # tiles + 32 elite values per head exceed the LDS
-    assert ekv.elitekv_decode_path(mk(32, 2048)) == GEN         # r = 32 (50 % cache)
+    assert ekv.elitekv_decode_path(mk(32, 1024)) == MC          # r = 32: 37.5 % of the full cache
+    assert ekv.elitekv_decode_path(mk(32, 1152)) == MC
+    assert ekv.elitekv_decode_path(mk(32, 2048)) == GEN         # r = 32 at 50 % cache: tiles + 64 elite values per head exceed the LDS
+    assert ekv.elitekv_decode_path(mk(32, 1280)) == GEN
     assert ekv.elitekv_decode_path(mk(8, 1500)) == GEN
     assert ekv.elitekv_decode_path(mk(8, 1536, "fp32")) == GEN
     assert ekv.elitekv_decode_path(mk(8, 1536), 576) == MC      # separated latents, whole wave slices

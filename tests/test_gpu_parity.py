@@ -46,6 +46,9 @@ APPEND_CASES = {
     "bf16_r16_one_token": (shape(4096, 32, 128, 16, 1792, "bf16"), 1, 32767),
     "bf16_r16_batch_16": (shape(4096, 32, 128, 16, 1792, "bf16"), 16, 4095),
     "bf16_r16_300_tokens": (shape(4096, 32, 128, 16, 1792, "bf16"), 300, 8191),
+    "bf16_r32_one_token": (shape(4096, 32, 128, 32, 1024, "bf16"), 1, 32767),
+    "bf16_r32_batch_16": (shape(4096, 32, 128, 32, 1152, "bf16"), 16, 4095),
+    "bf16_r32_300_tokens": (shape(4096, 32, 128, 32, 1024, "bf16"), 300, 8191),
 }
 
 
@@ -129,7 +132,14 @@ DECODE_CASES["bf16_r16_latent_1792"] = (shape(64, 32, 128, 16, 1792, "bf16"), [3
 DECODE_CASES["bf16_r16_latent_1024_batch_9"] = (shape(64, 32, 128, 16, 1024, "bf16"),
                                                 [0, 1, 15, 16, 17, 250, 33, 48, 100], [0, 3])
 DECODE_CASES["bf16_r16_latent_1536_40_heads"] = (shape(64, 40, 128, 16, 1536, "bf16"), [97, 160], [0, 2])
+DECODE_CASES["bf16_r16_latent_896_one_wave_per_simd"] = (shape(64, 32, 128, 16, 896, "bf16"), [150, 33, 16], [0, 3])
 DECODE_CASES["bf16_r16_small_heads"] = (shape(64, 8, 64, 16, 256, "bf16"), [70, 33], [0, 2])
+# r = 32 elite chunks per head (Table 2's largest RoPElite setting; 37.5 % of the full cache at the 7B shape with d_c 1024)
+DECODE_CASES["bf16_r32_latent_1024"] = (shape(64, 32, 128, 32, 1024, "bf16"), [300, 1, 257, 16], [0, 1, 4])
+DECODE_CASES["bf16_r32_latent_1152_batch_9"] = (shape(64, 32, 128, 32, 1152, "bf16"),
+                                                [0, 1, 15, 16, 17, 250, 33, 48, 100], [0, 3])
+DECODE_CASES["bf16_r32_latent_768_40_heads"] = (shape(64, 40, 128, 32, 768, "bf16"), [97, 160], [0, 2])
+DECODE_CASES["bf16_r32_eight_heads"] = (shape(64, 8, 128, 32, 256, "bf16"), [70, 33], [0, 2])
 DECODE_CASES["bf16_latent_2048_40_heads"] = (shape(64, 40, 128, 8, 2048, "bf16"), [97, 160], [0, 2])
 DECODE_CASES["bf16_latent_1024_batch_9"] = (shape(64, 32, 128, 8, 1024, "bf16"), [0, 1, 15, 16, 17, 250, 33, 48, 100],
                                             [0, 3])

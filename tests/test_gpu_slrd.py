@@ -95,6 +95,9 @@ DECODE_CASES = {
     "bf16_7b_12pct_384_384": (shape(64, 32, 128, 4, 384, 384, "bf16"), [130, 64], [0, 3]),
     "bf16_small_heads_64_192": (shape(64, 8, 64, 4, 64, 192, "bf16"), [70, 33], [0, 2]),
     "bf16_13b_960_960": (shape(64, 40, 128, 8, 960, 960, "bf16"), [97, 40], [0, 2]),      # generic kernels
+    "bf16_448_448_one_wave_per_simd": (shape(64, 32, 128, 8, 448, 448, "bf16"), [150, 33], [0, 2]),   # 224-column wave slices
+    "bf16_r16_448_448": (shape(64, 32, 128, 16, 448, 448, "bf16"), [150, 33], [0, 2]),    # generic kernels (32 elite values beside 224-column slices)
+    "bf16_r32_512_512": (shape(64, 32, 128, 32, 512, 512, "bf16"), [97, 16], [0, 2]),     # generic kernels (64 elite values per head)
 }
 
 

@@ -40,6 +40,8 @@ STEP_CASES = {
     "bf16_r16_one_sequence": (shape(4096, 32, 128, 16, 1792, "bf16"), [301]),                 # 2r = 32 elite values per head
     "bf16_r16_three_sequences": (shape(4096, 32, 128, 16, 1024, "bf16"), [1, 64, 97]),
     "bf16_r16_twelve_sequences": (shape(4096, 32, 128, 16, 1792, "bf16"), [7 + 13 * i for i in range(12)]),
+    "bf16_r32_one_sequence": (shape(4096, 32, 128, 32, 1024, "bf16"), [301]),                 # 2r = 64 elite values per head
+    "bf16_r32_twelve_sequences": (shape(4096, 32, 128, 32, 1152, "bf16"), [7 + 13 * i for i in range(12)]),
     "fp32_tiny_three_sequences": (synth.CONFIGS["tiny_fp32"].as_dict(), [129, 5, 60]),
 }
 
