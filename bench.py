@@ -313,6 +313,7 @@ def main():
         result["prefill_attn"] = prefill_attn(ekv, ev, cfg, dims, planes, W_uk_d, W_uv_d, idx_d, dev, dt, stream,
                                               T=args.prefill_tokens)
         result["ropelite_search"] = ropelite_search(ekv, ev, cfg, dev, stream)
+        result["ropelite_search"]["at_2048_tokens"] = ropelite_search(ekv, ev, cfg, dev, stream, T=2048, iters=2)
         result["append_prefill"] = append_prefill(ekv, ev, cfg, dims, W_ke_d, W_dkv_d, W_dkv2_d, idx_d, dev, dt, stream,
                                                   T=args.prefill_tokens)
         # the step against the roofline with everything it has to read once (cache + the four weight
@@ -519,7 +520,10 @@ def ropelite_search(ekv, ev, cfg, dev, stream, T=512, iters=3):
     evals = T * (T + 1) / 2 * n_h * r * (d_h // 2)      # (causal pair, chunk) evaluations over all rounds
     # Algorithm 1 per round, causal pair and chunk: the rotated and the plain 2-D dot product, their scaled
     # difference (8 flops), its share of the residual (1), and |residual - difference| added to the chunk's
-    # distance (3): 12 fp32 vector flops, no contraction with a shared operand -- bounded by the vector ALUs
+    # distance (3): 12 fp32 flops.  The kernel takes the two dot products of a 16 x 16 tile of pairs as one
+    # rank-4 fp32 MFMA per chunk (twice per round: once summed into the residual, once per candidate), the rest is
+    # vector work; fp32 matrix and fp32 vector peak are the same 157.3 TFLOP/s on this chip, so the bound is
+    # priced as "alu" against it
     tf = 12.0 * evals / (ms * 1e-3) / 1e12
     return {"tokens": T, "rounds": r, "ms_per_layer": round(ms, 4), "G_pair_chunk_evals_per_s": round(evals / ms / 1e6, 1),
             "bound": "alu", "flops_per_pair_chunk_round": 12, "TFLOPs": round(tf, 2), "peak_TFLOPs": FP32_VALU_PEAK_TFLOPS,

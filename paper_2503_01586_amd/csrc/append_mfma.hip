@@ -538,7 +538,7 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
     const int64_t wgs128 = col_blocks * ((a.T + 127) / 128);
     if (wgs128 >= 256 && wgs128 <= 384) return launch_gemm_dma<1, 6, 4, 2, 2>(a, stream);
     if (wgs128 >= 256) return launch_gemm_dma<2, 4, 2, 2>(a, stream);
-    return launch_gemm_dma<1, 6, 2, 2, 2>(a, stream);
+    return launch_gemm_dma<1, 6, 2, 2>(a, stream);
   }
   if (col_blocks * ((a.T + 255) / 256) >= 1024) return launch_gemm_wn<4>(a, stream);
   return launch_gemm_wn<1>(a, stream);
