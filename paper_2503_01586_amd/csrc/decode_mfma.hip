@@ -780,9 +780,12 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
 #define X(DC, NWV, DCW)                                                                                \
   if (d.d_c == DC) {                                                                                   \
     if constexpr (DCW <= 256) {                                                                        \
-      if (sep) e = two_r == 32 ? launch_attn<NWV, DCW, 32, true>(prm, a.B, stream)                     \
-                 : two_r == 16 ? launch_attn<NWV, DCW, 16, true>(prm, a.B, stream)                     \
-                               : launch_attn<NWV, DCW, 8, true>(prm, a.B, stream);                     \
+      if (sep && two_r == 32) {                                                                        \
+        if constexpr (DCW != 224) e = launch_attn<NWV, DCW, 32, true>(prm, a.B, stream);               \
+      } else if (sep) {                                                                                \
+        e = two_r == 16 ? launch_attn<NWV, DCW, 16, true>(prm, a.B, stream)                            \
+                        : launch_attn<NWV, DCW, 8, true>(prm, a.B, stream);                            \
+      }                                                                                                \
     }                                                                                                  \
     if (!sep) e = two_r == 64 ? launch_attn<NWV, DCW, 64, false>(prm, a.B, stream)                     \
                   : two_r == 32 ? launch_attn<NWV, DCW, 32, false>(prm, a.B, stream)                   \
