@@ -303,7 +303,12 @@ struct GemmDmaLayout {
 // SPB = stages consumed per barrier (1 or 2).  With 2 the work-group synchronises once per 64 contraction rows:
 // half as many barriers and load waits, the operands of the second stage of a pair read while the first is
 // multiplied, NS - 2 stages in flight behind the pair.
-template <int WN, int NS, int WNW, int CM, int SPB>
+// KG = groups of waves that split the contraction rows of every stage between them (1 or 2).  With 2 (eight waves on
+// a 128 x 128 tile) the waves of a group own 64 x 64 outputs each instead of 64 x 32 and take one of the two 16-row
+// k-steps of every stage: a wave then reads 4 KB instead of 6 KB of operands from LDS per four MFMAs (the LDS, not the
+// matrix cores, is the busiest unit of this tile: 48 KB read + 16 KB written per stage against 128 B per cycle), and the
+// two groups add their halves through LDS once, before the epilogue.
+template <int WN, int NS, int WNW, int CM, int SPB, int KG>
 __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
     const bf16_t* __restrict__ x, const int32_t* __restrict__ pos, const int64_t* __restrict__ slot, int64_t T,
     const bf16_t* __restrict__ W_ke, const bf16_t* __restrict__ W_dkv, const bf16_t* __restrict__ W_dkv2, int d_ck,
@@ -312,7 +317,12 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
   using L = GemmDmaLayout<WN, NS, WNW, CM>;
   extern __shared__ __attribute__((aligned(16))) char gsm[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave % CM, wn = wave / CM;
+  static_assert(KG == 1 || (KG == 2 && WN == 1 && WNW == 4 && CM == 2), "contraction groups: eight waves on 128 x 128");
+  constexpr int WNC = KG * WN;                     // 32-token tiles a wave accumulates
+  constexpr int KSN = 2 / KG;                      // k-steps of a stage a wave multiplies
+  const int kg = KG == 2 ? wave >> 2 : 0;          // contraction group of this wave
+  const int wv = KG == 2 ? wave & 3 : wave;        // wave inside its group
+  const int wm = wv % CM, wn = wv / CM;
   const int n32 = lane & 31, hi = lane >> 5, i16 = lane & 15, q16 = lane >> 4;
   const int NE = 2 * r * n_h;
   // Work-groups go to the eight XCDs round-robin by linear index.  All column blocks of one token
@@ -363,11 +373,11 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
     issue_slot = (issue_slot + 1 == NS) ? 0 : issue_slot + 1;
   };
 
-  am_f32x16 acc[2][WN];
+  am_f32x16 acc[2][WNC];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < WN; ++j) acc[i][j] = (am_f32x16)(0.f);
+    for (int j = 0; j < WNC; ++j) acc[i][j] = (am_f32x16)(0.f);
 
   // ---- operand read offsets inside a stage
   // weights, transposed read: k rows 8*(q16/2) + 4e + i16/4 of a k-step (block kb = 2*ks + q16/2 ...)
@@ -385,9 +395,10 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     const int row = n32 & 15;
-    b_off[ks] = L::A_BYTES + (wn * WN * 2 + (n32 >> 4)) * 1024 + row * 64 + (((2 * ks + hi) ^ gd_swz4(row)) << 4);
+    b_off[ks] = L::A_BYTES + (wn * WNC * 2 + (n32 >> 4)) * 1024 + row * 64 + (((2 * ks + hi) ^ gd_swz4(row)) << 4);
   }
 
+  const int b_off_g = kg ? b_off[1] : b_off[0];   // contraction groups: the group's k-step
   // wait until this wave's direct loads have landed except those of the `ahead` most recent stages
   auto wait_loads = [&](int ahead) {
     switch (ahead) {
@@ -400,33 +411,34 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
   };
   // operands of one stage in registers: both 16-row k-steps
   struct StageOps {
-    am_bf16x8 a[2][2];           // [ks][32-column tile]
-    am_bf16x8 b[2][WN];          // [ks][32-token tile]
+    am_bf16x8 a[KSN][2];         // [k-step][32-column tile]
+    am_bf16x8 b[KSN][WNC];       // [k-step][32-token tile]
   };
   int read_slot = 0;             // ring slot of the next stage to be read into registers; stages are read in order
   auto read_ops = [&](StageOps& o) {
     const char* st = gsm + read_slot * L::STAGE;
     read_slot = (read_slot + 1 == NS) ? 0 : read_slot + 1;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int kq = 0; kq < KSN; ++kq) {
+      const int ks = KG == 2 ? kg : kq;            // the group's k-step of the stage
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         // a k-step is two 8-row weight blocks per 64-column block: 2 * CM KiB
         const am_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 2048 * CM + a_off[i][0]));
         const am_s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((am_lds_s16x4_t*)(st + ks * 2048 * CM + a_off[i][1]));
-        o.a[ks][i] = __builtin_bit_cast(am_bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+        o.a[kq][i] = __builtin_bit_cast(am_bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
       }
 #pragma unroll
-      for (int j = 0; j < WN; ++j) o.b[ks][j] = *reinterpret_cast<const am_bf16x8*>(st + b_off[ks] + j * 2048);
+      for (int j = 0; j < WNC; ++j) o.b[kq][j] = *reinterpret_cast<const am_bf16x8*>(st + (KG == 2 ? b_off_g : b_off[kq]) + j * 2048);
     }
   };
   auto multiply = [&](const StageOps& o) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int ks = 0; ks < KSN; ++ks)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < WN; ++j)
+        for (int j = 0; j < WNC; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[ks][i], o.b[ks][j], acc[i][j], 0, 0, 0);
   };
 
@@ -466,8 +478,41 @@ __global__ __launch_bounds__(64 * CM * WNW) void append_gemm_dma_kernel(
     }
   }
 
-  gemm_epilogue<WN>(acc, n0, t0, wm, wn, n32, hi, T, pos, slot, elite_idx, ke_plane, c_plane, plane_rows, n_h, d_h,
-                    r, d_c, rope);
+  if constexpr (KG == 2) {
+    // The two groups hold sums over different contraction rows of the same 64 x 64 outputs.  Group g finishes the
+    // g-th 32-token tile: every wave leaves the tile it does not finish in LDS (the ring is free now), adds what its
+    // partner of the other group left for it, and runs the epilogue on 64 columns x 32 tokens.
+    static_assert(8 * 2 * 16 * 64 * 4 <= L::LDS_BYTES, "the exchange reuses the ring");
+    __syncthreads();
+    float* xb = reinterpret_cast<float*>(gsm);
+    auto put = [&](int writer, const am_f32x16 (&t)[2]) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xb[((writer * 2 + i) * 16 + v) * 64 + lane] = t[i][v];
+    };
+    am_f32x16 fin[2][1];
+    if (kg == 0) {
+      const am_f32x16 other[2] = {acc[0][1], acc[1][1]};
+      put(wv * 2 + 0, other);
+      fin[0][0] = acc[0][0]; fin[1][0] = acc[1][0];
+    } else {
+      const am_f32x16 other[2] = {acc[0][0], acc[1][0]};
+      put(wv * 2 + 1, other);
+      fin[0][0] = acc[0][1]; fin[1][0] = acc[1][1];
+    }
+    __syncthreads();
+    const int partner = wv * 2 + (1 - kg);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) fin[i][0][v] += xb[((partner * 2 + i) * 16 + v) * 64 + lane];
+    gemm_epilogue<1>(fin, n0, t0, wm, wn * 2 + kg, n32, hi, T, pos, slot, elite_idx, ke_plane, c_plane, plane_rows, n_h,
+                     d_h, r, d_c, rope);
+  } else {
+    gemm_epilogue<WN>(acc, n0, t0, wm, wn, n32, hi, T, pos, slot, elite_idx, ke_plane, c_plane, plane_rows, n_h, d_h,
+                      r, d_c, rope);
+  }
 }
 
 bool append_gemm_supported(const elitekv_dims& d, int64_t T, int d_ck) {
@@ -493,18 +538,18 @@ static hipError_t launch_gemm_wn(const AppendArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <int WN, int NS, int WNW, int CM, int SPB = 1>
+template <int WN, int NS, int WNW, int CM, int SPB = 1, int KG = 1>
 static hipError_t launch_gemm_dma(const AppendArgs& a, hipStream_t stream) {
   using L = GemmDmaLayout<WN, NS, WNW, CM>;
   const elitekv_dims& d = a.dims;
   const int N = 2 * d.r * d.n_heads + d.d_c;
   static LdsLimit lds_limit;
-  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW, CM, SPB>),
+  const hipError_t le = raise_lds_limit(lds_limit, reinterpret_cast<const void*>(&append_gemm_dma_kernel<WN, NS, WNW, CM, SPB, KG>),
                                         L::LDS_BYTES);
   if (le != hipSuccess) return le;
   const int64_t tblocks = (a.T + L::BN - 1) / L::BN;
   const dim3 grid((unsigned)((tblocks + 7) / 8 * 8 * (N / L::COLS)));   // token blocks padded to whole rounds of 8 XCDs
-  append_gemm_dma_kernel<WN, NS, WNW, CM, SPB><<<grid, 64 * CM * WNW, L::LDS_BYTES, stream>>>(
+  append_gemm_dma_kernel<WN, NS, WNW, CM, SPB, KG><<<grid, 64 * CM * WNW, L::LDS_BYTES, stream>>>(
       (const bf16_t*)a.x, a.pos, a.slot, a.T, (const bf16_t*)a.W_ke, (const bf16_t*)a.W_dkv,
       (const bf16_t*)a.W_dkv2, a.d_ck, a.elite_idx, (bf16_t*)a.ke_plane, (bf16_t*)a.c_plane, a.plane_rows,
       d.d_model, d.n_heads, d.head_dim, d.r, d.d_c, rope_table(d.rope_base, d.head_dim),
@@ -534,9 +579,9 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
     if (col_blocks * ((a.T + 255) / 256) >= 512) return launch_gemm_dma<2, 6, 4, 2>(a, stream);
     // 128 x 128 tiles: with about one work-group per compute unit eight waves (two per SIMD, 32 tokens x 64
     // columns each) hide a little more of the stage latency than four (595 against 549 TFLOP/s at 2048 tokens
-    // x 2048 columns); with more rounds the four-wave form and its larger share of the tile per wave is kept
+    // x 2048 columns; two ring stages per barrier: 626; the waves as two contraction groups: 688); with more rounds the four-wave form and its larger share of the tile per wave is kept
     const int64_t wgs128 = col_blocks * ((a.T + 127) / 128);
-    if (wgs128 >= 256 && wgs128 <= 384) return launch_gemm_dma<1, 6, 4, 2, 2>(a, stream);
+        if (wgs128 >= 256 && wgs128 <= 384) return launch_gemm_dma<1, 6, 4, 2, 2, 2>(a, stream);
     if (wgs128 >= 256) return launch_gemm_dma<2, 4, 2, 2>(a, stream);
     return launch_gemm_dma<1, 6, 2, 2>(a, stream);
   }
