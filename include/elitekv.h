@@ -336,13 +336,12 @@ int elitekv_slrd_prefill_attn(const elitekv_dims* dims, int32_t d_ck, const void
  *   stores it but out[b] is unspecified: depending on the shape the new token is attended to from
  *   its fresh row or from whatever row seq_len[b] - 1 of the plane holds.  seq_len[b] <= 0:
  *   nothing is attended, out[b] is 0, and the token is still stored at slot[b] if that is in range.
- *   For fewer than eight sequences (bf16 shapes of the matrix-core path) the step is four launches:
- *   the first pass of the append together with the query preparation; the attention, in which the
- *   work-group that owns the tile of a sequence's newest position first adds up the append's partial
- *   sums, rotates and stores the new row; the merge with the up-projection (and the final reduction).  With 8 to
- *   64 sequences the first pass of the append and the query preparation share a launch as well
- *   (five launches instead of six).  Other shapes run the two entry points' kernels one after
- *   the other.
+ *   For up to 64 sequences (bf16 shapes of the matrix-core path) the step is three launches (four
+ *   from eight sequences on): the first pass of the append together with the query preparation; the
+ *   attention, in which the work-group that owns the tile of a sequence's newest position first adds
+ *   up the append's partial sums, rotates and stores the new row; the merge with the up-projection
+ *   (from two sequences on followed by the launch that adds its column-chunk partials).  Other shapes
+ *   run the two entry points' kernels one after the other.
  *   All other arguments, layouts, ownership and errors as in elitekv_append and
  *   elitekv_decode_attn.  ws: elitekv_decode_step_workspace_bytes bytes (EWORKSPACE if smaller).
  * ------------------------------------------------------------------------------------------- */

@@ -222,8 +222,19 @@ __global__ __launch_bounds__(256) void decode_front_mfma_kernel(const AppendSkin
 
 bool decode_front_mfma_supported(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p) {
   const elitekv_dims& d = a.dims;
-  if (!p.mfma || p.fresh || ap.T != a.B) return false;
+  if (!p.mfma || p.fresh == 1 || ap.T != a.B) return false;
   return qprep_mfma_supported(d, p.d_q, a.B) && append_skinny_supported(d, ap.T, ap.d_ck);
+}
+
+// Fused step for 8 to 64 sequences: the contraction splits and the rows of a split that the batched front launch
+// leaves for the attention kernel's owner work-groups (no finishing launch).
+bool decode_front_mfma_plan(const elitekv_dims& d, int d_ck, int d_q, int64_t B, int* ks_out, int* kc_out) {
+  if (!qprep_mfma_supported(d, d_q, B) || !append_skinny_supported(d, B, d_ck > 0 ? d_ck : d.d_c)) return false;
+  int ks = append_skinny_ksplit(d);
+  const int kc = append_skinny_kc(d, ks);
+  ks = (d.d_model + kc - 1) / kc;
+  *ks_out = ks; *kc_out = kc;
+  return true;
 }
 
 template <int KS>
@@ -233,7 +244,7 @@ static hipError_t launch_front_mfma_ks(const AppendArgs& ap, const DecodeArgs& a
   int ks = append_skinny_ksplit(d);
   const int kc = append_skinny_kc(d, ks);
   ks = (d.d_model + kc - 1) / kc;            // splits that still have rows; never more than planned
-  float* partial = (float*)ap.ws;
+  float* partial = p.fresh == 2 ? (float*)(a.ws + p.off_apart) : (float*)ap.ws;
   const size_t sm_q = qprep_mfma_lds(d.head_dim, d.r);
   const size_t sm = sm_q > (size_t)kSkLds ? sm_q : (size_t)kSkLds;
   const int q_blocks = p.d_q / 128, n_qprep = q_blocks * d.n_heads, n_blocks = N / kSkCols;
@@ -244,7 +255,7 @@ static hipError_t launch_front_mfma_ks(const AppendArgs& ap, const DecodeArgs& a
   if (ap.T <= 32) decode_front_mfma_kernel<KS, 1><<<grid, 256, sm, stream>>>(A, Q, rope, n_qprep, q_blocks, n_blocks);
   else decode_front_mfma_kernel<KS, 2><<<grid, 256, sm, stream>>>(A, Q, rope, n_qprep, q_blocks, n_blocks);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || p.fresh == 2) return e;            // fused step: the attention launch finishes the new rows
   return launch_append_finish(ap, partial, ks, stream);
 }
 

@@ -81,6 +81,9 @@ static int plan_decode(const elitekv_dims* d, int32_t d_ck, int64_t B, int64_t m
     if (want_fresh && B > 0 && decode_front_plan(*d, d_ck, p->d_q, B, &ks, &kc)) {
       p->fresh = 1; p->fr_ks = ks; p->fr_kc = kc;
       p->fr_stride = 2 * d->r * d->n_heads + d->d_c;
+    } else if (want_fresh && !block && B > 0 && decode_front_mfma_plan(*d, d_ck, p->d_q, B, &ks, &kc)) {
+      p->fresh = 2; p->fr_ks = ks; p->fr_kc = kc;
+      p->fr_stride = 2 * d->r * d->n_heads + d->d_c;
     }
     if (block) {
       int yks = 0, ykc = 0;
@@ -400,10 +403,10 @@ static int step_impl(const elitekv_dims* dims, int32_t d_ck, const void* x, cons
                              ke_plane, c_plane, plane_rows, out, ws, 7, 1);
   hipError_t e;
   if (p.fresh) {
-    // front kernel (first pass of the append + query preparation), then attention (whose new-token
+    // front kernel (first pass of the append + query preparation), then attention (whose owner
     // work-groups finish the append), merge and up-projection
     a.fr_slot = slot; a.fr_ke_out = ke_plane; a.fr_c_out = c_plane;
-    e = launch_decode_front(ap, a, p, stream);
+    e = p.fresh == 2 ? launch_decode_front_mfma(ap, a, p, stream) : launch_decode_front(ap, a, p, stream);
     a.stages = 6;
     if (e == hipSuccess) e = launch_decode_mfma(a, p, stream);
   } else if (decode_front_mfma_supported(ap, a, p)) {

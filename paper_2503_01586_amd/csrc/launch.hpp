@@ -47,9 +47,10 @@ struct DecodePlan {
   size_t off_u;         // split latent accumulators        fp32 [B, n_splits, ...]
   size_t off_opart;     // up-projection partials           fp32
   size_t off_cnt;       // MFMA path: arrival counters of the merge kernels' chunk groups   int32 [B, n_h]
-  // fused decode step (fresh = 1): the cache row of the newest token of every sequence is finished (summed,
+  // fused decode step (fresh != 0): the cache row of the newest token of every sequence is finished (summed,
   // rotated, stored) inside the attention kernel, by the work-group whose tiles include its position,
-  // from the append's contraction-split sums
+  // from the append's contraction-split sums.  1: fewer than eight sequences (weight-streaming front launch),
+  // 2: eight to 64 sequences (matrix-core front launch)
   int32_t fresh;
   int32_t n_part;       // partials per batch row (= n_splits)
   int32_t fr_ks;        // contraction splits of the step's append
@@ -158,6 +159,7 @@ hipError_t launch_block_front(const AppendArgs& ap, const void* W_q, const Decod
 hipError_t launch_oproj(const DecodeArgs& a, const DecodePlan& p, const void* W_o, void* y, hipStream_t stream);
 // ... for batches of eight rows and up (matrix-core roles; includes the append's finishing launch)
 bool decode_front_mfma_supported(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p);
+bool decode_front_mfma_plan(const elitekv_dims& d, int d_ck, int d_q, int64_t B, int* ks, int* kc);
 hipError_t launch_decode_front_mfma(const AppendArgs& ap, const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);
 bool merge_mfma_supported(const elitekv_dims& d, int d_u, int64_t B, int64_t n_splits);
 hipError_t launch_merge_mfma(const DecodeArgs& a, const DecodePlan& p, hipStream_t stream);

@@ -25,7 +25,8 @@ constexpr int kQmRows = 64;     // batch rows staged in LDS per pass
 inline size_t qprep_mfma_lds(int head_dim, int r) { return (size_t)kQmRows * (head_dim - 2 * r + 8) * 2 + 64 * sizeof(int); }
 
 // bx = block of 128 latent columns, by = head; qms = qprep_mfma_lds(...) bytes of 16-byte aligned LDS;
-// KS = contraction steps of 16 non-elite dims (the tail is zero-filled).  P.sincos is not written here.
+// KS = contraction steps of 16 non-elite dims (the tail is zero-filled).  P.sincos (optional) is written by the
+// work-groups that rotate the elite query.
 template <int KS>
 __device__ __forceinline__ void qprep_mfma_body(const QprepRowsParams& P, const RopeTable& rope, int bx, int by,
                                                 char* qms) {
@@ -90,6 +91,7 @@ __device__ __forceinline__ void qprep_mfma_body(const QprepRowsParams& P, const 
         float* o = qe + ((int64_t)b * n_h + h) * 2 * r;
         o[2 * j] = (u * cs - v * sn) * scale_log2e;
         o[2 * j + 1] = (u * sn + v * cs) * scale_log2e;
+        if (P.sincos) P.sincos[((int64_t)b * n_h + h) * r + j] = make_float2(sn, cs);
       }
     }
     __syncthreads();
