@@ -140,7 +140,11 @@ size_t elitekv_decode_workspace_bytes(const elitekv_dims* dims, int64_t B, int64
  *   seq_len    [B] int32            cached rows each batch row attends to; values above
  *                                   max_seq_len, or reaching past plane_rows, are clamped
  *                                   on the device; seq_len[b] == 0 gives a zero output row
- *   max_seq_len                     HOST upper bound on seq_len[] (plans the split)
+ *   max_seq_len                     HOST upper bound on seq_len[] (plans the split).  Of every batch row
+ *                                   the first min(max_seq_len, rows left in the planes) rows may be READ
+ *                                   whatever seq_len[b] says (a kernel requests its first rows before
+ *                                   seq_len[b] has arrived); rows at or beyond seq_len[b] never reach a
+ *                                   result, whatever they hold
  *   batch_stride_rows               plane rows between consecutive batch rows' first row
  *   W_uk       [d_c, n_h, d_h-2r]   dims->dtype
  *   W_uv       [d_c, n_h, d_h]      dims->dtype

@@ -178,6 +178,35 @@ def test_decode_matches_oracle_on_same_planes(name):
         assert orc.max_abs_rel(o, outs[0]) <= TOL[dt]
 
 
+@pytest.mark.parametrize("name", ["bf16_7b", "bf16_13b_ragged_batch", "bf16_7b_12pct", "bf16_r32_latent_1024", "fp32_ragged_batch"])
+def test_rows_beyond_a_sequence_never_reach_the_result(name):
+    """max_seq_len is only a host-side bound: the kernels may read a sequence's rows up to it before seq_len[b] has
+    arrived on the device (the split attention kernel requests its first tile at once).  Whatever those rows hold
+    must not matter: the planes beyond every seq_len[b] are filled with NaN, max_seq_len is the whole stride, and
+    the result has to be finite and equal to the oracle's, with few and with many splits."""
+    sh, seqs, _ = DECODE_CASES[name]
+    dt = sh["dtype"]
+    B, stride = len(seqs), max(seqs) + 40
+    rng, idx, W_ke, W_dkv, W_uk, W_uv, x, q = _draw(sh, B * stride, B, 900 + len(name))
+    dims = dims_of(sh)
+    pos = np.tile(np.arange(stride), B)
+    ke64, c64 = orc.append(x, pos, W_ke, W_dkv, idx, sh["head_dim"], sh["rope_base"])
+    ked, cd = dev(ke64, dt), dev(c64, dt)
+    qd, Wukd, Wuvd = dev(q, dt), dev(W_uk, dt), dev(W_uv, dt)
+    q_pos = np.array([max(s - 1, 0) for s in seqs])
+    ref = orc.decode_attn(host64(qd), q_pos, host64(ked).reshape(B, stride, sh["n_heads"], -1),
+                          host64(cd).reshape(B, stride, -1), seqs, host64(Wukd), host64(Wuvd), idx,
+                          sh["head_dim"], sh["rope_base"])
+    for b, s in enumerate(seqs):                      # poison what no query may see
+        ked[b * stride + s:(b + 1) * stride] = float("nan")
+        cd[b * stride + s:(b + 1) * stride] = float("nan")
+    for ns in (0, 1, 7):
+        out = host64(gpu_decode(dims, qd, i32(q_pos), i32(seqs), stride, stride, Wukd, Wuvd, i32(idx), ked, cd,
+                                n_splits=ns))
+        assert np.all(np.isfinite(out)), "n_splits=%d" % ns
+        assert orc.max_abs_rel(out, ref) <= TOL[dt], "n_splits=%d" % ns
+
+
 @pytest.mark.parametrize("d_c,n_heads", [(1536, 32), (768, 32), (1920, 40)])
 def test_decode_with_scores_that_keep_rising(d_c, n_heads):
     """The running maximum of the online softmax has to be raised many times along the sequence:
