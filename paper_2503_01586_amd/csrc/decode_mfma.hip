@@ -45,7 +45,7 @@ struct AttnMfmaParams {
   float* part_l;          // [B, n_splits, HG*32]        split sums
   bf16_t* part_u;         // [B, n_splits, HG*32, d_c]   split latent accumulators, head-major
   int n_h, d_c, n_splits, chunk, head_groups;
-  int batch, pair_map;    // pair_map: 1-D grid, the two head groups of an item share an XCD
+  int batch, pair_map;    // pair_map: 1-D grid, the two head groups of an item share an XCD (2: one head group, every batch row on one XCD)
   int q_per_seq;          // query rows per sequence (several queries share the cache rows of a sequence)
   int d_q, d_u;           // widths of the absorbed query and of the latent accumulators (d_c when joint)
   int q_slice;            // column slice per wave (DC_W), as the query preparation laid qt out
@@ -237,18 +237,34 @@ __global__ __launch_bounds__(NW * 64, (AttnMfmaLayout<NW, DC_W, TWO_R>::kGroupsP
   const bool do_v = !SEP || cw >= nwk;                   // this wave's slice is accumulated as values
   const int vwave = SEP ? cw - nwk : cw;                 // position of the slice among the value slices
   int split = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
-  if (p.pair_map) {
+  if (p.pair_map == 2) {
+    // One head group, a multiple of eight batch rows: all splits of batch row b run on XCD b % 8 (work-groups go to
+    // the XCDs round-robin by linear index), so an XCD's L2 fetches the absorbed queries of its own rows only
+    // instead of every row's (at 64 rows that is 3 MB per XCD, which the streamed cache rows keep evicting:
+    // 294 MB fetched per launch against 268 MB of cache).
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    b = (slot / p.n_splits) * 8 + xcd;
+    split = slot % p.n_splits;
+    if (b >= p.batch) return;
+  } else if (p.pair_map) {
     // Two head groups read the same latent rows.  Work-groups go to the eight XCDs round-robin by
     // linear index, so indices i and i + 8 land on the same XCD back to back: they are given the
     // two head groups of one (split, batch row) item, and the second reader of a row finds it in
     // that XCD's L2 instead of fetching it from HBM again.
+    // (3: a multiple of eight batch rows, and every row's splits on XCD b % 8 as above)
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int item = (slot >> 1) * 8 + xcd;
     const int per_row = p.n_splits;
-    if (item >= per_row * p.batch) return;
     hg = slot & 1;
-    split = item % per_row;
-    b = item / per_row;
+    if (p.pair_map == 3) {
+      b = ((slot >> 1) / per_row) * 8 + xcd;
+      split = (slot >> 1) % per_row;
+      if (b >= p.batch) return;
+    } else {
+      const int item = (slot >> 1) * 8 + xcd;
+      if (item >= per_row * p.batch) return;
+      split = item % per_row;
+      b = item / per_row;
+    }
   }
   if (split == 0 && hg == 0)
     for (int i = tid; i < p.n_h; i += NW * 64) p.chunk_counters[(int64_t)b * p.n_h + i] = 0;
@@ -522,7 +538,7 @@ __global__ __launch_bounds__(NW * 64, (AttnMfmaLayout<NW, DC_W, TWO_R>::kGroupsP
   char* ctile1 = ctile0 + L::TILE_BYTES;
   char* ketile1 = KE2 ? ketile0 + L::KE_BYTES : ketile0;
   // The second work-group of a head-group pair swaps neighbouring tiles (see tile_at below).
-  const int swp = (p.pair_map && hg) ? 1 : 0;
+  const int swp = ((p.pair_map & 1) && hg) ? 1 : 0;
 
   // ---- start-up.  seq_len[b] takes a trip to memory (about 1.5 us after a launch); the first tile does not wait
   // for it.  Its rows are requested at once, on the assumption that the tile lies wholly inside the sequence:
@@ -664,7 +680,9 @@ static hipError_t launch_attn_as(const AttnMfmaParams& prm, int64_t B, hipStream
       lds_limit, reinterpret_cast<const void*>(&attn_mfma_kernel<NW, DC_W, TWO_R, SEP, SMODE>), L::LDS_BYTES);
   if (le != hipSuccess) return le;
   const int per_row = prm.n_splits;
-  const dim3 grid = prm.pair_map ? dim3((unsigned)((per_row * B + 7) / 8 * 16), 1, 1)
+  const dim3 grid = prm.pair_map == 2 ? dim3((unsigned)((B + 7) / 8 * 8 * per_row), 1, 1)
+                  : prm.pair_map == 3 ? dim3((unsigned)((B + 7) / 8 * 16 * per_row), 1, 1)
+                  : prm.pair_map ? dim3((unsigned)((per_row * B + 7) / 8 * 16), 1, 1)
                                  : dim3(per_row, prm.head_groups, (unsigned)B);
   attn_mfma_kernel<NW, DC_W, TWO_R, SEP, SMODE><<<grid, NW * 64, L::LDS_BYTES, stream>>>(prm);
   return hipGetLastError();
@@ -674,7 +692,7 @@ template <int NW, int DC_W, int TWO_R, bool SEP>
 static hipError_t launch_attn(const AttnMfmaParams& prm, int64_t B, hipStream_t stream) {
   if constexpr (AttnMfmaLayout<NW, DC_W, TWO_R>::kFits) {
     // head-group pairs share their rows through the L2; every other launch reads a row once
-    return prm.pair_map ? launch_attn_as<NW, DC_W, TWO_R, SEP, 2>(prm, B, stream)
+    return (prm.pair_map & 1) ? launch_attn_as<NW, DC_W, TWO_R, SEP, 2>(prm, B, stream)
                         : launch_attn_as<NW, DC_W, TWO_R, SEP, 1>(prm, B, stream);
   } else {
     return hipErrorInvalidValue;                            // decode_mfma_supported() keeps such shapes away
@@ -757,7 +775,9 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.n_h = d.n_heads; prm.d_c = d.d_c; prm.n_splits = p.n_splits; prm.chunk = p.chunk;
   prm.head_groups = p.head_groups; prm.max_seq_len = a.max_seq_len;
   prm.batch_stride_rows = a.batch_stride_rows; prm.plane_rows = a.plane_rows;
-  prm.batch = (int)a.B; prm.pair_map = p.head_groups == 2 ? 1 : 0;
+  prm.batch = (int)a.B;
+  const bool rows_to_xcds = a.B >= 8 && a.B % 8 == 0 && a.q_per_seq == 1;
+  prm.pair_map = p.head_groups == 2 ? (rows_to_xcds ? 3 : 1) : rows_to_xcds ? 2 : 0;
   prm.d_q = p.d_q; prm.d_u = p.d_u; prm.q_per_seq = a.q_per_seq; prm.q_slice = slice_width(d.d_c);
   prm.n_part = p.n_part; prm.fresh = p.fresh;
   prm.fr_partial = nullptr; prm.fr_sincos = nullptr; prm.fr_slot = nullptr; prm.fr_ks = 0; prm.fr_stride = 0;
