@@ -162,10 +162,9 @@ constexpr float kRescaleSlack = 8.f;
 // cache type and stored at slot[b].  Run by the work-group(s) that own the tile the token lies in,
 // before they request anything from the planes: the tile loads then bring the row in like any other.
 template <int NT, int TWO_R>
-__device__ __forceinline__ void store_new_token_row(const AttnMfmaParams& p, int b) {
+__device__ __forceinline__ void store_new_token_row(const AttnMfmaParams& p, int b, int64_t slot) {
   const int tid = threadIdx.x;
   const int NE = p.n_h * TWO_R, N = NE + p.d_c;
-  const int64_t slot = p.fr_slot[b];
   if (slot < 0 || slot >= p.plane_rows) return;            // a token without a row is not stored
   for (int pr = tid; pr < N / 2; pr += NT) {
     const int n = 2 * pr;
@@ -291,6 +290,11 @@ __global__ __launch_bounds__(NW * 64, (AttnMfmaLayout<NW, DC_W, TWO_R>::kGroupsP
   f32x4 qv[TWO_R > 0 ? TWO_R / 4 : 1];
   int32_t len_raw;                                       // seq_len[b] through the scalar cache: not behind the vector loads
   asm volatile("s_load_dword %0, %1, 0x0" : "=s"(len_raw) : "s"(p.seq_len + __builtin_amdgcn_readfirstlane(b)) : "memory");
+  // fr_slot[b] (fused step: the row of the newest token) in the same trip: fetched by the owner work-group where it
+  // finishes that row, it would be one more trip to memory (about 1.5 us) ahead of the split sums' loads.  Outside
+  // a fused step the host points fr_slot at readable workspace bytes and the value is not used.
+  int64_t slot_raw;
+  asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(slot_raw) : "s"(p.fr_slot + __builtin_amdgcn_readfirstlane(b)) : "memory");
   auto load_query = [&]() {
     {
       // every wave loads a slice, also the waves of a separated latent that only accumulate values (they read slice 0
@@ -554,7 +558,7 @@ __global__ __launch_bounds__(NW * 64, (AttnMfmaLayout<NW, DC_W, TWO_R>::kGroupsP
     issue_ke(spec_t, ketile0, NtEven{});
   }
   if (!p.fresh) load_query();
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(len_raw) : : "memory");
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(len_raw), "+s"(slot_raw) : : "memory");
   {
     int64_t len = len_raw;
     len = min(len, t_cap);
@@ -571,7 +575,7 @@ __global__ __launch_bounds__(NW * 64, (AttnMfmaLayout<NW, DC_W, TWO_R>::kGroupsP
     // This comes before the query loads: nothing may touch their registers until they have landed.
     const bool own = t_end > 0 ? split == (int)(((t_end - 1) / kTile) % p.n_splits) : (split == 0 && hg == 0);
     if (own) {
-      store_new_token_row<NW * 64, TWO_R>(p, b);
+      store_new_token_row<NW * 64, TWO_R>(p, b, slot_raw);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     load_query();
@@ -780,7 +784,9 @@ hipError_t launch_decode_mfma(const DecodeArgs& a, const DecodePlan& p, hipStrea
   prm.pair_map = p.head_groups == 2 ? (rows_to_xcds ? 3 : 1) : rows_to_xcds ? 2 : 0;
   prm.d_q = p.d_q; prm.d_u = p.d_u; prm.q_per_seq = a.q_per_seq; prm.q_slice = slice_width(d.d_c);
   prm.n_part = p.n_part; prm.fresh = p.fresh;
-  prm.fr_partial = nullptr; prm.fr_sincos = nullptr; prm.fr_slot = nullptr; prm.fr_ks = 0; prm.fr_stride = 0;
+  // fr_slot is read (through the scalar cache) by every work-group of every launch; outside a fused step it points
+  // at the first bytes of the workspace (the elite queries: at least 32 bytes per batch row) and the value is ignored
+  prm.fr_partial = nullptr; prm.fr_sincos = nullptr; prm.fr_slot = (const int64_t*)(a.ws + p.off_qe); prm.fr_ks = 0; prm.fr_stride = 0;
   prm.fr_ke_out = nullptr; prm.fr_c_out = nullptr;
   prm.chunk_counters = (int*)(a.ws + p.off_cnt);
   if (p.fresh) {

@@ -147,6 +147,56 @@ def test_step_with_a_sequence_that_attends_to_nothing(B):
     assert orc.max_abs_rel(o[1:], ref) <= TOL["bf16"]
 
 
+# (shape, cached tokens per sequence including the new one, sequence splits): splits of several tiles, so the owner
+# work-group of a new row stores it while its earlier tiles stream and requests the row's tile last
+LONG_SPLIT_CASES = {
+    "bf16_7b_one_sequence_two_splits": (shape(4096, 32, 128, 8, 1536, "bf16"), [301], 2),
+    "bf16_7b_one_sequence_one_split": (shape(4096, 32, 128, 8, 1536, "bf16"), [130], 1),
+    "bf16_7b_three_tiles_exactly": (shape(4096, 32, 128, 8, 1536, "bf16"), [48], 1),
+    "bf16_7b_three_sequences_three_splits": (shape(4096, 32, 128, 8, 1536, "bf16"), [100, 250, 49], 3),
+    "bf16_7b_nine_sequences_two_splits": (shape(4096, 32, 128, 8, 1536, "bf16"), [300, 17, 64, 129, 255, 33, 97, 48, 200], 2),
+    "bf16_7b_12pct_sixteen_sequences": (shape(4096, 32, 128, 4, 768, "bf16"), [40 + 13 * i for i in range(16)], 2),
+    "bf16_13b_one_sequence_two_splits": (shape(5120, 40, 128, 8, 1920, "bf16"), [200], 2),
+    "bf16_13b_eight_sequences_one_split": (shape(5120, 40, 128, 8, 1920, "bf16"), [50 + 21 * i for i in range(8)], 1),
+}
+
+
+@pytest.mark.parametrize("name", list(LONG_SPLIT_CASES))
+def test_step_reads_back_the_rows_it_stores_in_long_splits(name):
+    """The slots of the new rows hold NaN before the step: an attention tile that was requested before the step's
+    own row had reached it would carry the NaN into the output."""
+    sh, seqs, n_splits = LONG_SPLIT_CASES[name]
+    dt, n_h, d_h = sh["dtype"], sh["n_heads"], sh["head_dim"]
+    B, stride = len(seqs), max(seqs) + 2
+    rng, idx, W_ke, W_dkv, W_uk, W_uv, x, q = _draw(sh, B, B, 900 + len(name))
+    dims = dims_of(sh)
+    ke, c = _planes(rng, B, stride, n_h, sh["r"], sh["d_c"], dt)
+    pos = np.array(seqs) - 1
+    slot = np.arange(B) * stride + pos
+    ke[i64(slot)] = float("nan")
+    c[i64(slot)] = float("nan")
+    xd, qd, Wked, Wdkvd, Wukd, Wuvd = (dev(a, dt) for a in (x, q, W_ke, W_dkv, W_uk, W_uv))
+    out = torch.full((B, n_h, d_h), float("nan"), dtype=ekv.torch_dtype(dims), device=DEV)
+    ws = torch.full((ekv.elitekv_decode_step_workspace_bytes(dims, B, max(seqs), n_splits),), 0xFF, dtype=torch.uint8,
+                    device=DEV)
+    for rep in range(3):                                  # the second and third step find warm caches: other timing
+        if rep:
+            ke[i64(slot)] = float("nan")
+            c[i64(slot)] = float("nan")
+        ekv.elitekv_decode_step(dims, xd, qd, i32(pos), i64(slot), i32(seqs), max(seqs), stride, Wked, Wdkvd, Wukd, Wuvd,
+                                i32(idx), ke, c, out, ws, n_splits=n_splits)
+        torch.cuda.synchronize()
+        ke_g, c_g = host64(ke).reshape(B * stride, n_h, -1), host64(c)
+        ke_ref, c_ref = orc.append(host64(xd), pos, host64(Wked), host64(Wdkvd), idx, d_h, sh["rope_base"])
+        assert orc.max_abs_rel(c_g[slot], c_ref) <= TOL[dt]
+        assert orc.max_abs_rel(ke_g[slot], ke_ref) <= TOL[dt]
+        ref = orc.decode_attn(host64(qd), pos, ke_g.reshape(B, stride, n_h, -1), c_g.reshape(B, stride, -1), seqs,
+                              host64(Wukd), host64(Wuvd), idx, d_h, sh["rope_base"])
+        o = host64(out)
+        assert np.all(np.isfinite(o)), "step %d: NaN from a new row's slot reached the output" % rep
+        assert orc.max_abs_rel(o, ref) <= TOL[dt]
+
+
 def test_step_argument_errors():
     sh = shape(4096, 32, 128, 8, 1536, "bf16")
     dims = dims_of(sh)
