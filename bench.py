@@ -8,6 +8,10 @@ in HBM before the timed region.  The timed steps cycle over several distinct cop
 cache planes (>= 1 GiB in total) and of the weights (>= 512 MB in total: a model's next layer brings its
 own) so that the 256 MB Infinity Cache cannot serve the reads.
 
+Order of a run: the oracle's timing on the host and the companion measurements (streaming ceiling,
+uncompressed attention, several queries, whole block, prefill-sized calls, search) first, then the
+headline region: W untimed warm-up steps, a synchronisation, exactly K timed steps, a synchronisation.
+
 Prints one JSON line.
 """
 from __future__ import annotations
