@@ -581,7 +581,7 @@ hipError_t launch_append_gemm(const AppendArgs& a, hipStream_t stream) {
     // columns each) hide a little more of the stage latency than four (595 against 549 TFLOP/s at 2048 tokens
     // x 2048 columns; two ring stages per barrier: 626; the waves as two contraction groups: 688); with more rounds the four-wave form and its larger share of the tile per wave is kept
     const int64_t wgs128 = col_blocks * ((a.T + 127) / 128);
-        if (wgs128 >= 256 && wgs128 <= 384) return launch_gemm_dma<1, 6, 4, 2, 2, 2>(a, stream);
+    if (wgs128 >= 256 && wgs128 <= 384) return launch_gemm_dma<1, 6, 4, 2, 2, 2>(a, stream);
     if (wgs128 >= 256) return launch_gemm_dma<2, 4, 2, 2>(a, stream);
     return launch_gemm_dma<1, 6, 2, 2>(a, stream);
   }
